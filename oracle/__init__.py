@@ -1,0 +1,193 @@
+"""CPU oracle (test infrastructure only).
+
+Thin ctypes loader for ``tg_oracle.c``: exact brute-force k-NN (O-BF) and the
+two-phase NN-Descent of Algorithm 1 (O-NND), both single-threaded and in
+double precision.  Nothing in the product path may import this package; it is
+for ``tests/``, the smoke check and the benchmark's CPU-baseline leg.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tg_oracle.c")
+_LIB = os.path.join(_HERE, "libtg_oracle.so")
+
+METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, no HIP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        i64, i32, u64, dbl, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p
+        L.oracle_mix64.restype = u64
+        L.oracle_mix64.argtypes = [u64]
+        L.oracle_hash3.restype = u64
+        L.oracle_hash3.argtypes = [u64, u64, u64, u64]
+        L.oracle_distance.restype = dbl
+        L.oracle_distance.argtypes = [vp, i64, i32, i64, i64]
+        L.obf_knn.restype = i32
+        L.obf_knn.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp]
+        L.onnd_create.restype = vp
+        L.onnd_create.argtypes = [vp, i64, i64, i32, i32] + [i32] * 10 + [u64]
+        L.onnd_destroy.argtypes = [vp]
+        L.onnd_export.argtypes = [vp, vp, vp, vp]
+        L.onnd_counters.argtypes = [vp, vp]
+        L.onnd_import.argtypes = [vp, vp, vp, vp]
+        L.onnd_init.argtypes = [vp]
+        L.onnd_phase1_sample.argtypes = [vp]
+        L.onnd_block.argtypes = [vp, i64, vp, vp]
+        L.oracle_merge_list.restype = i64
+        L.oracle_merge_list.argtypes = [i32, i64, vp, vp, vp, vp, vp, i64]
+        L.onnd_phase1_round.restype = i64
+        L.onnd_phase1_round.argtypes = [vp]
+        L.onnd_begin_phase2.argtypes = [vp]
+        L.onnd_phase2_round.restype = i64
+        L.onnd_phase2_round.argtypes = [vp]
+        L.onnd_run.argtypes = [vp, i32, i32, dbl, vp]
+        L.oracle_recall.restype = dbl
+        L.oracle_recall.argtypes = [vp, vp, i64, i32]
+        _lib = L
+    return _lib
+
+
+def _f32(X):
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    assert X.ndim == 2
+    return X
+
+
+def mix64(z: int) -> int:
+    return lib().oracle_mix64(z & (2**64 - 1))
+
+
+def hash3(seed: int, tag: int, x: int, y: int) -> int:
+    return lib().oracle_hash3(seed, tag, x, y)
+
+
+def distance(X, metric: int, a: int, b: int) -> float:
+    X = _f32(X)
+    return lib().oracle_distance(X.ctypes.data, X.shape[1], metric, a, b)
+
+
+def brute_force_knn(X, k: int, metric: int = METRIC_L2, rows=None):
+    """O-BF: exact k-NN of the given rows (all rows if None) under (dist, id) order."""
+    X = _f32(X)
+    n, d = X.shape
+    if rows is None:
+        rows_arr, nq, rp = None, n, None
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        nq, rp = len(rows_arr), rows_arr.ctypes.data
+    ids = np.empty((nq, k), dtype=np.int32)
+    dist = np.empty((nq, k), dtype=np.float64)
+    rc = lib().obf_knn(X.ctypes.data, n, d, k, metric, rp, nq, ids.ctypes.data, dist.ctypes.data)
+    if rc != 0:
+        raise ValueError("obf_knn: invalid arguments")
+    return ids, dist
+
+
+def recall(ids, truth) -> float:
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    truth = np.ascontiguousarray(truth, dtype=np.int32)
+    assert ids.shape == truth.shape
+    return lib().oracle_recall(ids.ctypes.data, truth.ctypes.data, ids.shape[0], ids.shape[1])
+
+
+def merge_list(self_id, ids, dist, fresh, cand_ids, cand_dist):
+    """The neighbour-list update rule on explicit arrays; returns (ids, dist, fresh, inserted)."""
+    ids = np.array(ids, dtype=np.int32)
+    dist = np.array(dist, dtype=np.float64)
+    fresh = np.array(fresh, dtype=np.uint8)
+    cid = np.ascontiguousarray(cand_ids, dtype=np.int32)
+    cd = np.ascontiguousarray(cand_dist, dtype=np.float64)
+    ins = lib().oracle_merge_list(len(ids), self_id, ids.ctypes.data, dist.ctypes.data, fresh.ctypes.data,
+                                  cid.ctypes.data, cd.ctypes.data, len(cid))
+    return ids, dist, fresh, ins
+
+
+class NNDescent:
+    """O-NND: one object per build; methods are the steps of Algorithm 1."""
+
+    def __init__(self, X, k, metric=METRIC_L2, S=None, R=None, C=64, retain=1, tile=16,
+                 ng_row=2, ng_col=2, m=2, all_block=False, use_threshold=True, seed=1):
+        self.X = _f32(X)
+        self.n, self.d = self.X.shape
+        self.k = k
+        S = min(k, 32) if S is None else S
+        R = 32 if R is None else R
+        self.S, self.R = S, R
+        self._h = lib().onnd_create(self.X.ctypes.data, self.n, self.d, k, metric, S, R, C,
+                                    retain, tile, ng_row, ng_col, m, int(all_block),
+                                    int(use_threshold), seed)
+        if not self._h:
+            raise ValueError("onnd_create: invalid arguments")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().onnd_destroy(self._h)
+            self._h = None
+
+    def init(self):
+        lib().onnd_init(self._h)
+
+    def phase1_sample(self):
+        """Draw this round's forward and reverse samples without running the round."""
+        lib().onnd_phase1_sample(self._h)
+
+    def block(self, v: int):
+        """(NEW ids, OLD ids) of anchor v for the samples last drawn."""
+        blk = np.empty(2 * self.S + 2 * self.R, dtype=np.int32)
+        sizes = (ctypes.c_int * 2)()
+        lib().onnd_block(self._h, v, blk.ctypes.data, sizes)
+        return blk[:sizes[0]].copy(), blk[sizes[0]:sizes[0] + sizes[1]].copy()
+
+    def phase1_round(self) -> int:
+        return lib().onnd_phase1_round(self._h)
+
+    def begin_phase2(self):
+        lib().onnd_begin_phase2(self._h)
+
+    def phase2_round(self) -> int:
+        return lib().onnd_phase2_round(self._h)
+
+    def run(self, it1, it2, delta=0.0):
+        done = (ctypes.c_int * 2)()
+        lib().onnd_run(self._h, it1, it2, delta, done)
+        return done[0], done[1]
+
+    def set_graph(self, ids, dist, fresh):
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        dist = np.ascontiguousarray(dist, dtype=np.float64)
+        fresh = np.ascontiguousarray(fresh, dtype=np.uint8)
+        assert ids.shape == dist.shape == fresh.shape == (self.n, self.k)
+        lib().onnd_import(self._h, ids.ctypes.data, dist.ctypes.data, fresh.ctypes.data)
+
+    def counters(self):
+        c = (ctypes.c_int64 * 3)()
+        lib().onnd_counters(self._h, c)
+        return {"pairs": c[0], "offered": c[1], "updates": c[2]}
+
+    def graph(self):
+        ids = np.empty((self.n, self.k), dtype=np.int32)
+        dist = np.empty((self.n, self.k), dtype=np.float64)
+        fresh = np.empty((self.n, self.k), dtype=np.uint8)
+        lib().onnd_export(self._h, ids.ctypes.data, dist.ctypes.data, fresh.ctypes.data)
+        return ids, dist, fresh
