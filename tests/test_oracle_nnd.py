@@ -306,11 +306,12 @@ def test_early_stop():
     assert o2.run(3, 2, delta=0.0) == (3, 2)
 
 
-def test_join_pair_count_is_new_new_plus_new_old():
+@pytest.mark.parametrize("retain", [0, 1])
+def test_join_pair_count_is_new_new_plus_new_old(retain):
     # 3.1.1 step (2): distances between new-new and new-old pairs, never old-old
     X = inputs.make("C1", n=300, d=8)
     k = 10
-    o = oracle.NNDescent(X, k, S=k, R=5, C=32, seed=6)
+    o = oracle.NNDescent(X, k, S=k, R=5, C=32, retain=retain, seed=6)
     o.init()
     o.phase1_round()
     o.phase1_round()
