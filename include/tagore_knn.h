@@ -1,0 +1,170 @@
+/*
+ * tagore_knn.h — C boundary of the MI355X (gfx950) GNN-Descent k-NN graph builder.
+ *
+ * The library builds an approximate k-nearest-neighbour graph with the two-phase
+ * GNN-Descent of the Tagore paper (section 4, Algorithm 1): random neighbour lists,
+ * then it1 rounds of shared-sample local joins (phase 1) and it2 rounds of per-node
+ * expansion of the closest unvisited neighbours (phase 2), each round followed by a
+ * lock-free per-list update (section 4.2).
+ *
+ * Conventions for every entry point
+ *   - Every pointer marked "device" is HIP device memory of the current device and is
+ *     owned by the caller; the library never frees or keeps it beyond the call, except
+ *     that a handle keeps X and its workspace until tg_knn_destroy.
+ *   - All device work is enqueued on the hipStream_t passed as `stream` (NULL = the
+ *     default stream).  Calls return after enqueueing unless stated otherwise.
+ *   - Return value: TG_OK or a negative tg_status.  Nothing is printed and no C++
+ *     exception crosses the boundary; tg_last_error() gives a message for the calling
+ *     thread's last failure.  On TG_ERR_INVALID_ARG outputs are untouched.
+ *   - Distances: TG_METRIC_L2 is the squared Euclidean distance, TG_METRIC_IP is
+ *     -<x,y>, TG_METRIC_COSINE is 1 - <x,y>/(|x||y|)  (the paper leaves "dis" open).
+ *   - Lists are ordered by (distance, id) ascending; a list never holds its own node
+ *     or the same id twice.
+ */
+#ifndef TAGORE_KNN_H
+#define TAGORE_KNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TG_OK = 0,
+    TG_ERR_INVALID_ARG = -1,
+    TG_ERR_UNSUPPORTED = -2,
+    TG_ERR_OUT_OF_MEMORY = -3,
+    TG_ERR_HIP = -4
+} tg_status;
+
+typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_metric;
+
+/*
+ * Parameters of Algorithm 1 and of the choices the paper leaves open.
+ *   k        list length (degree of the graph), 1 <= k <= 64, k < n
+ *   it1,it2  rounds of phase 1 / phase 2 (Algorithm 1 input; the paper sets it1 = it2)
+ *   S        forward sample cap per class (new / old) in phase 1, 1 <= S <= 32
+ *   R        reverse sample cap per class in phase 1, 0 <= R <= 32
+ *   C        candidate slots per node and round (section 4.2 "candidate list"),
+ *            a power of two, 16 <= C <= 128
+ *   ng_row   retention groups of row tiles  (2 or 4)  } section 4.2: per node one closest
+ *   ng_col   retention groups of column tiles (2,4,8) } candidate per sub-tile group
+ *   m        neighbours expanded per node and phase-2 round (the paper: m = 2), 1..4
+ *   delta    early stop: a phase ends when a round changes fewer than delta*n*k
+ *            entries; 0 = run exactly it1 + it2 rounds (never synchronises with the host)
+ *   seed     seed of every random decision (initial lists, reverse sampling, slots)
+ *   finalize 1: recompute the reported distances directly from the vectors and
+ *            re-sort each list before writing the outputs
+ */
+typedef struct tg_knn_params {
+    int32_t k;
+    int32_t metric;
+    int32_t it1, it2;
+    int32_t S, R, C;
+    int32_t ng_row, ng_col;
+    int32_t m;
+    float delta;
+    int32_t finalize;
+    uint64_t seed;
+} tg_knn_params;
+
+#define TG_MAX_ROUNDS 64
+
+/* What a build did; filled by tg_knn_build_ex / tg_knn_get_stats (host memory). */
+typedef struct tg_knn_stats {
+    int32_t rounds_phase1, rounds_phase2;
+    int64_t updates[TG_MAX_ROUNDS];      /* list entries replaced in round r (both phases, in order) */
+    float ms_norms, ms_init, ms_finalize;
+    float ms_sample[TG_MAX_ROUNDS];      /* reverse-sample build of round r (phase 1)               */
+    float ms_join[TG_MAX_ROUNDS];        /* local join (phase 1) or expand+update (phase 2)         */
+    float ms_update[TG_MAX_ROUNDS];      /* list update kernel (phase 1)                            */
+    double join_pairs[TG_MAX_ROUNDS];    /* pairs the join of round r had to evaluate               */
+    double join_vectors[TG_MAX_ROUNDS];  /* vectors the join of round r had to gather               */
+} tg_knn_stats;
+
+typedef struct tg_knn_handle tg_knn_handle;
+
+/* Defaults for a given k and total round budget: it1 = ceil(iters/2), it2 = iters - it1
+ * (section 7.3: it1 = it2), S = min(k,32), R = 32, C = 64, ng_row = 4, ng_col = 8, m = 2,
+ * delta = 0, finalize = 1, seed = 1.  iters <= 0 selects 16 rounds with delta = 0.001. */
+int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);
+
+/* Device bytes a build of this size needs as workspace. 0 if the arguments are invalid. */
+size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_params* p);
+
+/*
+ * The whole of Algorithm 1.  X: device, row-major n x d fp32.  out_ids: device, n x k
+ * int32.  out_dist: device, n x k fp32, may be NULL.  Allocates and frees its own
+ * workspace (synchronises the stream once at the end to do so).
+ * iters > 0: exactly it1 = ceil(iters/2) and it2 = iters - it1 rounds; iters <= 0: up to
+ * 16 rounds with early stop.  Valid iff 1 <= k <= 64, k < n < 2^30, 1 <= d <= 4096.
+ */
+int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, int32_t iters,
+                 uint64_t seed, int32_t* out_ids, float* out_dist, void* stream);
+
+/* As tg_knn_build with explicit parameters and a caller-provided device workspace of at
+ * least tg_knn_workspace_bytes() bytes (256-byte aligned).  stats may be NULL; when it is
+ * not, the call synchronises the stream before returning so that the timings are final. */
+int tg_knn_build_ex(const float* X, int64_t n, int32_t d, const tg_knn_params* p, void* workspace,
+                    size_t workspace_bytes, int32_t* out_ids, float* out_dist, tg_knn_stats* stats,
+                    void* stream);
+
+/* ---- Algorithm 1 step by step (what tg_knn_build_ex runs, one call per line) ---------- */
+
+/* Binds X, the parameters, a workspace and a stream.  X and workspace must stay valid
+ * until tg_knn_destroy.  The handle itself is host memory owned by the library. */
+int tg_knn_create(tg_knn_handle** h, const float* X, int64_t n, int32_t d, const tg_knn_params* p,
+                  void* workspace, size_t workspace_bytes, void* stream);
+int tg_knn_destroy(tg_knn_handle* h);
+
+/* Algorithm 1 lines 1-2: random lists, their distances, sorted, every entry "new". */
+int tg_knn_init(tg_knn_handle* h);
+/* Algorithm 1 lines 4-7: one phase-1 round (sample, local join, update).  updates: host,
+ * may be NULL; when given, the call waits for the round and stores the number of list
+ * entries it replaced. */
+int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates);
+/* Phase switch: every list entry becomes "unvisited". */
+int tg_knn_begin_phase2(tg_knn_handle* h);
+/* Algorithm 1 lines 9-12: one phase-2 round. */
+int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates);
+/* Writes the graph: with finalize = 1 distances are recomputed directly and rows re-sorted. */
+int tg_knn_finalize(tg_knn_handle* h, int32_t* out_ids, float* out_dist);
+/* Stats of the rounds run so far on this handle (synchronises the stream). */
+int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out);
+
+/* ---- state inspection, for tests of the individual steps ------------------------------ */
+
+/* Current lists as they are (no finalize): ids n x k int32, dist n x k fp32, fresh n x k
+ * uint8 (1 = new / unvisited); all device, any may be NULL. */
+int tg_knn_export(tg_knn_handle* h, int32_t* ids, float* dist, uint8_t* fresh);
+/* Replace the lists (rows must be sorted by (dist,id), ids valid); all device. */
+int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* dist, const uint8_t* fresh);
+/* Step (1) of a phase-1 round on its own (section 3.1.1): draws the reverse samples of
+ * the coming round and writes every anchor's block: blk device n x 128 int32 (NEW ids
+ * first, then OLD ids), sizes device n x 2 int32 (|NEW|, |OLD|).  Does not advance the round. */
+int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* sizes);
+/* The local join's distance tile for explicit blocks, through the same LDS/MFMA core:
+ * blk device nb x 128 int32, sizes device nb x 2 (|NEW| <= 64, |NEW|+|OLD| <= 128),
+ * out device nb x 64 x 128 fp32; entry (b, r, c) is dist(blk[b][r], blk[b][c]) for
+ * r < |NEW|, r < c < |NEW|+|OLD|, and is left untouched elsewhere. */
+int tg_knn_join_distances(tg_knn_handle* h, const int32_t* blk, const int32_t* sizes, int64_t nb,
+                          float* out);
+
+/*
+ * Exact k-NN of selected rows by exhaustive search on the GPU (ground truth for the
+ * recall of section 7.1).  query_rows: device int64[nq] row indices into X (NULL = rows
+ * 0..nq-1); out_ids device nq x k, out_dist device nq x k (may be NULL).  Order (dist, id).
+ */
+int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric,
+                 const int64_t* query_rows, int64_t nq, int32_t* out_ids, float* out_dist,
+                 void* stream);
+
+/* Message of the calling thread's last error (static storage, never NULL). */
+const char* tg_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAGORE_KNN_H */

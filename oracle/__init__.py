@@ -141,8 +141,8 @@ class NNDescent:
             raise ValueError("onnd_create: invalid arguments")
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().onnd_destroy(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.onnd_destroy(self._h)
             self._h = None
 
     def init(self):

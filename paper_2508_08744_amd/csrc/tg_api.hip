@@ -1,0 +1,456 @@
+// The C boundary (include/tagore_knn.h): argument checks, workspace layout, and the round
+// loop of Algorithm 1.  Host code only; every device step is a launcher from tg_kernels.h.
+#include "../../include/tagore_knn.h"
+#include "tg_device.h"
+#include "tg_kernels.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+static thread_local char g_err[256] = "";
+
+static int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+extern "C" const char* tg_last_error(void) { return g_err; }
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(TG_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
+{
+    if (!p) return fail(TG_ERR_INVALID_ARG, "params is NULL");
+    if (p->k < 1 || p->k > 64) return fail(TG_ERR_INVALID_ARG, "k = %d outside 1..64", p->k);
+    if (n <= p->k) return fail(TG_ERR_INVALID_ARG, "need k < n (k = %d, n = %lld)", p->k, (long long)n);
+    if (n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "n = %lld must be below 2^30", (long long)n);
+    if (d < 1 || d > 4096) return fail(TG_ERR_INVALID_ARG, "d = %d outside 1..4096", d);
+    if (p->metric < 0 || p->metric > 2) return fail(TG_ERR_INVALID_ARG, "unknown metric %d", p->metric);
+    if (p->it1 < 0 || p->it2 < 0 || p->it1 + p->it2 > TG_MAX_ROUNDS)
+        return fail(TG_ERR_INVALID_ARG, "it1 = %d, it2 = %d: need 0 <= it1 + it2 <= %d", p->it1, p->it2, TG_MAX_ROUNDS);
+    if (p->S < 1 || p->S > 32) return fail(TG_ERR_INVALID_ARG, "S = %d outside 1..32", p->S);
+    if (p->R < 0 || p->R > 32) return fail(TG_ERR_INVALID_ARG, "R = %d outside 0..32", p->R);
+    if (p->C < 16 || p->C > 128 || (p->C & (p->C - 1))) return fail(TG_ERR_INVALID_ARG, "C = %d must be 16, 32, 64 or 128", p->C);
+    if (p->ng_row != 2 && p->ng_row != 4) return fail(TG_ERR_INVALID_ARG, "ng_row = %d must be 2 or 4", p->ng_row);
+    if (p->ng_col != 2 && p->ng_col != 4 && p->ng_col != 8) return fail(TG_ERR_INVALID_ARG, "ng_col = %d must be 2, 4 or 8", p->ng_col);
+    if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);
+    if (!(p->delta >= 0.0f && p->delta < 1.0f)) return fail(TG_ERR_INVALID_ARG, "delta must be in [0, 1)");
+    return TG_OK;
+}
+
+extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
+{
+    if (!p) return fail(TG_ERR_INVALID_ARG, "params is NULL");
+    memset(p, 0, sizeof(*p));
+    p->k = k;
+    p->metric = TG_METRIC_L2;
+    p->delta = 0.0f;
+    if (iters <= 0) { iters = 16; p->delta = 0.001f; }
+    p->it1 = (iters + 1) / 2;
+    p->it2 = iters - p->it1;
+    p->S = k < 32 ? (k < 1 ? 1 : k) : 32;
+    p->R = 32;
+    p->C = 64;
+    p->ng_row = 4;
+    p->ng_col = 8;
+    p->m = 2;
+    p->finalize = 1;
+    p->seed = 1;
+    return TG_OK;
+}
+
+// ---- workspace layout -----------------------------------------------------------------
+struct Carver {
+    char* base;
+    size_t used;
+    template <class T> T* take(size_t count)
+    {
+        used = (used + 255) & ~(size_t)255;
+        T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+        used += count * sizeof(T);
+        return p;
+    }
+};
+
+struct tg_knn_handle {
+    tg_knn_params p;
+    TgGraph g;
+    TgSample sm;
+    TgCand cd;
+    hipStream_t stream;
+    u64* d_updates;      // TG_MAX_ROUNDS counters
+    u64* d_stat_bins;    // TG_MAX_ROUNDS x 2 x TG_STAT_BINS
+    float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
+    int round;           // rounds run so far (both phases)
+    int rounds1, rounds2;
+    bool phase2;
+    bool norms_done;
+    // timing
+    std::vector<hipEvent_t> ev;
+    struct Span { int kind, round, e0, e1; };
+    std::vector<Span> spans;
+};
+enum { SPAN_NORMS, SPAN_INIT, SPAN_SAMPLE, SPAN_JOIN, SPAN_UPDATE, SPAN_FINALIZE };
+
+static int round_up4(int d) { return (d + 3) & ~3; }
+
+static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* ws, size_t* need)
+{
+    const tg_knn_params& p = h->p;
+    Carver c{reinterpret_cast<char*>(ws), 0};
+    const int ld = round_up4(d);
+    const bool pad = (ld != d) || ((reinterpret_cast<uintptr_t>(X) & 15) != 0);
+    h->x_padded = pad ? c.take<float>((size_t)n * ld) : nullptr;
+    h->g.n = n; h->g.d = d; h->g.ld = ld; h->g.k = p.k; h->g.metric = p.metric;
+    h->g.X = pad ? h->x_padded : X;
+    h->g.nrm = c.take<float>(n);
+    h->g.rnorm = c.take<float>(n);
+    h->g.gid = c.take<u32>((size_t)n * p.k);
+    h->g.gid_next = c.take<u32>((size_t)n * p.k);
+    h->g.gdist = c.take<float>((size_t)n * p.k);
+    h->g.kth = c.take<u64>(n);
+    h->sm.S = p.S; h->sm.R = p.R;
+    h->sm.deg = c.take<u32>(n);
+    h->sm.off = c.take<u64>(n + 1);
+    h->sm.csr = c.take<u32>((size_t)n * p.k);
+    h->sm.rev_new = c.take<u32>((size_t)n * (p.R ? p.R : 1));
+    h->sm.rev_old = c.take<u32>((size_t)n * (p.R ? p.R : 1));
+    h->sm.cnt_new = c.take<uint8_t>(n);
+    h->sm.cnt_old = c.take<uint8_t>(n);
+    h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(n));
+    h->cd.C = p.C;
+    h->cd.slots = c.take<u64>((size_t)n * p.C);
+    h->d_updates = c.take<u64>(TG_MAX_ROUNDS);
+    h->d_stat_bins = c.take<u64>((size_t)TG_MAX_ROUNDS * 2 * TG_STAT_BINS);
+    *need = (c.used + 255) & ~(size_t)255;
+}
+
+extern "C" size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_params* p)
+{
+    if (check_problem(n, d, p) != TG_OK) return 0;
+    tg_knn_handle tmp;
+    tmp.p = *p;
+    size_t need = 0;
+    // worst case: rows need an aligned, padded copy
+    carve(&tmp, reinterpret_cast<const float*>(4), n, d, nullptr, &need);
+    return need;
+}
+
+static int begin_span(tg_knn_handle* h, int kind, int round)
+{
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1;
+    h->ev.push_back(a);
+    h->ev.push_back(b);
+    h->spans.push_back({kind, round, (int)h->ev.size() - 2, (int)h->ev.size() - 1});
+    (void)hipEventRecord(a, h->stream);
+    return (int)h->spans.size() - 1;
+}
+static void end_span(tg_knn_handle* h, int span)
+{
+    if (span >= 0) (void)hipEventRecord(h->ev[h->spans[span].e1], h->stream);
+}
+
+extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int32_t d, const tg_knn_params* p,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!out) return fail(TG_ERR_INVALID_ARG, "handle pointer is NULL");
+    *out = nullptr;
+    int rc = check_problem(n, d, p);
+    if (rc != TG_OK) return rc;
+    if (!X) return fail(TG_ERR_INVALID_ARG, "X is NULL");
+    if (!workspace) return fail(TG_ERR_INVALID_ARG, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(TG_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    tg_knn_handle* h = new (std::nothrow) tg_knn_handle();
+    if (!h) return fail(TG_ERR_OUT_OF_MEMORY, "host allocation failed");
+    h->p = *p;
+    h->stream = reinterpret_cast<hipStream_t>(stream);
+    size_t need = 0;
+    carve(h, X, n, d, workspace, &need);
+    if (need > workspace_bytes) {
+        delete h;
+        return fail(TG_ERR_INVALID_ARG, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    }
+    h->round = h->rounds1 = h->rounds2 = 0;
+    h->phase2 = false;
+    h->norms_done = false;
+    if (h->x_padded) tg_launch_pad_rows(X, n, d, h->x_padded, h->g.ld, h->stream);
+    tg_launch_fill_u32(h->sm.deg, (size_t)n, 0u, h->stream);
+    tg_launch_fill_u64(h->cd.slots, (size_t)n * p->C, TG_EMPTY_KEY, h->stream);
+    tg_launch_fill_u64(h->d_updates, TG_MAX_ROUNDS, 0ull, h->stream);
+    tg_launch_fill_u64(h->d_stat_bins, (size_t)TG_MAX_ROUNDS * 2 * TG_STAT_BINS, 0ull, h->stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete h;
+        return fail(TG_ERR_HIP, "launch failed: %s", hipGetErrorString(e));
+    }
+    *out = h;
+    return TG_OK;
+}
+
+extern "C" int tg_knn_destroy(tg_knn_handle* h)
+{
+    if (!h) return TG_OK;
+    for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
+    delete h;
+    return TG_OK;
+}
+
+static int launch_status(const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(TG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return TG_OK;
+}
+
+static void ensure_norms(tg_knn_handle* h)
+{
+    if (h->norms_done) return;
+    int sp = begin_span(h, SPAN_NORMS, 0);
+    tg_launch_norms(h->g, h->stream);
+    end_span(h, sp);
+    h->norms_done = true;
+}
+
+extern "C" int tg_knn_init(tg_knn_handle* h)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    ensure_norms(h);
+    int sp = begin_span(h, SPAN_INIT, 0);
+    tg_launch_init(h->g, tg_hash_seed(h->p.seed, TG_TAG_INIT), h->stream);
+    end_span(h, sp);
+    h->round = h->rounds1 = h->rounds2 = 0;
+    h->phase2 = false;
+    return launch_status("init");
+}
+
+static int read_updates(tg_knn_handle* h, int round, int64_t* updates)
+{
+    u64 v = 0;
+    HIP_TRY(hipMemcpyAsync(&v, h->d_updates + round, sizeof(u64), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    *updates = (int64_t)v;
+    return TG_OK;
+}
+
+extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (h->phase2) return fail(TG_ERR_INVALID_ARG, "phase 1 round after the switch to phase 2");
+    if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
+    const int r = h->round;
+    int sp = begin_span(h, SPAN_SAMPLE, r);
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->stream);
+    end_span(h, sp);
+    sp = begin_span(h, SPAN_JOIN, r);
+    tg_launch_join(h->g, h->sm, h->cd, h->p.ng_row, h->p.ng_col, tg_hash_seed(h->p.seed, TG_TAG_SLOT(r)),
+                   h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
+    end_span(h, sp);
+    sp = begin_span(h, SPAN_UPDATE, r);
+    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + r, h->stream);
+    end_span(h, sp);
+    h->round++;
+    h->rounds1++;
+    int rc = launch_status("phase-1 round");
+    if (rc != TG_OK) return rc;
+    return updates ? read_updates(h, r, updates) : TG_OK;
+}
+
+extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    tg_launch_mark_all_fresh(h->g, h->stream);
+    h->phase2 = true;
+    return launch_status("phase switch");
+}
+
+extern "C" int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->phase2) return fail(TG_ERR_INVALID_ARG, "phase 2 round before tg_knn_begin_phase2");
+    if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
+    const int r = h->round;
+    int sp = begin_span(h, SPAN_JOIN, r);
+    tg_launch_phase2(h->g, h->p.m, h->d_updates + r, h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
+    end_span(h, sp);
+    u32* t = h->g.gid; h->g.gid = h->g.gid_next; h->g.gid_next = t;   // the written lists are current now
+    h->round++;
+    h->rounds2++;
+    int rc = launch_status("phase-2 round");
+    if (rc != TG_OK) return rc;
+    return updates ? read_updates(h, r, updates) : TG_OK;
+}
+
+extern "C" int tg_knn_finalize(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
+    int sp = begin_span(h, SPAN_FINALIZE, 0);
+    tg_launch_finalize(h->g, h->p.finalize, out_ids, out_dist, h->stream);
+    end_span(h, sp);
+    return launch_status("finalize");
+}
+
+extern "C" int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out)
+{
+    if (!h || !out) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    memset(out, 0, sizeof(*out));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    out->rounds_phase1 = h->rounds1;
+    out->rounds_phase2 = h->rounds2;
+    std::vector<u64> upd(TG_MAX_ROUNDS);
+    HIP_TRY(hipMemcpy(upd.data(), h->d_updates, TG_MAX_ROUNDS * sizeof(u64), hipMemcpyDeviceToHost));
+    for (int r = 0; r < TG_MAX_ROUNDS; ++r) out->updates[r] = (int64_t)upd[r];
+    if (h->round > 0) {
+        std::vector<u64> bins((size_t)h->round * 2 * TG_STAT_BINS);
+        HIP_TRY(hipMemcpy(bins.data(), h->d_stat_bins, bins.size() * sizeof(u64), hipMemcpyDeviceToHost));
+        for (int r = 0; r < h->round; ++r) {
+            double pairs = 0, vecs = 0;
+            for (int b = 0; b < TG_STAT_BINS; ++b) {
+                pairs += (double)bins[((size_t)r * 2) * TG_STAT_BINS + b];
+                vecs += (double)bins[((size_t)r * 2 + 1) * TG_STAT_BINS + b];
+            }
+            out->join_pairs[r] = pairs;
+            out->join_vectors[r] = vecs;
+        }
+    }
+    for (const auto& s : h->spans) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, h->ev[s.e0], h->ev[s.e1]) != hipSuccess) continue;
+        switch (s.kind) {
+        case SPAN_NORMS: out->ms_norms += ms; break;
+        case SPAN_INIT: out->ms_init += ms; break;
+        case SPAN_FINALIZE: out->ms_finalize += ms; break;
+        case SPAN_SAMPLE: out->ms_sample[s.round] += ms; break;
+        case SPAN_JOIN: out->ms_join[s.round] += ms; break;
+        case SPAN_UPDATE: out->ms_update[s.round] += ms; break;
+        }
+    }
+    return TG_OK;
+}
+
+extern "C" int tg_knn_export(tg_knn_handle* h, int32_t* ids, float* dist, uint8_t* fresh)
+{
+    if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    tg_launch_export(h->g, ids, dist, fresh, h->stream);
+    return launch_status("export");
+}
+
+extern "C" int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* dist, const uint8_t* fresh)
+{
+    if (!h || !ids || !dist || !fresh) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    ensure_norms(h);
+    tg_launch_import(h->g, ids, dist, fresh, h->stream);
+    return launch_status("import");
+}
+
+extern "C" int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* sizes)
+{
+    if (!h || !blk || !sizes) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->stream);
+    tg_launch_dump_blocks(h->g, h->sm, blk, sizes, h->stream);
+    return launch_status("sample");
+}
+
+extern "C" int tg_knn_join_distances(tg_knn_handle* h, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out)
+{
+    if (!h || !blk || !sizes || !out) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (nb < 0) return fail(TG_ERR_INVALID_ARG, "nb < 0");
+    if (nb == 0) return TG_OK;
+    // the blocks come from the caller: check them on the host side before any kernel trusts them
+    std::vector<int32_t> hs((size_t)nb * 2), hb((size_t)nb * TG_BLOCK_COLS);
+    HIP_TRY(hipMemcpyAsync(hs.data(), sizes, hs.size() * sizeof(int32_t), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipMemcpyAsync(hb.data(), blk, hb.size() * sizeof(int32_t), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    for (int64_t b = 0; b < nb; ++b) {
+        const int nN = hs[b * 2], nO = hs[b * 2 + 1];
+        if (nN < 0 || nO < 0 || nN > TG_BLOCK_ROWS || nN + nO > TG_BLOCK_COLS)
+            return fail(TG_ERR_INVALID_ARG, "block %lld: sizes (%d, %d) outside (<= 64, sum <= 128)", (long long)b, nN, nO);
+        for (int i = 0; i < nN + nO; ++i) {
+            const int32_t id = hb[b * TG_BLOCK_COLS + i];
+            if (id < 0 || id >= h->g.n) return fail(TG_ERR_INVALID_ARG, "block %lld: id %d out of range", (long long)b, id);
+        }
+    }
+    ensure_norms(h);
+    tg_launch_join_distances(h->g, blk, sizes, nb, out, h->stream);
+    return launch_status("join distances");
+}
+
+// ---- whole builds ---------------------------------------------------------------------
+static int run_all(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
+{
+    const tg_knn_params& p = h->p;
+    const double stop = (double)p.delta * (double)h->g.n * (double)p.k;
+    int rc = tg_knn_init(h);
+    if (rc != TG_OK) return rc;
+    for (int r = 0; r < p.it1; ++r) {
+        int64_t upd = 0;
+        rc = tg_knn_phase1_round(h, p.delta > 0.0f ? &upd : nullptr);
+        if (rc != TG_OK) return rc;
+        if (p.delta > 0.0f && (double)upd < stop) break;
+    }
+    rc = tg_knn_begin_phase2(h);
+    if (rc != TG_OK) return rc;
+    for (int r = 0; r < p.it2; ++r) {
+        int64_t upd = 0;
+        rc = tg_knn_phase2_round(h, p.delta > 0.0f ? &upd : nullptr);
+        if (rc != TG_OK) return rc;
+        if (p.delta > 0.0f && (double)upd < stop) break;
+    }
+    return tg_knn_finalize(h, out_ids, out_dist);
+}
+
+extern "C" int tg_knn_build_ex(const float* X, int64_t n, int32_t d, const tg_knn_params* p, void* workspace,
+                               size_t workspace_bytes, int32_t* out_ids, float* out_dist, tg_knn_stats* stats,
+                               void* stream)
+{
+    if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
+    tg_knn_handle* h = nullptr;
+    int rc = tg_knn_create(&h, X, n, d, p, workspace, workspace_bytes, stream);
+    if (rc != TG_OK) return rc;
+    rc = run_all(h, out_ids, out_dist);
+    if (rc == TG_OK && stats) rc = tg_knn_get_stats(h, stats);
+    tg_knn_destroy(h);
+    return rc;
+}
+
+extern "C" int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, int32_t iters,
+                            uint64_t seed, int32_t* out_ids, float* out_dist, void* stream)
+{
+    tg_knn_params p;
+    tg_knn_default_params(k, iters, &p);
+    p.metric = metric;
+    p.seed = seed;
+    int rc = check_problem(n, d, &p);
+    if (rc != TG_OK) return rc;
+    if (!X) return fail(TG_ERR_INVALID_ARG, "X is NULL");
+    if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
+    const size_t bytes = tg_knn_workspace_bytes(n, d, &p);
+    void* ws = nullptr;
+    if (hipMalloc(&ws, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(TG_ERR_OUT_OF_MEMORY, "workspace of %zu bytes could not be allocated", bytes);
+    }
+    rc = tg_knn_build_ex(X, n, d, &p, ws, bytes, out_ids, out_dist, nullptr, stream);
+    hipError_t e = hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream));
+    (void)hipFree(ws);
+    if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "build failed: %s", hipGetErrorString(e));
+    return rc;
+}
+
+extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, const int64_t* query_rows,
+                            int64_t nq, int32_t* out_ids, float* out_dist, void* stream)
+{
+    (void)X; (void)n; (void)d; (void)k; (void)metric; (void)query_rows; (void)nq; (void)out_ids; (void)out_dist; (void)stream;
+    return fail(TG_ERR_UNSUPPORTED, "tg_exact_knn is not built yet");
+}

@@ -1,0 +1,66 @@
+// Host-callable launchers of the gfx950 kernels (internal; the public boundary is
+// include/tagore_knn.h).  Every launcher only enqueues work on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define TG_BLOCK_COLS 128   // a join block holds at most 64 NEW rows and 128 rows in total
+#define TG_BLOCK_ROWS 64
+#define TG_STAT_BINS 1024   // spread of the per-round statistics counters
+
+struct TgGraph {
+    int64_t n;
+    int32_t d;        // logical dimension
+    int32_t ld;       // row stride of X in floats, multiple of 4, columns d..ld-1 are zero
+    int32_t k;
+    int32_t metric;
+    const float* X;
+    float* nrm;       // n: squared norms
+    float* rnorm;     // n: 1/|x| (cosine only, else unused)
+    uint32_t* gid;    // n x k list words of the current round: id | fresh << 31
+    uint32_t* gid_next; // n x k, written by a phase-2 round
+    float* gdist;     // n x k
+    unsigned long long* kth;   // n: key of each list's last entry with both low bits set
+};
+
+struct TgSample {
+    int32_t S, R;
+    uint32_t* deg;            // n, zero between rounds
+    unsigned long long* off;  // n + 1
+    uint32_t* csr;            // n x k: source | class << 31
+    uint32_t* rev_new;        // n x R
+    uint32_t* rev_old;        // n x R
+    uint8_t* cnt_new;         // n
+    uint8_t* cnt_old;         // n
+    unsigned long long* scan_tmp; // block sums of the prefix sum
+};
+
+struct TgCand {
+    int32_t C;
+    unsigned long long* slots;   // n x C keys, TG_EMPTY_KEY when free
+};
+
+void tg_launch_norms(const TgGraph& g, hipStream_t s);
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s);
+void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
+void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s);
+void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col,
+                    uint64_t hs_slot, unsigned long long* stat_bins /* 2 x TG_STAT_BINS or null */,
+                    hipStream_t s);
+void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, int32_t* sizes, hipStream_t s);
+void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb,
+                              float* out, hipStream_t s);
+void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, unsigned long long* updates,
+                      hipStream_t s);
+void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
+void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates,
+                      unsigned long long* stat_bins, hipStream_t s);
+void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s);
+void tg_launch_export(const TgGraph& g, int32_t* ids, float* dist, uint8_t* fresh, hipStream_t s);
+void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s);
+void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hipStream_t s);
+void tg_launch_exact_knn(const float* X, int ld, const float* nrm, const float* rnorm, int64_t n, int d, int k,
+                         int metric, const int64_t* rows, int64_t nq, int32_t* out_ids, float* out_dist,
+                         hipStream_t s);
+size_t tg_scan_tmp_elems(int64_t n);

@@ -1,0 +1,433 @@
+// Neighbour-list kernels: norms, random initial lists (Algorithm 1 lines 1-2), the
+// lock-free list update of section 4.2, the phase-2 expand-and-update round
+// (Algorithm 1 lines 9-12), finalize, and state export/import.
+//
+// Ownership rule that makes the update lock-free: exactly one wavefront reads and
+// rewrites a given list in a given kernel; other nodes reach a list only through its
+// candidate slots (atomic minimum) or through the previous round's snapshot.
+#include "tg_device.h"
+#include "tg_kernels.h"
+
+#define LISTS_WAVES 4   // wavefronts (= nodes) per workgroup
+
+// ---------------------------------------------------------------------------------------
+// small utilities
+// ---------------------------------------------------------------------------------------
+__global__ void fill_u64_kernel(u64* p, size_t count, u64 v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) p[i] = v;
+}
+__global__ void fill_u32_kernel(u32* p, size_t count, u32 v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) p[i] = v;
+}
+static int grid_for(size_t count, int block)
+{
+    size_t g = (count + block - 1) / block;
+    if (g > 65536) g = 65536;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+void tg_launch_fill_u64(u64* p, size_t count, u64 v, hipStream_t s)
+{
+    if (count) hipLaunchKernelGGL(fill_u64_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, p, count, v);
+}
+void tg_launch_fill_u32(u32* p, size_t count, u32 v, hipStream_t s)
+{
+    if (count) hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, p, count, v);
+}
+
+// rows of d floats -> rows of ld floats, zero padded
+__global__ void pad_rows_kernel(const float* __restrict__ X, int64_t n, int d, float* __restrict__ Xp, int ld)
+{
+    size_t total = (size_t)n * ld;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < total; i += stride) {
+        size_t r = i / ld;
+        int c = (int)(i - r * ld);
+        Xp[i] = c < d ? X[r * (size_t)d + c] : 0.0f;
+    }
+}
+void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hipStream_t s)
+{
+    hipLaunchKernelGGL(pad_rows_kernel, dim3(grid_for((size_t)n * ld, 256)), dim3(256), 0, s, X, n, d, Xp, ld);
+}
+
+// ---------------------------------------------------------------------------------------
+// squared norms: 16 lanes per row, float4 loads
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X, int64_t n, int ld,
+                                                    float* __restrict__ nrm, float* __restrict__ rnorm)
+{
+    int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    int sub = threadIdx.x & 15;
+    float acc = 0.0f;
+    if (row < n) {
+        const float* x = X + row * (int64_t)ld;
+        for (int c = sub * 4; c < ld; c += 64) {
+            float4 v = *reinterpret_cast<const float4*>(x + c);
+            acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    acc += __shfl_xor(acc, 8);
+    if (row < n && sub == 0) {
+        nrm[row] = acc;
+        if (rnorm) rnorm[row] = 1.0f / sqrtf(acc);
+    }
+}
+void tg_launch_norms(const TgGraph& g, hipStream_t s)
+{
+    int64_t blocks = (g.n + 15) / 16;
+    hipLaunchKernelGGL(norms_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g.X, g.n, g.ld, g.nrm,
+                       g.metric == 2 ? g.rnorm : (float*)nullptr);
+}
+
+// ---------------------------------------------------------------------------------------
+// Distances from node v (its vector staged in LDS at xs, ld floats) to one candidate id per
+// lane (cid < 0: none), computed directly from the vectors: sum (x-y)^2, -<x,y> or
+// 1 - <x,y>/(|x||y|).  16 lanes share one candidate row, so the wave works on 4 rows at a
+// time; candidates are compacted first so that only live rows are fetched.
+// wscr: 128 words of LDS private to this wave.
+// ---------------------------------------------------------------------------------------
+__device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, float rn_v, int cid, u32* wscr)
+{
+    const int lane = tg_lane();
+    const int grp = lane >> 4, sub = lane & 15;
+    const bool valid = cid >= 0;
+    const u64 mask = __ballot(valid);
+    const int nv = __popcll(mask);
+    const int pos = __popcll(mask & tg_lanemask_lt());
+    if (valid) wscr[pos] = (u32)cid;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    float* wd = reinterpret_cast<float*>(wscr + 64);
+    for (int p0 = 0; p0 < nv; p0 += 4) {
+        const int p = p0 + grp;
+        float acc = 0.0f;
+        int c = -1;
+        if (p < nv) {
+            c = (int)wscr[p];
+            const float* y = g.X + (int64_t)c * g.ld;
+            if (g.metric == 0) {
+                for (int col = sub * 4; col < g.ld; col += 64) {
+                    float4 a = *reinterpret_cast<const float4*>(xs + col);
+                    float4 b = *reinterpret_cast<const float4*>(y + col);
+                    float t0 = a.x - b.x, t1 = a.y - b.y, t2 = a.z - b.z, t3 = a.w - b.w;
+                    acc += t0 * t0 + t1 * t1 + t2 * t2 + t3 * t3;
+                }
+            } else {
+                for (int col = sub * 4; col < g.ld; col += 64) {
+                    float4 a = *reinterpret_cast<const float4*>(xs + col);
+                    float4 b = *reinterpret_cast<const float4*>(y + col);
+                    acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+                }
+            }
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        acc += __shfl_xor(acc, 4);
+        acc += __shfl_xor(acc, 8);
+        if (p < nv && sub == 0) {
+            float dist = acc;
+            if (g.metric == 1) dist = -acc;
+            else if (g.metric == 2) dist = 1.0f - acc * rn_v * g.rnorm[c];
+            wd[p] = dist;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    float out = valid ? wd[pos] : 0.0f;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return out;
+}
+
+// stage row v of X into this wave's LDS slice
+__device__ inline void stage_row(const TgGraph& g, int64_t v, float* xs)
+{
+    const float* x = g.X + v * (int64_t)g.ld;
+    for (int col = tg_lane() * 4; col < g.ld; col += 256)
+        *reinterpret_cast<float4*>(xs + col) = *reinterpret_cast<const float4*>(x + col);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ inline bool id_in_list(u32 id, u64 list_key, int k)
+{
+    // list_key: one list entry per lane (lanes < k); true if `id` equals any listed id
+    bool hit = false;
+    const u32 lid = tg_key_id(list_key);
+    for (int q = 0; q < k; ++q) hit |= (id == (u32)__builtin_amdgcn_readlane((int)lid, q));
+    return hit;
+}
+
+// ---------------------------------------------------------------------------------------
+// Algorithm 1 lines 1-2.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
+// hash and keeps the first k that differ from v and from all earlier draws.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init)
+{
+    extern __shared__ float smem[];
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    if (v >= g.n) return;
+    float* xs = smem + (size_t)wave * g.ld;
+    u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+    stage_row(g, v, xs);
+
+    int cnt = 0;
+    for (u64 t0 = 0; cnt < g.k; t0 += 64) {
+        const u32 c = (u32)(((tg_hash_xy(hs_init, (u64)v, t0 + (u64)lane) >> 32) * (u64)g.n) >> 32);
+        bool bad = (c == (u32)v);
+        for (int q = 0; q < cnt; ++q) bad |= (c == wscr[q]);
+        for (int q = 0; q < 63; ++q) {
+            u32 cq = (u32)__builtin_amdgcn_readlane((int)c, q);
+            bad |= (q < lane && cq == c);
+        }
+        const u64 ok = __ballot(!bad);
+        const int rank = cnt + __popcll(ok & tg_lanemask_lt());
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (!bad && rank < g.k) wscr[rank] = c;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        cnt = min(g.k, cnt + __popcll(ok));
+    }
+    const int cid = lane < g.k ? (int)wscr[lane] : -1;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
+    const float dist = wave_direct_dist(g, xs, rn_v, cid, wscr);
+    u64 key = lane < g.k ? tg_key(dist, (u32)cid, 1u) : TG_EMPTY_KEY;
+    key = tg_wave_sort(key);
+    if (lane < g.k) {
+        g.gid[v * g.k + lane] = tg_key_id(key) | 0x80000000u;
+        g.gdist[v * g.k + lane] = tg_key_dist(key);
+        if (lane == g.k - 1) g.kth[v] = key | 3ull;
+    }
+}
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s)
+{
+    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
+    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
+    hipLaunchKernelGGL(init_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, hs_init);
+}
+
+// ---------------------------------------------------------------------------------------
+// Section 4.2 list update (phase 1).  The wave that owns list v reads the list and v's
+// candidate slots, drops candidates the list already holds, sorts the rest, merges the two
+// ascending sequences and keeps the first k.  Entries sampled as "new" this round become
+// old; arrivals are new.  Used slots are handed back empty.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates)
+{
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    if (v >= g.n) return;
+    const int k = g.k;
+    u32 w = 0;
+    float dist = 0.0f;
+    if (lane < k) {
+        w = g.gid[v * k + lane];
+        dist = g.gdist[v * k + lane];
+    }
+    u32 fresh = w >> 31;
+    const u64 mf = __ballot(lane < k && fresh);
+    const bool flip = fresh && __popcll(mf & tg_lanemask_lt()) < S;
+    if (flip) fresh = 0;
+    u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
+
+    bool any_cand = false;
+    for (int c0 = 0; c0 < cd.C; c0 += 64) {
+        u64* slot = cd.slots + v * (int64_t)cd.C + c0 + lane;
+        u64 ck = (c0 + lane < cd.C) ? *slot : TG_EMPTY_KEY;
+        if (__ballot(ck != TG_EMPTY_KEY) == 0) continue;
+        any_cand = true;
+        if (c0 + lane < cd.C) *slot = TG_EMPTY_KEY;
+        const u32 cid = tg_key_id(ck);
+        const bool listed = id_in_list(cid, L, k);      // all lanes take part
+        if (cid == (u32)v || listed) ck = TG_EMPTY_KEY;
+        ck = tg_wave_sort(ck);
+        L = tg_wave_merge_low(L, ck);
+        if (lane >= k) L = TG_EMPTY_KEY;
+    }
+    if (!any_cand && mf == 0) return;
+    const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
+    if (lane < k) {
+        g.gid[v * k + lane] = tg_key_id(L) | (((u32)L & 1u) << 31);
+        g.gdist[v * k + lane] = tg_key_dist(L);
+        if (lane == k - 1) g.kth[v] = L | 3ull;
+    }
+    if (ins && lane == 0) atomicAdd(updates, (u64)ins);
+}
+void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, hipStream_t s)
+{
+    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
+    hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates);
+}
+
+// phase switch: every entry unvisited
+__global__ void mark_fresh_kernel(u32* gid, size_t count)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) gid[i] |= 0x80000000u;
+}
+void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
+{
+    size_t count = (size_t)g.n * g.k;
+    hipLaunchKernelGGL(mark_fresh_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, g.gid, count);
+}
+
+// ---------------------------------------------------------------------------------------
+// Algorithm 1 lines 9-12, one wave per node v: take the first m unvisited entries u of
+// G[v], mark them visited, read G[u] from the lists as they stood when the round began
+// (g.gid; this round writes g.gid_next), measure v against the ids that are neither v nor
+// listed, and merge them into G[v].  One candidate per lane: k <= 64.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, u64* updates, u64* stat_bins)
+{
+    extern __shared__ float smem[];
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    if (v >= g.n) return;
+    const int k = g.k;
+    float* xs = smem + (size_t)wave * g.ld;
+    u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+
+    u32 w = 0;
+    float dist = 0.0f;
+    if (lane < k) {
+        w = g.gid[v * k + lane];
+        dist = g.gdist[v * k + lane];
+    }
+    u32 fresh = w >> 31;
+    u64 mf = __ballot(lane < k && fresh);
+    if (fresh && __popcll(mf & tg_lanemask_lt()) < m) fresh = 0;   // non-revisitation
+    u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
+    const u32 my_id = w & TG_ID_MASK;
+    const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
+    const int nexp = min(m, __popcll(mf));
+    if (nexp > 0) stage_row(g, v, xs);
+
+    int evaluated = 0;
+    for (int e = 0; e < nexp; ++e) {
+        const int src = __ffsll((long long)mf) - 1;
+        mf &= mf - 1;
+        const u32 u = (u32)__builtin_amdgcn_readlane((int)my_id, src);
+        int cid = -1;
+        if (lane < k) cid = (int)(g.gid[(int64_t)u * k + lane] & TG_ID_MASK);
+        const bool listed = id_in_list((u32)cid, L, k);  // all lanes take part
+        if (cid == (int)v || listed) cid = -1;
+        evaluated += __popcll(__ballot(cid >= 0));
+        const float cdist = wave_direct_dist(g, xs, rn_v, cid, wscr);
+        u64 ck = cid >= 0 ? tg_key(cdist, (u32)cid, 3u) : TG_EMPTY_KEY;
+        ck = tg_wave_sort(ck);
+        L = tg_wave_merge_low(L, ck);
+        if (lane >= k) L = TG_EMPTY_KEY;
+    }
+    const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
+    if (lane < k) {
+        g.gid_next[v * k + lane] = tg_key_id(L) | (((u32)L & 1u) << 31);
+        g.gdist[v * k + lane] = tg_key_dist(L);
+        if (lane == k - 1) g.kth[v] = L | 3ull;
+    }
+    if (lane == 0) {
+        if (ins) atomicAdd(updates, (u64)ins);
+        if (stat_bins && evaluated) {
+            atomicAdd(stat_bins + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);                 // pairs
+            atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);  // vectors
+        }
+    }
+}
+void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
+{
+    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
+    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
+    hipLaunchKernelGGL(phase2_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, updates, stat_bins);
+}
+
+// ---------------------------------------------------------------------------------------
+// Output: optionally recompute every kept distance directly from the vectors (the join
+// ranks with the norm-plus-Gram form, which loses digits to cancellation) and re-sort.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, int recompute, int32_t* out_ids, float* out_dist)
+{
+    extern __shared__ float smem[];
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    if (v >= g.n) return;
+    const int k = g.k;
+    float* xs = smem + (size_t)wave * g.ld;
+    u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+    int id = -1;
+    float dist = 0.0f;
+    if (lane < k) {
+        id = (int)(g.gid[v * k + lane] & TG_ID_MASK);
+        dist = g.gdist[v * k + lane];
+    }
+    if (recompute) {
+        stage_row(g, v, xs);
+        const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
+        dist = wave_direct_dist(g, xs, rn_v, id, wscr);
+        u64 key = lane < k ? tg_key(dist, (u32)id, 0u) : TG_EMPTY_KEY;
+        key = tg_wave_sort(key);
+        id = (int)tg_key_id(key);
+        dist = tg_key_dist(key);
+    }
+    if (lane < k) {
+        out_ids[v * k + lane] = id;
+        if (out_dist) out_dist[v * k + lane] = dist;
+    }
+}
+void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s)
+{
+    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
+    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
+    hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, recompute, out_ids, out_dist);
+}
+
+// ---------------------------------------------------------------------------------------
+// state export / import
+// ---------------------------------------------------------------------------------------
+__global__ void export_kernel(TgGraph g, int32_t* ids, float* dist, uint8_t* fresh)
+{
+    size_t count = (size_t)g.n * g.k;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) {
+        u32 w = g.gid[i];
+        if (ids) ids[i] = (int32_t)(w & TG_ID_MASK);
+        if (dist) dist[i] = g.gdist[i];
+        if (fresh) fresh[i] = (uint8_t)(w >> 31);
+    }
+}
+void tg_launch_export(const TgGraph& g, int32_t* ids, float* dist, uint8_t* fresh, hipStream_t s)
+{
+    size_t count = (size_t)g.n * g.k;
+    hipLaunchKernelGGL(export_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, g, ids, dist, fresh);
+}
+__global__ void import_kernel(TgGraph g, const int32_t* ids, const float* dist, const uint8_t* fresh)
+{
+    size_t count = (size_t)g.n * g.k;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) {
+        g.gid[i] = (u32)ids[i] | ((u32)(fresh[i] != 0) << 31);
+        g.gdist[i] = dist[i];
+        if ((int)(i % g.k) == g.k - 1) g.kth[i / g.k] = tg_key(dist[i], (u32)ids[i], 3u);
+    }
+}
+void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s)
+{
+    size_t count = (size_t)g.n * g.k;
+    hipLaunchKernelGGL(import_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, g, ids, dist, fresh);
+}

@@ -1,0 +1,153 @@
+// Phase-1 sampling (step (1) of section 3.1.1): forward samples are read straight from
+// the lists (first S new and first S old entries in list order); this file builds the
+// bounded reverse samples.  Every sampled edge v -> u is counted at u, a prefix sum turns
+// the counts into segments, the edges are scattered into their segments, and the wave
+// that owns node u keeps, per class, the R arrivals with the smallest
+// (hash(round, source, u), source): a uniform subset that does not depend on arrival order.
+#include "tg_device.h"
+#include "tg_kernels.h"
+
+// ---- walk over the sampled edges: each group of KP lanes (KP = power of two >= k) owns one list
+template <class F>
+__device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, F f)
+{
+    const int lane = tg_lane();
+    const int per_wave = 64 / kp;
+    const int64_t wave_id = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int sub = lane & (kp - 1), grp = lane / kp;
+    const int64_t v = wave_id * per_wave + grp;
+    const bool live = v < g.n && sub < g.k;
+    u32 w = live ? g.gid[v * g.k + sub] : 0u;
+    const bool fresh = live && (w >> 31);
+    const bool old = live && !(w >> 31);
+    const u64 gmask = (kp == 64 ? ~0ull : ((1ull << kp) - 1ull)) << (grp * kp);
+    const u64 below = tg_lanemask_lt() & gmask;
+    const u64 mf = __ballot(fresh), mo = __ballot(old);
+    const bool take_new = fresh && __popcll(mf & below) < S;
+    const bool take_old = old && __popcll(mo & below) < S;
+    if (take_new || take_old) f((u32)v, w & TG_ID_MASK, take_old ? 1u : 0u);
+}
+
+__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg)
+{
+    for_each_sampled_edge(g, S, kp, [&](u32, u32 u, u32) { atomicAdd(deg + u, 1u); });
+}
+
+// fills segments from their ends: deg[u] counts down to zero again
+__global__ __launch_bounds__(256) void rev_fill_kernel(TgGraph g, int S, int kp, u32* deg, const u64* off, u32* csr)
+{
+    for_each_sampled_edge(g, S, kp, [&](u32 v, u32 u, u32 cls) {
+        u32 left = atomicSub(deg + u, 1u);
+        csr[off[u] + left - 1] = v | (cls << 31);
+    });
+}
+
+// ---- exclusive prefix sum of deg[0..n) into off[0..n], three passes -------------------------
+#define SCAN_BLOCK 1024   // elements per workgroup (256 threads x 4)
+
+__global__ __launch_bounds__(256) void scan_partial_kernel(const u32* deg, int64_t n, u64* block_sums)
+{
+    __shared__ u64 red[4];
+    int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * 4;
+    u64 s = 0;
+    for (int i = 0; i < 4; ++i) if (base + i < n) s += deg[base + i];
+    for (int o = 32; o > 0; o >>= 1) s += tg_shfl_xor64(s, o);
+    if (tg_lane() == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+// one workgroup scans the block sums in place (exclusive), and writes the grand total to off[n]
+__global__ __launch_bounds__(256) void scan_sums_kernel(u64* block_sums, int64_t nblocks, u64* off_total)
+{
+    __shared__ u64 carry_s;
+    __shared__ u64 wsum[4];
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < nblocks; base += 256) {
+        int64_t i = base + threadIdx.x;
+        u64 x = i < nblocks ? block_sums[i] : 0;
+        u64 incl = x;
+        for (int o = 1; o < 64; o <<= 1) {
+            u64 y = tg_shfl64(incl, max(tg_lane() - o, 0));
+            if (tg_lane() >= o) incl += y;
+        }
+        if (tg_lane() == 63) wsum[threadIdx.x >> 6] = incl;
+        __syncthreads();
+        u64 pre = carry_s;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pre += wsum[w];
+        if (i < nblocks) block_sums[i] = pre + incl - x;
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = pre + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *off_total = carry_s;
+}
+__global__ __launch_bounds__(256) void scan_final_kernel(const u32* deg, int64_t n, const u64* block_sums, u64* off)
+{
+    __shared__ u64 wsum[4];
+    int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * 4;
+    u32 x[4];
+    u64 s = 0;
+    for (int i = 0; i < 4; ++i) { x[i] = base + i < n ? deg[base + i] : 0u; s += x[i]; }
+    u64 incl = s;
+    for (int o = 1; o < 64; o <<= 1) {
+        u64 y = tg_shfl64(incl, max(tg_lane() - o, 0));
+        if (tg_lane() >= o) incl += y;
+    }
+    if (tg_lane() == 63) wsum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    u64 pre = block_sums[blockIdx.x];
+    for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pre += wsum[w];
+    u64 run = pre + incl - s;
+    for (int i = 0; i < 4; ++i) {
+        if (base + i < n) off[base + i] = run;
+        run += x[i];
+    }
+}
+size_t tg_scan_tmp_elems(int64_t n) { return (size_t)((n + SCAN_BLOCK - 1) / SCAN_BLOCK) + 1; }
+
+// ---- per node: keep the R smallest (priority, source) of each class ------------------------
+__global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev)
+{
+    const int lane = tg_lane();
+    const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (u >= g.n) return;
+    const u64 beg = sm.off[u], end = sm.off[u + 1];
+    u64 best_new = TG_EMPTY_KEY, best_old = TG_EMPTY_KEY;   // ascending across the wave
+    int tot_new = 0, tot_old = 0;
+    for (u64 base = beg; base < end; base += 64) {
+        u64 kn = TG_EMPTY_KEY, ko = TG_EMPTY_KEY;
+        if (base + lane < end) {
+            const u32 e = sm.csr[base + lane];
+            const u32 v = e & TG_ID_MASK;
+            const u64 key = (tg_hash_xy(hs_rev, (u64)v, (u64)u) & 0xFFFFFFFF00000000ull) | (u64)v;
+            if (e >> 31) ko = key; else kn = key;
+        }
+        const int cn = __popcll(__ballot(kn != TG_EMPTY_KEY));
+        const int co = __popcll(__ballot(ko != TG_EMPTY_KEY));
+        if (cn) { best_new = tg_wave_merge_low(best_new, tg_wave_sort(kn)); tot_new += cn; }
+        if (co) { best_old = tg_wave_merge_low(best_old, tg_wave_sort(ko)); tot_old += co; }
+    }
+    const int R = sm.R;
+    tot_new = min(tot_new, R);
+    tot_old = min(tot_old, R);
+    if (lane < tot_new) sm.rev_new[u * R + lane] = (u32)best_new;
+    if (lane < tot_old) sm.rev_old[u * R + lane] = (u32)best_old;
+    if (lane == 0) { sm.cnt_new[u] = (uint8_t)tot_new; sm.cnt_old[u] = (uint8_t)tot_old; }
+}
+
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s)
+{
+    int kp = 1;
+    while (kp < g.k) kp <<= 1;
+    const int per_wave = 64 / kp;
+    const int64_t waves = (g.n + per_wave - 1) / per_wave;
+    const unsigned edge_blocks = (unsigned)((waves + 3) / 4);
+    const int64_t nsb = (g.n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    hipLaunchKernelGGL(rev_count_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg);
+    hipLaunchKernelGGL(scan_partial_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sm.scan_tmp, nsb, sm.off + g.n);
+    hipLaunchKernelGGL(scan_final_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp, sm.off);
+    hipLaunchKernelGGL(rev_fill_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg, sm.off, sm.csr);
+    hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, hs_rev);
+}
