@@ -88,7 +88,7 @@ struct tg_knn_handle {
     TgSample sm;
     TgCand cd;
     hipStream_t stream;
-    u64* d_updates;      // TG_MAX_ROUNDS counters
+    u64* d_updates;      // TG_MAX_ROUNDS x TG_STAT_BINS partial counters (spread to avoid one hot address)
     u64* d_stat_bins;    // TG_MAX_ROUNDS x 2 x TG_STAT_BINS
     float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
     int round;           // rounds run so far (both phases)
@@ -123,14 +123,16 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->sm.deg = c.take<u32>(n);
     h->sm.off = c.take<u64>(n + 1);
     h->sm.csr = c.take<u32>((size_t)n * p.k);
-    h->sm.rev_new = c.take<u32>((size_t)n * (p.R ? p.R : 1));
-    h->sm.rev_old = c.take<u32>((size_t)n * (p.R ? p.R : 1));
-    h->sm.cnt_new = c.take<uint8_t>(n);
-    h->sm.cnt_old = c.take<uint8_t>(n);
+    {
+        const int fwd = p.k < 2 * p.S ? p.k : 2 * p.S;
+        h->sm.BC = (fwd + 2 * p.R + 15) & ~15;
+    }
+    h->sm.blk = c.take<u32>((size_t)n * h->sm.BC);
+    h->sm.bsz = c.take<u32>(n);
     h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(n));
     h->cd.C = p.C;
     h->cd.slots = c.take<u64>((size_t)n * p.C);
-    h->d_updates = c.take<u64>(TG_MAX_ROUNDS);
+    h->d_updates = c.take<u64>((size_t)TG_MAX_ROUNDS * TG_STAT_BINS);
     h->d_stat_bins = c.take<u64>((size_t)TG_MAX_ROUNDS * 2 * TG_STAT_BINS);
     *need = (c.used + 255) & ~(size_t)255;
 }
@@ -187,7 +189,7 @@ extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int
     if (h->x_padded) tg_launch_pad_rows(X, n, d, h->x_padded, h->g.ld, h->stream);
     tg_launch_fill_u32(h->sm.deg, (size_t)n, 0u, h->stream);
     tg_launch_fill_u64(h->cd.slots, (size_t)n * p->C, TG_EMPTY_KEY, h->stream);
-    tg_launch_fill_u64(h->d_updates, TG_MAX_ROUNDS, 0ull, h->stream);
+    tg_launch_fill_u64(h->d_updates, (size_t)TG_MAX_ROUNDS * TG_STAT_BINS, 0ull, h->stream);
     tg_launch_fill_u64(h->d_stat_bins, (size_t)TG_MAX_ROUNDS * 2 * TG_STAT_BINS, 0ull, h->stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -236,9 +238,12 @@ extern "C" int tg_knn_init(tg_knn_handle* h)
 
 static int read_updates(tg_knn_handle* h, int round, int64_t* updates)
 {
-    u64 v = 0;
-    HIP_TRY(hipMemcpyAsync(&v, h->d_updates + round, sizeof(u64), hipMemcpyDeviceToHost, h->stream));
+    std::vector<u64> bins(TG_STAT_BINS);
+    HIP_TRY(hipMemcpyAsync(bins.data(), h->d_updates + (size_t)round * TG_STAT_BINS, TG_STAT_BINS * sizeof(u64),
+                           hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(hipStreamSynchronize(h->stream));
+    u64 v = 0;
+    for (u64 b : bins) v += b;
     *updates = (int64_t)v;
     return TG_OK;
 }
@@ -257,7 +262,7 @@ extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates)
                    h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
     end_span(h, sp);
     sp = begin_span(h, SPAN_UPDATE, r);
-    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + r, h->stream);
+    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, h->stream);
     end_span(h, sp);
     h->round++;
     h->rounds1++;
@@ -281,7 +286,7 @@ extern "C" int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates)
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
     int sp = begin_span(h, SPAN_JOIN, r);
-    tg_launch_phase2(h->g, h->p.m, h->d_updates + r, h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
+    tg_launch_phase2(h->g, h->p.m, h->d_updates + (size_t)r * TG_STAT_BINS, h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
     end_span(h, sp);
     u32* t = h->g.gid; h->g.gid = h->g.gid_next; h->g.gid_next = t;   // the written lists are current now
     h->round++;
@@ -308,9 +313,15 @@ extern "C" int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out)
     HIP_TRY(hipStreamSynchronize(h->stream));
     out->rounds_phase1 = h->rounds1;
     out->rounds_phase2 = h->rounds2;
-    std::vector<u64> upd(TG_MAX_ROUNDS);
-    HIP_TRY(hipMemcpy(upd.data(), h->d_updates, TG_MAX_ROUNDS * sizeof(u64), hipMemcpyDeviceToHost));
-    for (int r = 0; r < TG_MAX_ROUNDS; ++r) out->updates[r] = (int64_t)upd[r];
+    if (h->round > 0) {
+        std::vector<u64> upd((size_t)h->round * TG_STAT_BINS);
+        HIP_TRY(hipMemcpy(upd.data(), h->d_updates, upd.size() * sizeof(u64), hipMemcpyDeviceToHost));
+        for (int r = 0; r < h->round; ++r) {
+            u64 v = 0;
+            for (int b = 0; b < TG_STAT_BINS; ++b) v += upd[(size_t)r * TG_STAT_BINS + b];
+            out->updates[r] = (int64_t)v;
+        }
+    }
     if (h->round > 0) {
         std::vector<u64> bins((size_t)h->round * 2 * TG_STAT_BINS);
         HIP_TRY(hipMemcpy(bins.data(), h->d_stat_bins, bins.size() * sizeof(u64), hipMemcpyDeviceToHost));

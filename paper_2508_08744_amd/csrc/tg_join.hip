@@ -13,119 +13,115 @@
 #include "tg_kernels.h"
 
 #define JOIN_THREADS 256
-#define JOIN_HDR_BYTES 3104   // kth[128] u64, hA[128] u64, ids[128], aux[128], sizes[4]  (16-byte multiple)
+#define JOIN_HDR_BYTES 3072   // hA[128] u64, kd[128], kid[128], ids[128], aux[128]
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------------------
-// Block assembly by one full wave.  ids: LDS int[128]; sizes: LDS int[2] = (|NEW|, |NEW|+|OLD|).
-// ---------------------------------------------------------------------------------------
-__device__ inline void build_block(const TgGraph& g, const TgSample& sm, int64_t v, int* ids, int* sizes)
+// cross-lane helpers: rotations inside a row of 16 lanes are DPP operand modifiers (no LDS)
+template <int N>
+__device__ inline float ror16_f(float x)
 {
-    const int lane = tg_lane();
-    const int k = g.k, S = sm.S, R = sm.R;
-    const u64 lt = tg_lanemask_lt();
-    const u32 w = lane < k ? g.gid[v * k + lane] : 0u;
-    const bool fr = lane < k && (w >> 31);
-    const bool ol = lane < k && !(w >> 31);
-    const u64 mf = __ballot(fr), mo = __ballot(ol);
-    const bool is_nf = fr && __popcll(mf & lt) < S;     // sampled new forward entry
-    const bool is_of = ol && __popcll(mo & lt) < S;     // sampled old forward entry
-    const u32 fid = w & TG_ID_MASK;
-    const int cn = sm.cnt_new[v], co = sm.cnt_old[v];
-    const u32 rn = lane < cn ? sm.rev_new[v * R + lane] : 0xFFFFFFFFu;
-    const u32 ro = lane < co ? sm.rev_old[v * R + lane] : 0xFFFFFFFFu;
-    const u64 m_nf = __ballot(is_nf), m_of = __ballot(is_of);
-    bool rn_dup = false, ro_dup = false, of_drop = false;
-    for (int q = 0; q < k; ++q) {
-        const u32 f = (u32)__builtin_amdgcn_readlane((int)fid, q);
-        if ((m_nf >> q) & 1ull) { rn_dup |= (rn == f); ro_dup |= (ro == f); }
-        else if ((m_of >> q) & 1ull) ro_dup |= (ro == f);
-    }
-    for (int q = 0; q < cn; ++q) of_drop |= (fid == (u32)__builtin_amdgcn_readlane((int)rn, q));
-    const bool keep_rn = lane < cn && !rn_dup;
-    const bool keep_of = is_of && !of_drop;
-    const bool keep_ro = lane < co && !ro_dup;
-    const u64 m_krn = __ballot(keep_rn), m_kof = __ballot(keep_of), m_kro = __ballot(keep_ro);
-    const int n_nf = __popcll(m_nf);
-    const int nN = n_nf + __popcll(m_krn);
-    const int n_kof = __popcll(m_kof);
-    const int nT = nN + n_kof + __popcll(m_kro);
-    if (is_nf) ids[__popcll(m_nf & lt)] = (int)fid;
-    if (keep_rn) ids[n_nf + __popcll(m_krn & lt)] = (int)rn;
-    if (keep_of) ids[nN + __popcll(m_kof & lt)] = (int)fid;
-    if (keep_ro) ids[nN + n_kof + __popcll(m_kro & lt)] = (int)ro;
-    if (lane == 0) { sizes[0] = nN; sizes[1] = nT; }
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xF, 0xF, false));
+}
+template <int N>
+__device__ inline u32 ror16_u(u32 x)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, 0x120 + N, 0xF, 0xF, false);
+}
+#define TG_NO_ID 0x7FFFFFFFu
+// minimum of (dist, id) pairs over the 16 lanes of a row; every lane gets the result
+__device__ inline void rowmin16(float& dist, u32& id)
+{
+    float m = dist;
+    m = fminf(m, ror16_f<8>(m));
+    m = fminf(m, ror16_f<4>(m));
+    m = fminf(m, ror16_f<2>(m));
+    m = fminf(m, ror16_f<1>(m));
+    u32 c = dist == m ? id : TG_NO_ID;
+    c = min(c, ror16_u<8>(c));
+    c = min(c, ror16_u<4>(c));
+    c = min(c, ror16_u<2>(c));
+    c = min(c, ror16_u<1>(c));
+    dist = m;
+    id = c;
+}
+__device__ inline void pairmin(float& bd, u32& bi, float d, u32 i)
+{
+    const bool take = d < bd || (d == bd && i < bi);
+    bd = take ? d : bd;
+    bi = take ? i : bi;
 }
 
-__global__ __launch_bounds__(256) void dump_blocks_kernel(TgGraph g, TgSample sm, int32_t* blk, int32_t* sizes)
-{
-    __shared__ int s_ids[4][TG_BLOCK_COLS];
-    __shared__ int s_sz[4][2];
-    const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * 4 + wave;
-    if (v >= g.n) return;
-    build_block(g, sm, v, s_ids[wave], s_sz[wave]);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    const int nT = s_sz[wave][1];
-    for (int i = lane; i < TG_BLOCK_COLS; i += 64) blk[v * TG_BLOCK_COLS + i] = i < nT ? s_ids[wave][i] : -1;
-    if (lane == 0) { sizes[v * 2] = s_sz[wave][0]; sizes[v * 2 + 1] = nT - s_sz[wave][0]; }
-}
-void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, int32_t* sizes, hipStream_t s)
-{
-    hipLaunchKernelGGL(dump_blocks_kernel, dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, blk, sizes);
-}
-
-// ---------------------------------------------------------------------------------------
-__device__ inline u64 rowmin16(u64 x)
-{
-    x = tg_min64(x, tg_shfl_xor64(x, 1));
-    x = tg_min64(x, tg_shfl_xor64(x, 2));
-    x = tg_min64(x, tg_shfl_xor64(x, 4));
-    x = tg_min64(x, tg_shfl_xor64(x, 8));
-    return x;
-}
-
-__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u64* s_hA, int tpos, u64 key)
+__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u64* s_hA, int tpos, float dist, u32 c)
 {
     const u32 t = (u32)s_ids[tpos];
-    const u32 c = tg_key_id(key);
     const u32 slot = (u32)(tg_mix64(s_hA[tpos] + (u64)c) >> 32) & (u32)(cd.C - 1);
-    atomicMin(cd.slots + (int64_t)t * cd.C + slot, key);
+    atomicMin(cd.slots + (int64_t)t * cd.C + slot, tg_key(dist, c, 3u));
 }
 
-// MODE 0: emit candidates.  MODE 1: write the distance tile of caller-given blocks.
+// MODE 0: emit candidates for the stored blocks.  MODE 1: write the distance tile of caller-given blocks.
 template <int DK, int NGR, int NGC, int MODE>
 __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
                                                             const int32_t* xsizes, float* xout)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    u64* s_kth = reinterpret_cast<u64*>(smem_raw);
-    u64* s_hA = s_kth + TG_BLOCK_COLS;
-    int* s_ids = reinterpret_cast<int*>(s_hA + TG_BLOCK_COLS);
-    float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);
-    int* s_sz = reinterpret_cast<int*>(s_aux + TG_BLOCK_COLS);
+    u64* s_hA = reinterpret_cast<u64*>(smem_raw);                       // slot-hash prefix of each member
+    float* s_kd = reinterpret_cast<float*>(s_hA + TG_BLOCK_COLS);       // threshold: distance of the member's last entry
+    u32* s_kid = reinterpret_cast<u32*>(s_kd + TG_BLOCK_COLS);          //            and its id
+    int* s_ids = reinterpret_cast<int*>(s_kid + TG_BLOCK_COLS);
+    float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);     // squared norm (or 1/|x| for cosine)
     float* tile = reinterpret_cast<float*>(smem_raw + JOIN_HDR_BYTES);
     constexpr int LDT = DK + 4;          // LDS row stride in floats (16-byte pad against bank conflicts)
+    constexpr int F4 = DK / 4;           // float4 per row and slab
+    constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t v = blockIdx.x;
+    int nN, nT;
+    const u32* bids;
     if (MODE == 0) {
-        if (wave == 0) build_block(g, sm, v, s_ids, s_sz);
+        const u32 z = sm.bsz[v];
+        nN = (int)(z & 0xFFu);
+        nT = (int)(z >> 8);
+        bids = sm.blk + v * (int64_t)sm.BC;
     } else {
-        if (tid < TG_BLOCK_COLS) s_ids[tid] = xblk[v * TG_BLOCK_COLS + tid];
-        if (tid == 0) { s_sz[0] = xsizes[v * 2]; s_sz[1] = xsizes[v * 2] + xsizes[v * 2 + 1]; }
+        nN = xsizes[v * 2];
+        nT = nN + xsizes[v * 2 + 1];
+        bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
     }
-    __syncthreads();
-    const int nN = s_sz[0], nT = s_sz[1];
     if (nN == 0 || nT < 2) return;
+
+    // gather of one slab: global -> registers now, registers -> LDS once the tile is free
+    float4 pre[PER];
+    auto issue = [&](int ks) {
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            const int e = tid + JOIN_THREADS * it;
+            const int row = e / F4, col = ks + (e % F4) * 4;
+            pre[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < nT && col < g.ld) pre[it] = *reinterpret_cast<const float4*>(g.X + (int64_t)bids[row] * g.ld + col);
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+            const int e = tid + JOIN_THREADS * it;
+            const int row = e / F4;
+            if (row < nT) *reinterpret_cast<float4*>(tile + row * LDT + (e % F4) * 4) = pre[it];
+        }
+    };
+    issue(0);
+
     if (tid < nT) {
-        const int id = s_ids[tid];
+        const int id = (int)bids[tid];
+        s_ids[tid] = id;
         s_aux[tid] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
         if (MODE == 0) {
-            s_kth[tid] = g.kth[id];
+            const u64 kth = g.kth[id];
+            s_kd[tid] = tg_unord((u32)(kth >> 32));
+            s_kid[tid] = ((u32)kth) >> 2;
             s_hA[tid] = tg_mix64(hs_slot + (u64)id);
         }
     }
@@ -154,18 +150,11 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 #pragma unroll
         for (int tj = 0; tj < 4; ++tj) acc[ti][tj] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
-    constexpr int F4 = DK / 4;
     for (int ks = 0; ks < g.ld; ks += DK) {
         __syncthreads();
-        const int total = nT * F4;
-        for (int e = tid; e < total; e += JOIN_THREADS) {
-            const int row = e / F4, c4 = e % F4;
-            const int col = ks + c4 * 4;
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < g.ld) val = *reinterpret_cast<const float4*>(g.X + (int64_t)s_ids[row] * g.ld + col);
-            *reinterpret_cast<float4*>(tile + row * LDT + c4 * 4) = val;
-        }
+        commit();
         __syncthreads();
+        if (ks + DK < g.ld) issue(ks + DK);      // next slab travels while this one is multiplied
         const int kend = min(DK, (g.ld - ks + 15) & ~15);
         // Lane (r, q) = (lane % 16, lane / 16) reads 4 consecutive columns 16*s + 4*q .. +3 of its
         // row; step t of the four MFMAs then contracts columns {16*s + 4*q + t : q = 0..3}.  The
@@ -192,20 +181,34 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     }
 
     // ---- epilogue.  Accumulator element e of tile (i, j) in lane (c16, g4) is the pair
-    // (row a = 16 i + 4 g4 + e, column b = 16 j + c16).
-    u64 colbest[4][NGR / 2];
+    // (row a = 16 i + 4 g4 + e, column b = 16 j + c16).  "Empty" is (inf, TG_NO_ID).
+    const float INF = __builtin_inff();
+    float cbd[4][NGR / 2];
+    u32 cbi[4][NGR / 2];
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj)
 #pragma unroll
-        for (int rg = 0; rg < NGR / 2; ++rg) colbest[tj][rg] = TG_EMPTY_KEY;
+        for (int rg = 0; rg < NGR / 2; ++rg) { cbd[tj][rg] = INF; cbi[tj][rg] = TG_NO_ID; }
 
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
         const int i = wr + 2 * ti;
         if (i >= MT) continue;
+        // per-lane row data for e = 0..3
+        float aux_a[4], kd_a[4];
+        u32 id_a[4], kid_a[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int a = 16 * i + 4 * g4 + e;
+            const int aa = a < nN ? a : 0;
+            aux_a[e] = s_aux[aa];
+            id_a[e] = (u32)s_ids[aa];
+            if (MODE == 0) { kd_a[e] = s_kd[aa]; kid_a[e] = s_kid[aa]; }
+        }
 #pragma unroll
         for (int cg = 0; cg < NGC / 2; ++cg) {
-            u64 best[4] = {TG_EMPTY_KEY, TG_EMPTY_KEY, TG_EMPTY_KEY, TG_EMPTY_KEY};
+            float rbd[4] = {INF, INF, INF, INF};
+            u32 rbi[4] = {TG_NO_ID, TG_NO_ID, TG_NO_ID, TG_NO_ID};
             bool any = false;
 #pragma unroll
             for (int tj = 0; tj < 4; ++tj) {
@@ -217,36 +220,36 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 const int bb = b_ok ? b : 0;
                 const float aux_b = s_aux[bb];
                 const u32 id_b = (u32)s_ids[bb];
-                const u64 kth_b = MODE == 0 ? s_kth[bb] : 0ull;
+                const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
+                const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int a = 16 * i + 4 * g4 + e;
                     const bool ok = b_ok && a < nN && b > a;
-                    const int aa = a < nN ? a : 0;
                     const float gram = acc[ti][tj][e];
                     float dist;
-                    if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, gram, s_aux[aa] + aux_b));
-                    else if (g.metric == 1) dist = -gram;
-                    else dist = 1.0f - gram * s_aux[aa] * aux_b;
+                    if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, gram, aux_a[e] + aux_b));
+                    else if (g.metric == 1) dist = -gram + 0.0f;
+                    else dist = 1.0f - gram * aux_a[e] * aux_b + 0.0f;
                     if (MODE == 1) {
                         if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + a) * TG_BLOCK_COLS + b] = dist;
                     } else {
-                        const u64 hi = (u64)tg_ord(dist) << 32;
-                        u64 kr = hi | (u64)((id_b << 2) | 3u);
-                        u64 kc = hi | (u64)(((u32)s_ids[aa] << 2) | 3u);
-                        if (!ok || kr >= s_kth[aa]) kr = TG_EMPTY_KEY;
-                        if (!ok || kc >= kth_b) kc = TG_EMPTY_KEY;
-                        best[e] = tg_min64(best[e], kr);
-                        colbest[tj][ti & (NGR / 2 - 1)] = tg_min64(colbest[tj][ti & (NGR / 2 - 1)], kc);
+                        // row node a meets column node b: b is a candidate of a and a of b, each
+                        // only if it would precede the last entry of the target's list
+                        const bool pr = ok && (dist < kd_a[e] || (dist == kd_a[e] && id_b < kid_a[e]));
+                        const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a[e] < kid_b));
+                        if (pr) pairmin(rbd[e], rbi[e], dist, id_b);
+                        if (pc) pairmin(cbd[tj][ti & (NGR / 2 - 1)], cbi[tj][ti & (NGR / 2 - 1)], dist, id_a[e]);
                     }
                 }
             }
             if (MODE == 0 && any) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) best[e] = rowmin16(best[e]);
-                const u64 mine = c16 == 0 ? best[0] : c16 == 1 ? best[1] : c16 == 2 ? best[2] : best[3];
+                for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
+                const float md = c16 == 0 ? rbd[0] : c16 == 1 ? rbd[1] : c16 == 2 ? rbd[2] : rbd[3];
+                const u32 mi = c16 == 0 ? rbi[0] : c16 == 1 ? rbi[1] : c16 == 2 ? rbi[2] : rbi[3];
                 const int a = 16 * i + 4 * g4 + c16;
-                if (c16 < 4 && mine != TG_EMPTY_KEY) emit_candidate(cd, s_ids, s_hA, a, mine);
+                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, a, md, mi);
             }
         }
     }
@@ -257,17 +260,18 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
             if (j >= NT) continue;
 #pragma unroll
             for (int rg = 0; rg < NGR / 2; ++rg) {
-                u64 x = colbest[tj][rg];
-                x = tg_min64(x, tg_shfl_xor64(x, 16));
-                x = tg_min64(x, tg_shfl_xor64(x, 32));
+                float d0 = cbd[tj][rg];
+                u32 i0 = cbi[tj][rg];
+                pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
+                pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
                 const int b = 16 * j + c16;
-                if (g4 == 0 && x != TG_EMPTY_KEY) emit_candidate(cd, s_ids, s_hA, b, x);
+                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, b, d0, i0);
             }
         }
     }
 }
 
-static size_t join_lds_bytes(int DK) { return JOIN_HDR_BYTES + (size_t)TG_BLOCK_COLS * (DK + 4) * sizeof(float); }
+static size_t join_lds_bytes(int DK, int rows) { return JOIN_HDR_BYTES + (size_t)rows * (DK + 4) * sizeof(float); }
 
 // LDS beyond 64 KB per workgroup has to be asked for once per kernel
 template <class K>
@@ -279,9 +283,11 @@ static void allow_large_lds(K kernel, size_t bytes)
 template <int DK, int NGR, int NGC>
 static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, hipStream_t s)
 {
-    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0>, join_lds_bytes(DK)), true);
+    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
     (void)once;
-    hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3((unsigned)g.n), dim3(JOIN_THREADS), join_lds_bytes(DK), s,
+    // rows of a stored block never exceed BC (16-row tiles may read a little further: keep a tile of slack)
+    const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;
+    hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3((unsigned)g.n), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s,
                        g, sm, c, hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr);
 }
 template <int DK>
@@ -295,7 +301,7 @@ static void launch_join_dk(const TgGraph& g, const TgSample& sm, const TgCand& c
     else if (ngr == 4 && ngc == 4) launch_join_t<DK, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
     else launch_join_t<DK, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
-static int join_slab(int ld) { return ld <= 64 ? 64 : 128; }
+static int join_slab(int ld) { (void)ld; return 64; }
 
 void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col, uint64_t hs_slot,
                     unsigned long long* stat_bins, hipStream_t s)
@@ -309,13 +315,13 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
 {
     TgSample sm = {};
     TgCand c = {};
-    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64)),
-                        allow_large_lds(join_kernel<128, 2, 2, 1>, join_lds_bytes(128)), true);
+    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)),
+                        allow_large_lds(join_kernel<128, 2, 2, 1>, join_lds_bytes(128, TG_BLOCK_COLS)), true);
     (void)once;
     if (join_slab(g.ld) == 64)
-        hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(64), s, g, sm,
+        hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm,
                            c, 0ull, (u64*)nullptr, blk, sizes, out);
     else
-        hipLaunchKernelGGL((join_kernel<128, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(128), s, g,
+        hipLaunchKernelGGL((join_kernel<128, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(128, TG_BLOCK_COLS), s, g,
                            sm, c, 0ull, (u64*)nullptr, blk, sizes, out);
 }

@@ -28,10 +28,9 @@ struct TgSample {
     uint32_t* deg;            // n, zero between rounds
     unsigned long long* off;  // n + 1
     uint32_t* csr;            // n x k: source | class << 31
-    uint32_t* rev_new;        // n x R
-    uint32_t* rev_old;        // n x R
-    uint8_t* cnt_new;         // n
-    uint8_t* cnt_old;         // n
+    int32_t BC;               // row stride of blk: min(k, 2S) + 2R rounded up to 16
+    uint32_t* blk;            // n x BC: this round's block of every anchor, NEW ids then OLD ids
+    uint32_t* bsz;            // n: |NEW| | (|NEW|+|OLD|) << 8
     unsigned long long* scan_tmp; // block sums of the prefix sum
 };
 

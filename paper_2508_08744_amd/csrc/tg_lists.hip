@@ -266,7 +266,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         g.gdist[v * k + lane] = tg_key_dist(L);
         if (lane == k - 1) g.kth[v] = L | 3ull;
     }
-    if (ins && lane == 0) atomicAdd(updates, (u64)ins);
+    if (ins && lane == 0) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
 }
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, hipStream_t s)
 {
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         if (lane == k - 1) g.kth[v] = L | 3ull;
     }
     if (lane == 0) {
-        if (ins) atomicAdd(updates, (u64)ins);
+        if (ins) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
         if (stat_bins && evaluated) {
             atomicAdd(stat_bins + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);                 // pairs
             atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);  // vectors

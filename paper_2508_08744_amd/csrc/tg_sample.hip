@@ -4,6 +4,7 @@
 // the counts into segments, the edges are scattered into their segments, and the wave
 // that owns node u keeps, per class, the R arrivals with the smallest
 // (hash(round, source, u), source): a uniform subset that does not depend on arrival order.
+// The same wave then assembles the anchor's block and stores it for the join.
 #include "tg_device.h"
 #include "tg_kernels.h"
 
@@ -106,7 +107,49 @@ __global__ __launch_bounds__(256) void scan_final_kernel(const u32* deg, int64_t
 }
 size_t tg_scan_tmp_elems(int64_t n) { return (size_t)((n + SCAN_BLOCK - 1) / SCAN_BLOCK) + 1; }
 
-// ---- per node: keep the R smallest (priority, source) of each class ------------------------
+// ---- per node: keep the R smallest (priority, source) of each class, then assemble the block --
+// Block of anchor v:  NEW = new_fwd ++ (new_rev not yet there),
+//                     OLD = (old_fwd not in NEW) ++ (old_rev in neither).
+// fwd entries sit one per lane (lanes < k), rn / ro are the kept reverse arrivals, ascending
+// by (priority, source), one per lane (lanes < cn / co).
+__device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int64_t v, u32 rn, int cn, u32 ro, int co)
+{
+    const int lane = tg_lane();
+    const int k = g.k, S = sm.S;
+    const u64 lt = tg_lanemask_lt();
+    const u32 w = lane < k ? g.gid[v * k + lane] : 0u;
+    const bool fr = lane < k && (w >> 31);
+    const bool ol = lane < k && !(w >> 31);
+    const u64 mf = __ballot(fr), mo = __ballot(ol);
+    const bool is_nf = fr && __popcll(mf & lt) < S;     // sampled new forward entry
+    const bool is_of = ol && __popcll(mo & lt) < S;     // sampled old forward entry
+    const u32 fid = w & TG_ID_MASK;
+    if (lane >= cn) rn = 0xFFFFFFFFu;
+    if (lane >= co) ro = 0xFFFFFFFFu;
+    const u64 m_nf = __ballot(is_nf), m_of = __ballot(is_of);
+    bool rn_dup = false, ro_dup = false, of_drop = false;
+    for (int q = 0; q < k; ++q) {
+        const u32 f = (u32)__builtin_amdgcn_readlane((int)fid, q);
+        if ((m_nf >> q) & 1ull) { rn_dup |= (rn == f); ro_dup |= (ro == f); }
+        else if ((m_of >> q) & 1ull) ro_dup |= (ro == f);
+    }
+    for (int q = 0; q < cn; ++q) of_drop |= (fid == (u32)__builtin_amdgcn_readlane((int)rn, q));
+    const bool keep_rn = lane < cn && !rn_dup;
+    const bool keep_of = is_of && !of_drop;
+    const bool keep_ro = lane < co && !ro_dup;
+    const u64 m_krn = __ballot(keep_rn), m_kof = __ballot(keep_of), m_kro = __ballot(keep_ro);
+    const int n_nf = __popcll(m_nf);
+    const int nN = n_nf + __popcll(m_krn);
+    const int n_kof = __popcll(m_kof);
+    const int nT = nN + n_kof + __popcll(m_kro);
+    u32* ids = sm.blk + v * (int64_t)sm.BC;
+    if (is_nf) ids[__popcll(m_nf & lt)] = fid;
+    if (keep_rn) ids[n_nf + __popcll(m_krn & lt)] = rn;
+    if (keep_of) ids[nN + __popcll(m_kof & lt)] = fid;
+    if (keep_ro) ids[nN + n_kof + __popcll(m_kro & lt)] = ro;
+    if (lane == 0) sm.bsz[v] = (u32)nN | ((u32)nT << 8);
+}
+
 __global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev)
 {
     const int lane = tg_lane();
@@ -128,12 +171,30 @@ __global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm,
         if (cn) { best_new = tg_wave_merge_low(best_new, tg_wave_sort(kn)); tot_new += cn; }
         if (co) { best_old = tg_wave_merge_low(best_old, tg_wave_sort(ko)); tot_old += co; }
     }
-    const int R = sm.R;
-    tot_new = min(tot_new, R);
-    tot_old = min(tot_old, R);
-    if (lane < tot_new) sm.rev_new[u * R + lane] = (u32)best_new;
-    if (lane < tot_old) sm.rev_old[u * R + lane] = (u32)best_old;
-    if (lane == 0) { sm.cnt_new[u] = (uint8_t)tot_new; sm.cnt_old[u] = (uint8_t)tot_old; }
+    assemble_block(g, sm, u, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R));
+}
+
+// blocks as stored -> the boundary's fixed n x 128 layout (padding -1) and (|NEW|, |OLD|)
+__global__ void dump_blocks_kernel(TgGraph g, TgSample sm, int32_t* blk, int32_t* sizes)
+{
+    size_t total = (size_t)g.n * TG_BLOCK_COLS;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < total; i += stride) {
+        const size_t v = i / TG_BLOCK_COLS;
+        const int c = (int)(i % TG_BLOCK_COLS);
+        const u32 z = sm.bsz[v];
+        const int nN = (int)(z & 0xFFu), nT = (int)(z >> 8);
+        blk[i] = c < nT ? (int32_t)sm.blk[v * sm.BC + c] : -1;
+        if (c == 0) { sizes[v * 2] = nN; sizes[v * 2 + 1] = nT - nN; }
+    }
+}
+void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, int32_t* sizes, hipStream_t s)
+{
+    size_t total = (size_t)g.n * TG_BLOCK_COLS;
+    size_t grid = (total + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL(dump_blocks_kernel, dim3((unsigned)grid), dim3(256), 0, s, g, sm, blk, sizes);
 }
 
 void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s)
