@@ -462,6 +462,51 @@ extern "C" int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int
 extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, const int64_t* query_rows,
                             int64_t nq, int32_t* out_ids, float* out_dist, void* stream)
 {
-    (void)X; (void)n; (void)d; (void)k; (void)metric; (void)query_rows; (void)nq; (void)out_ids; (void)out_dist; (void)stream;
-    return fail(TG_ERR_UNSUPPORTED, "tg_exact_knn is not built yet");
+    if (!X || !out_ids) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (k < 1 || k > 64) return fail(TG_ERR_INVALID_ARG, "k = %d outside 1..64", k);
+    if (n <= k || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "need k < n < 2^30");
+    if (d < 1 || d > 4096) return fail(TG_ERR_INVALID_ARG, "d = %d outside 1..4096", d);
+    if (metric < 0 || metric > 2) return fail(TG_ERR_INVALID_ARG, "unknown metric %d", metric);
+    if (nq < 0) return fail(TG_ERR_INVALID_ARG, "nq < 0");
+    if (nq == 0) return TG_OK;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (query_rows) {   // the row indices come from the caller: check them before a kernel uses them
+        std::vector<int64_t> hr((size_t)nq);
+        HIP_TRY(hipMemcpyAsync(hr.data(), query_rows, hr.size() * sizeof(int64_t), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        for (int64_t r : hr)
+            if (r < 0 || r >= n) return fail(TG_ERR_INVALID_ARG, "query row %lld out of range", (long long)r);
+    } else if (nq > n) {
+        return fail(TG_ERR_INVALID_ARG, "nq > n without query_rows");
+    }
+    const int ld = round_up4(d);
+    const bool pad = (ld != d) || ((reinterpret_cast<uintptr_t>(X) & 15) != 0);
+    const int slices = tg_exact_slices(n, nq);
+    Carver c{nullptr, 0};
+    c.take<float>(pad ? (size_t)n * ld : 0);
+    c.take<float>(n);
+    c.take<float>(n);
+    c.take<u64>((size_t)nq * slices * k);
+    const size_t bytes = (c.used + 255) & ~(size_t)255;
+    void* ws = nullptr;
+    if (hipMalloc(&ws, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(TG_ERR_OUT_OF_MEMORY, "scratch of %zu bytes could not be allocated", bytes);
+    }
+    Carver w{reinterpret_cast<char*>(ws), 0};
+    float* xp = w.take<float>(pad ? (size_t)n * ld : 0);
+    TgGraph g = {};
+    g.n = n; g.d = d; g.ld = ld; g.k = k; g.metric = metric;
+    g.X = pad ? xp : X;
+    g.nrm = w.take<float>(n);
+    g.rnorm = w.take<float>(n);
+    u64* partial = w.take<u64>((size_t)nq * slices * k);
+    if (pad) tg_launch_pad_rows(X, n, d, xp, ld, s);
+    if (metric == 2) tg_launch_norms(g, s);
+    tg_launch_exact_knn(g.X, ld, g.nrm, g.rnorm, n, d, k, metric, query_rows, nq, out_ids, out_dist, partial, slices, s);
+    int rc = launch_status("exact k-NN");
+    hipError_t e = hipStreamSynchronize(s);
+    (void)hipFree(ws);
+    if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "exact k-NN failed: %s", hipGetErrorString(e));
+    return rc;
 }

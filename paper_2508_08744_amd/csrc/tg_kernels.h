@@ -59,7 +59,8 @@ void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float
 void tg_launch_export(const TgGraph& g, int32_t* ids, float* dist, uint8_t* fresh, hipStream_t s);
 void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s);
 void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hipStream_t s);
+int tg_exact_slices(int64_t n, int64_t nq);
 void tg_launch_exact_knn(const float* X, int ld, const float* nrm, const float* rnorm, int64_t n, int d, int k,
                          int metric, const int64_t* rows, int64_t nq, int32_t* out_ids, float* out_dist,
-                         hipStream_t s);
+                         unsigned long long* partial /* nq x slices x k */, int nslices, hipStream_t s);
 size_t tg_scan_tmp_elems(int64_t n);

@@ -1,0 +1,92 @@
+"""CPU-only checks of the C boundary: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "tagore_knn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2508_08744_amd import knn
+    lib = knn.lib()
+    names = _declared()
+    assert len(names) >= 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(knn.EXPORTS) == names
+
+
+def test_default_params_follow_the_paper():
+    from paper_2508_08744_amd import knn
+    p = knn.default_params(32, 12)
+    assert (p.it1, p.it2) == (6, 6)            # it1 = it2 (section 7.3)
+    assert p.m == 2                            # top-m unvisited neighbours, m = 2 (section 4.1)
+    assert p.delta == 0.0 and p.k == 32
+    p = knn.default_params(16, 7)
+    assert (p.it1, p.it2, p.S) == (4, 3, 16)
+    p = knn.default_params(32, 0)
+    assert p.it1 + p.it2 == 16 and p.delta > 0
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    from paper_2508_08744_amd import knn
+    lib = knn.lib()
+    bad = [
+        dict(n=10, d=4, k=20),          # k >= n
+        dict(n=100, d=4, k=0),
+        dict(n=100, d=4, k=65),
+        dict(n=100, d=0, k=5),
+        dict(n=100, d=5000, k=5),
+        dict(n=2**30, d=4, k=5),
+        dict(n=100, d=4, k=5, metric=7),
+    ]
+    fake = ctypes.c_void_p(256)
+    for b in bad:
+        rc = lib.tg_knn_build(fake, b["n"], b["d"], b["k"], b.get("metric", 0), 4, 1, fake, None, None)
+        assert rc == -1, b
+        assert lib.tg_last_error()
+    assert lib.tg_knn_build(None, 100, 4, 5, 0, 4, 1, fake, None, None) == -1
+    assert lib.tg_knn_build(fake, 100, 4, 5, 0, 4, 1, None, None, None) == -1
+    for field, val in [("C", 48), ("C", 8), ("S", 0), ("S", 33), ("R", 33), ("ng_row", 3), ("ng_col", 16), ("m", 0),
+                       ("it1", 70), ("delta", 2.0)]:
+        p = knn.default_params(8, 4)
+        setattr(p, field, val)
+        assert lib.tg_knn_workspace_bytes(1000, 16, ctypes.byref(p)) == 0, field
+        h = ctypes.c_void_p()
+        assert lib.tg_knn_create(ctypes.byref(h), fake, 1000, 16, ctypes.byref(p), fake, 1 << 30, None) == -1
+    p = knn.default_params(8, 4)
+    need = lib.tg_knn_workspace_bytes(1000, 16, ctypes.byref(p))
+    assert need > 1000 * 8 * 4
+    h = ctypes.c_void_p()
+    assert lib.tg_knn_create(ctypes.byref(h), fake, 1000, 16, ctypes.byref(p), fake, need // 2, None) == -1
+    assert b"workspace too small" in lib.tg_last_error()
+    assert lib.tg_knn_create(ctypes.byref(h), fake, 1000, 16, ctypes.byref(p), ctypes.c_void_p(8), need, None) == -1
+    assert lib.tg_exact_knn(fake, 100, 4, 200, 0, None, 10, fake, None, None) == -1
+    assert lib.tg_knn_init(None) == -1 and lib.tg_knn_destroy(None) == 0
+
+
+def test_workspace_fits_the_largest_configuration():
+    # the 1e8 x 96 configuration must fit one MI355X (288 GB) together with its vectors and outputs
+    from paper_2508_08744_amd import inputs, knn
+    cfg = inputs.CONFIGS["C5"]
+    p = knn.default_params(cfg["k"], 12)
+    ws = knn.workspace_bytes(cfg["n"], cfg["d"], p)
+    total = ws + cfg["n"] * cfg["d"] * 4 + cfg["n"] * cfg["k"] * 8
+    assert total < 288e9, total / 1e9
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    from paper_2508_08744_amd import knn
+    monkeypatch.setattr(knn, "_lib", None)
+    monkeypatch.setattr(knn, "_LIB_PATH", "/nonexistent/libtagore_knn.so")
+    with pytest.raises(RuntimeError):
+        knn.lib()

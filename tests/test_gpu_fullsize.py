@@ -1,0 +1,46 @@
+"""The benchmark configuration (1M x 128, k = 32) in the launch configuration bench.py times:
+properties that hold at any size, and sampled rows checked one by one against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_08744_amd import inputs, knn
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c2_full_size():
+    cfg = inputs.CONFIGS["C2"]
+    n, d, k = cfg["n"], cfg["d"], cfg["k"]
+    X = inputs.make("C2")
+    Xg = torch.from_numpy(X).cuda()
+    import bench
+    prm = bench.bench_params(k)
+    ids, dist, st = knn.knn_build_ex(Xg, prm)
+    # --- properties over all n rows (checked with torch on the outputs)
+    assert int(ids.min()) >= 0 and int(ids.max()) < n
+    ar = torch.arange(n, device="cuda", dtype=torch.int32)[:, None]
+    assert not bool((ids == ar).any()), "self in list"
+    srt = torch.sort(ids, dim=1).values
+    assert not bool((srt[:, 1:] == srt[:, :-1]).any()), "duplicate id"
+    assert bool((dist[:, 1:] >= dist[:, :-1]).all()), "not sorted"
+    ties = dist[:, 1:] == dist[:, :-1]
+    assert bool((ids[:, 1:][ties] > ids[:, :-1][ties]).all()), "ties not ordered by id"
+    # --- sampled rows against the oracle, one by one
+    rows = inputs.sample_rows(n, 24, seed=3)
+    ids_s = ids[torch.from_numpy(rows).cuda()].cpu().numpy()
+    dist_s = dist[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    for q, r in enumerate(rows):
+        for j in range(k):
+            ref = oracle.distance(X, 0, int(r), int(ids_s[q, j]))
+            assert dist_s[q, j] == ref          # byte-valued features: fp32 is exact
+    truth, _ = oracle.brute_force_knn(X, k, 0, rows)
+    gi, gd = knn.exact_knn(Xg, k, "l2", torch.from_numpy(rows))
+    assert (gi.cpu().numpy() == truth).all(), "exact k-NN ids differ from the CPU's"
+    # --- recall on a larger sample, ground truth from the (just verified) exhaustive GPU search
+    rows2 = inputs.sample_rows(n, 2000, seed=4)
+    ti, _ = knn.exact_knn(Xg, k, "l2", torch.from_numpy(rows2))
+    rec = oracle.recall(ids[torch.from_numpy(rows2).cuda()].cpu().numpy(), ti.cpu().numpy())
+    assert rec >= 0.95, rec
+    assert st["rounds_phase1"] == prm.it1 and st["rounds_phase2"] == prm.it2

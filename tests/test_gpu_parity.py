@@ -1,0 +1,337 @@
+"""GPU parity: the HIP path, called through the C boundary, against the CPU oracle.
+
+Integer-valued inputs (the C2 recipe: byte-valued features) make every fp32 operation of
+the HIP path exact, so there the two must agree bit for bit after every step.  On real-valued
+inputs the decisions are taken in different precisions (fp32 Gram form vs fp64), so the
+comparison is statistical: recall within 0.005 of the oracle's at equal rounds, every reported
+distance within 1e-4 relative of an fp64 recomputation, lists sorted, duplicate-free, self-free.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_08744_amd import inputs, knn
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-4          # spec tolerance for reported distances
+RECALL_TOL = 0.005      # spec tolerance for recall against the oracle
+
+
+def _oracle_for(X, prm, metric=0):
+    return oracle.NNDescent(X, prm.k, metric=metric, S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16,
+                            ng_row=prm.ng_row, ng_col=prm.ng_col, m=prm.m, seed=prm.seed)
+
+
+def _same(gpu_graph, oracle_graph):
+    gi, gd, gf = [t.cpu().numpy() for t in gpu_graph]
+    oi, od, of = oracle_graph
+    return (gi == oi).all() and (gd.astype(np.float64) == od).all() and (gf == of).all()
+
+
+def _ref_dist(X, rows, ids, metric):
+    Xd = X.astype(np.float64)
+    a = Xd[rows][:, None, :]
+    b = Xd[ids]
+    if metric == 0:
+        return ((a - b) ** 2).sum(-1)
+    dot = (a * b).sum(-1)
+    if metric == 1:
+        return -dot
+    return 1.0 - dot / np.sqrt((a * a).sum(-1) * (b * b).sum(-1))
+
+
+def _check_properties(X, ids, dist, metric=0, rows=None):
+    n, k = ids.shape
+    rows = np.arange(n) if rows is None else rows
+    assert (ids >= 0).all() and (ids < len(X)).all()
+    assert (ids != rows[:, None]).all(), "self in list"
+    srt = np.sort(ids, axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all(), "duplicate id in a list"
+    assert (dist[:, 1:] >= dist[:, :-1]).all(), "list not sorted by distance"
+    ties = dist[:, 1:] == dist[:, :-1]
+    assert (ids[:, 1:][ties] > ids[:, :-1][ties]).all(), "equal distances not ordered by id"
+    ref = _ref_dist(X, rows, ids, metric)
+    scale = 1e-6 * float((X.astype(np.float64) ** 2).sum(1).mean())
+    rel = np.abs(dist - ref) / np.maximum(np.abs(ref), scale)
+    assert rel.max() <= REL_TOL, rel.max()
+
+
+@pytest.mark.parametrize("d", [4, 32, 100, 128, 200, 960])
+def test_join_distance_tile(d):
+    """The LDS/MFMA distance core on explicit blocks, ragged shapes included."""
+    n = 700
+    rng = np.random.default_rng(d)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    prm = knn.default_params(16, 4)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    shapes = [(64, 64), (1, 1), (17, 30), (64, 0), (5, 0), (33, 95), (16, 16), (2, 0), (1, 127), (48, 49)]
+    blk = np.zeros((len(shapes), 128), dtype=np.int32)
+    sizes = np.zeros((len(shapes), 2), dtype=np.int32)
+    for i, (a, o) in enumerate(shapes):
+        blk[i, :a + o] = rng.choice(n, size=a + o, replace=False)
+        sizes[i] = (a, o)
+    out = b.join_distances(torch.from_numpy(blk), torch.from_numpy(sizes)).cpu().numpy()
+    Xd = X.astype(np.float64)
+    for i, (a, o) in enumerate(shapes):
+        P = Xd[blk[i, :a + o]]
+        ref = ((P[:, None, :] - P[None, :, :]) ** 2).sum(-1)
+        used = np.zeros((64, 128), dtype=bool)
+        for r in range(a):
+            used[r, r + 1:a + o] = True
+        got = out[i][:a, :a + o]
+        m = used[:a, :a + o]
+        # norm-plus-Gram form in fp32: absolute error scales with the norms
+        tol = 4e-6 * (Xd ** 2).sum(1).max()
+        assert np.abs(got[m] - ref[:a][m]).max() <= tol
+        assert np.isnan(out[i][~used]).all(), "wrote outside the needed pairs"
+    b.close()
+
+
+def test_join_distance_rejects_bad_blocks():
+    X = torch.zeros((100, 8), device="cuda")
+    b = knn.Builder(X, knn.default_params(4, 2))
+    blk = torch.zeros((1, 128), dtype=torch.int32)
+    for sizes in ([65, 0], [10, 119], [-1, 3]):
+        with pytest.raises(knn.TagoreError):
+            b.join_distances(blk, torch.tensor([sizes], dtype=torch.int32))
+    blk[0, 1] = 100
+    with pytest.raises(knn.TagoreError):
+        b.join_distances(blk, torch.tensor([[2, 0]], dtype=torch.int32))
+    b.close()
+
+
+STEPWISE = [
+    # n, d, k, overrides: several tiles, ragged tails, odd d (padded rows), small and large caps
+    (3000, 64, 32, dict(C=64, ng_row=4, ng_col=8)),
+    (2500, 100, 16, dict(C=32, ng_row=2, ng_col=2, R=8)),
+    (1200, 30, 10, dict(C=16, ng_row=2, ng_col=4, S=6, R=20)),
+    (1500, 132, 32, dict(C=128, ng_row=4, ng_col=4)),
+    (900, 7, 48, dict(C=64, ng_row=2, ng_col=8, R=32)),
+    (400, 16, 64, dict(C=128, ng_row=4, ng_col=2, m=3)),
+]
+
+
+@pytest.mark.parametrize("n,d,k,kw", STEPWISE)
+def test_every_step_identical_to_oracle(n, d, k, kw):
+    """Algorithm 1 step by step on integer-valued data: blocks, lists, marks and update counts."""
+    X = inputs.make("C2", n=n, d=d, comps=max(2, n // 500))
+    prm = knn.default_params(k, 8, seed=5, **kw)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    b.init()
+    o.init()
+    assert _same(b.graph(), o.graph()), "initial lists"
+    for r in range(4):
+        blk, sizes = b.sample_blocks()
+        blk, sizes = blk.cpu().numpy(), sizes.cpu().numpy()
+        o.phase1_sample()
+        for v in range(n):
+            N, O = o.block(v)
+            assert sizes[v, 0] == len(N) and sizes[v, 1] == len(O), (r, v)
+            assert (blk[v, :len(N)] == N).all() and (blk[v, len(N):len(N) + len(O)] == O).all(), (r, v)
+            assert (blk[v, len(N) + len(O):] == -1).all()
+        assert b.phase1_round() == o.phase1_round(), "update count, phase 1 round %d" % r
+        assert _same(b.graph(), o.graph()), "lists after phase 1 round %d" % r
+    b.begin_phase2()
+    o.begin_phase2()
+    assert _same(b.graph(), o.graph())
+    for r in range(4):
+        assert b.phase2_round() == o.phase2_round(), "update count, phase 2 round %d" % r
+        assert _same(b.graph(), o.graph()), "lists after phase 2 round %d" % r
+    ids, dist = b.finalize()
+    oi, od, _ = o.graph()
+    assert (ids.cpu().numpy() == oi).all() and (dist.cpu().numpy().astype(np.float64) == od).all()
+    st = b.stats()
+    assert st["rounds_phase1"] == 4 and st["rounds_phase2"] == 4
+    b.close()
+
+
+def test_join_statistics_count_the_needed_pairs():
+    X = inputs.make("C2", n=2000, d=32, comps=4)
+    prm = knn.default_params(16, 6, seed=2)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    b.init(); o.init()
+    for r in range(3):
+        b.phase1_round(); o.phase1_round()
+        assert b.stats()["join_pairs"][r] == o.counters()["pairs"]
+    b.close()
+
+
+@pytest.mark.parametrize("iters", [1, 6, 9])
+def test_whole_build_identical_to_oracle(iters):
+    X = inputs.make("C2", n=2000, d=48, comps=4)
+    prm = knn.default_params(24, iters, seed=11)
+    ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    assert o.run(prm.it1, prm.it2) == (st["rounds_phase1"], st["rounds_phase2"])
+    oi, od, _ = o.graph()
+    assert (ids.cpu().numpy() == oi).all()
+    assert (dist.cpu().numpy().astype(np.float64) == od).all()
+
+
+def test_plain_entry_point_and_early_stop():
+    X = inputs.make("C2", n=3000, d=32, comps=6)
+    Xg = torch.from_numpy(X).cuda()
+    ids, dist = knn.knn_build(Xg, 16, "l2", iters=6, seed=4)
+    prm = knn.default_params(16, 6, seed=4)
+    o = _oracle_for(X, prm)
+    o.run(prm.it1, prm.it2)
+    assert (ids.cpu().numpy() == o.graph()[0]).all()
+    # iters <= 0: up to 16 rounds, each phase stops once a round changes < 0.1 % of the entries
+    ids0, _ = knn.knn_build(Xg, 16, "l2", iters=0, seed=4)
+    prm0 = knn.default_params(16, 0, seed=4)
+    o0 = _oracle_for(X, prm0)
+    r1, r2 = o0.run(prm0.it1, prm0.it2, delta=float(np.float32(prm0.delta)))
+    assert r1 < prm0.it1 or r2 < prm0.it2
+    assert (ids0.cpu().numpy() == o0.graph()[0]).all()
+    truth, _ = oracle.brute_force_knn(X, 16)
+    assert oracle.recall(ids0.cpu().numpy(), truth) > 0.97
+
+
+@pytest.mark.parametrize("cfg,metric", [("C1", "l2"), ("C4", "cosine"), ("C4", "ip"), ("C3", "l2")])
+def test_statistical_parity_on_real_valued_data(cfg, metric):
+    """Recall within 0.005 of the oracle's at equal rounds (mean over 3 seeds); reported
+    distances within 1e-4 relative of fp64; lists well-formed."""
+    sizes = {"C1": dict(n=6000), "C4": dict(n=5000, comps=10), "C3": dict(n=3000, d=200, comps=6)}[cfg]
+    X = inputs.make(cfg, **sizes)
+    k = 16
+    mcode = knn.METRICS[metric]
+    truth, _ = oracle.brute_force_knn(X, k, mcode)
+    gaps = []
+    for seed in (1, 2, 3):
+        prm = knn.default_params(k, 6, metric=metric, seed=seed, C=32)
+        ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
+        _check_properties(X, ids, dist, mcode)
+        o = _oracle_for(X, prm, mcode)
+        o.run(prm.it1, prm.it2)
+        r_gpu = oracle.recall(ids, truth)
+        r_cpu = oracle.recall(o.graph()[0], truth)
+        gaps.append(r_gpu - r_cpu)
+        assert r_gpu > 0.85
+    assert np.mean(gaps) >= -RECALL_TOL, gaps
+
+
+def test_phase1_lists_keep_their_invariants_without_finalize():
+    X = inputs.make("C1", n=4000)
+    prm = knn.default_params(16, 8, seed=3)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    b.init()
+    prev = None
+    for r in range(6):
+        if r == 3:
+            b.begin_phase2()
+        b.phase2_round() if r >= 3 else b.phase1_round()
+        ids, dist, fresh = [t.cpu().numpy() for t in b.graph()]
+        # in-round distances come from the Gram form: looser than the reported ones
+        srt = np.sort(ids, axis=1)
+        assert (srt[:, 1:] != srt[:, :-1]).all() and (ids != np.arange(len(ids))[:, None]).all()
+        assert (dist[:, 1:] >= dist[:, :-1]).all()
+        ref = _ref_dist(X, np.arange(len(ids)), ids, 0)
+        assert np.abs(dist - ref).max() <= 1e-5 * (X.astype(np.float64) ** 2).sum(1).max()
+        if prev is not None:
+            assert (dist <= prev + 1e-12).all()       # lists only improve
+        prev = dist
+    b.close()
+
+
+@pytest.mark.parametrize("metric", ["l2", "ip", "cosine"])
+def test_exact_knn_matches_oracle(metric):
+    mcode = knn.METRICS[metric]
+    # integer-valued rows: fp32 is exact, ids must match bit for bit (ties included)
+    X = inputs.make("C2", n=5000, d=24, comps=5)
+    rows = inputs.sample_rows(5000, 300)
+    ids, dist = knn.exact_knn(torch.from_numpy(X).cuda(), 20, metric, torch.from_numpy(rows))
+    oi, od = oracle.brute_force_knn(X, 20, mcode, rows)
+    if metric != "cosine":
+        assert (ids.cpu().numpy() == oi).all()
+        assert (dist.cpu().numpy().astype(np.float64) == od).all()
+    else:
+        np.testing.assert_allclose(dist.cpu().numpy(), od, rtol=0, atol=2e-6)
+    # real-valued rows: a mismatch is allowed only between ids whose fp64 distances agree to 1e-6
+    # relative (for cosine: to 5e-7 absolute, a few ulps of the O(1) cosine the fp32 path subtracts from 1)
+    X = inputs.make("C1", n=4000)
+    ids, dist = knn.exact_knn(torch.from_numpy(X).cuda(), 16, metric)
+    oi, od = oracle.brute_force_knn(X, 16, mcode)
+    ids = ids.cpu().numpy()
+    bad = np.argwhere(ids != oi)
+    assert len(bad) < 0.001 * ids.size
+    for q, j in bad:
+        a = oracle.distance(X, mcode, int(q), int(ids[q, j]))
+        tol = 5e-7 if metric == "cosine" else 1e-6 * max(abs(od[q, j]), 1e-3)
+        assert abs(a - od[q, j]) <= tol
+    _check_properties(X, ids, dist.cpu().numpy().astype(np.float64), mcode)
+
+
+def test_exact_knn_odd_shapes():
+    rng = np.random.default_rng(4)
+    X = np.rint(rng.uniform(0, 50, size=(1300, 5))).astype(np.float32)     # d not a multiple of 4, many ties
+    ids, dist = knn.exact_knn(torch.from_numpy(X).cuda(), 64, "l2", torch.tensor([0, 1299, 7]))
+    oi, od = oracle.brute_force_knn(X, 64, 0, np.array([0, 1299, 7]))
+    assert (ids.cpu().numpy() == oi).all() and (dist.cpu().numpy() == od).all()
+    with pytest.raises(knn.TagoreError):
+        knn.exact_knn(torch.from_numpy(X).cuda(), 8, "l2", torch.tensor([1300]))
+
+
+def test_degenerate_sizes():
+    # k = n - 1: the lists hold every other node from the start and must equal brute force
+    X = inputs.make("C2", n=33, d=12, comps=2)
+    prm = knn.default_params(32, 4, seed=1)
+    ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    oi, od = oracle.brute_force_knn(X, 32)
+    assert (ids.cpu().numpy() == oi).all() and (dist.cpu().numpy() == od).all()
+    # k = 1, d = 1
+    X = inputs.make("C2", n=500, d=1, comps=2)
+    prm = knn.default_params(1, 4, seed=1)
+    ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    o.run(prm.it1, prm.it2)
+    assert (ids.cpu().numpy() == o.graph()[0]).all()
+    # no rounds at all: the random lists come back sorted
+    prm = knn.default_params(8, 4, seed=9)
+    prm.it1 = prm.it2 = 0
+    X = inputs.make("C2", n=300, d=16, comps=2)
+    ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    o.init()
+    assert (ids.cpu().numpy() == o.graph()[0]).all() and st["rounds_phase1"] == 0
+    # phase 2 only / phase 1 only
+    for it1, it2 in ((0, 3), (3, 0)):
+        prm = knn.default_params(8, 4, seed=9)
+        prm.it1, prm.it2 = it1, it2
+        ids, _, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        o = _oracle_for(X, prm)
+        o.run(it1, it2)
+        assert (ids.cpu().numpy() == o.graph()[0]).all()
+
+
+def test_duplicate_points():
+    # many identical rows: zero distances and long tie runs
+    X = np.repeat(inputs.make("C2", n=60, d=16, comps=2), 20, axis=0)
+    prm = knn.default_params(16, 8, seed=2)
+    ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    o.run(prm.it1, prm.it2)
+    assert (ids.cpu().numpy() == o.graph()[0]).all()
+    _check_properties(X, ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64))
+
+
+def test_set_graph_round_trip_and_stream():
+    X = inputs.make("C2", n=800, d=20, comps=2)
+    prm = knn.default_params(12, 4, seed=6)
+    o = _oracle_for(X, prm)
+    o.init()
+    o.phase1_round()
+    oi, od, of = o.graph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                       # all work goes to the caller's stream
+        b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+        b.set_graph(torch.from_numpy(oi), torch.from_numpy(od), torch.from_numpy(of))
+        assert _same(b.graph(), (oi, od, of))
+        b.begin_phase2(); o.begin_phase2()
+        assert b.phase2_round() == o.phase2_round()
+        assert _same(b.graph(), o.graph())
+        b.close()
