@@ -64,7 +64,7 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
 template <int DK, int NGR, int NGC, int MODE>
 __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
-                                                            const int32_t* xsizes, float* xout)
+                                                            const int32_t* xsizes, float* xout, int skip_le)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     u64* s_hA = reinterpret_cast<u64*>(smem_raw);                       // slot-hash prefix of each member
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
         nT = nN + xsizes[v * 2 + 1];
         bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
     }
-    if (nN == 0 || nT < 2) return;
+    if (nN == 0 || nT < 2 || ((nT + 15) >> 4) <= skip_le) return;
 
     // gather of one slab: global -> registers now, registers -> LDS once the tile is free
     float4 pre[PER];
@@ -271,6 +271,158 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Register-resident variant for small blocks and d <= 128: one wave per anchor, no LDS tile
+// and no barrier.  The wave keeps the whole block in VGPRs in MFMA operand layout: lane
+// (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX and column step
+// s < 8, the four columns 16 s + 4 q .. + 3 of row 16 t + r.  Tile (i, j) is then 32
+// v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s].  Retention is per 16 x 16 tile
+// (ng_col = 8; ng_row = 4, or 2 with the column side combined over row groups i and i + 2).
+// Blocks with more than GMAX groups, or fewer than GMIN, are left to other launches.
+// MODE as in join_kernel.
+// ---------------------------------------------------------------------------------------
+template <int GMAX, int NGR, int MODE>
+__global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
+                                                        const int32_t* xblk, const int32_t* xsizes, float* xout,
+                                                        int64_t nblocks, int gmin)
+{
+    __shared__ u64 sh_hA[4][64];
+    __shared__ float sh_kd[4][64];
+    __shared__ u32 sh_kid[4][64];
+    __shared__ int sh_ids[4][64];
+    __shared__ float sh_aux[4][64];
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int64_t v = (int64_t)blockIdx.x * 4 + wave;
+    if (v >= nblocks) return;
+    int nN, nT;
+    const u32* bids;
+    if (MODE == 0) {
+        const u32 z = sm.bsz[v];
+        nN = (int)(z & 0xFFu);
+        nT = (int)(z >> 8);
+        bids = sm.blk + v * (int64_t)sm.BC;
+    } else {
+        nN = xsizes[v * 2];
+        nT = nN + xsizes[v * 2 + 1];
+        bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
+    }
+    const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
+    if (nN == 0 || nT < 2 || NT > GMAX || NT < gmin) return;
+    u64* s_hA = sh_hA[wave];
+    float* s_kd = sh_kd[wave];
+    u32* s_kid = sh_kid[wave];
+    int* s_ids = sh_ids[wave];
+    float* s_aux = sh_aux[wave];
+
+    const int r16 = lane & 15, q4 = lane >> 4;
+    // the block's rows, straight into MFMA operand registers (rows past the block repeat row 0
+    // and are masked in the epilogue)
+    float4 X[GMAX][8];
+#pragma unroll
+    for (int t = 0; t < GMAX; ++t) {
+        const int row = 16 * t + r16;
+        const u32 id = bids[(t < NT && row < nT) ? row : 0];
+        const float* x = g.X + (int64_t)id * g.ld + 4 * q4;
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+            X[t][s8] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < NT && 16 * s8 + 4 * q4 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 16 * s8);
+        }
+    }
+    if (lane < nT) {
+        const int id = (int)bids[lane];
+        s_ids[lane] = id;
+        s_aux[lane] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
+        if (MODE == 0) {
+            const u64 kth = g.kth[id];
+            s_kd[lane] = tg_unord((u32)(kth >> 32));
+            s_kid[lane] = ((u32)kth) >> 2;
+            s_hA[lane] = tg_mix64(hs_slot + (u64)id);
+        }
+    }
+    if (MODE == 0 && stat_bins && lane == 0) {
+        const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
+        atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
+        atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)nT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const float INF = __builtin_inff();
+    const int ksteps = (g.ld + 15) >> 4;
+#pragma unroll
+    for (int j = 0; j < GMAX; ++j) {
+        if (j >= NT) continue;
+        // column side of this tile column
+        const int b = 16 * j + r16;
+        const bool b_ok = b < nT;
+        const int bb = b_ok ? b : 0;
+        const float aux_b = s_aux[bb];
+        const u32 id_b = (u32)s_ids[bb];
+        const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
+        const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
+        float cbd[2] = {INF, INF};
+        u32 cbi[2] = {TG_NO_ID, TG_NO_ID};
+#pragma unroll
+        for (int i = 0; i <= j; ++i) {
+            if (i >= MT) continue;
+            floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s8 = 0; s8 < 8; ++s8) {
+                if (s8 < ksteps) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
+                }
+            }
+            // accumulator element e in lane (r16, q4): row a = 16 i + 4 q4 + e, column b = 16 j + r16
+            float rbd[4] = {INF, INF, INF, INF};
+            u32 rbi[4] = {TG_NO_ID, TG_NO_ID, TG_NO_ID, TG_NO_ID};
+            const int cslot = NGR == 4 ? 0 : (i & 1);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int a = 16 * i + 4 * q4 + e;
+                const bool ok = b_ok && a < nN && b > a;
+                const int aa = a < nN ? a : 0;
+                const float gram = acc[e];
+                float dist;
+                if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, gram, s_aux[aa] + aux_b));
+                else if (g.metric == 1) dist = -gram + 0.0f;
+                else dist = 1.0f - gram * s_aux[aa] * aux_b + 0.0f;
+                if (MODE == 1) {
+                    if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + a) * TG_BLOCK_COLS + b] = dist;
+                } else {
+                    const u32 id_a = (u32)s_ids[aa];
+                    const float kd_a = s_kd[aa];
+                    const bool pr = ok && (dist < kd_a || (dist == kd_a && id_b < s_kid[aa]));
+                    const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a < kid_b));
+                    if (pr) { rbd[e] = dist; rbi[e] = id_b; }
+                    if (pc) pairmin(cbd[cslot], cbi[cslot], dist, id_a);
+                }
+            }
+            if (MODE == 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
+                const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
+                const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
+                if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, 16 * i + 4 * q4 + r16, md, mi);
+                if (NGR == 4 || i + 2 > j || i + 2 >= MT) {
+                    // last tile of this row-tile group in this column: hand the column side over
+                    float d0 = cbd[cslot];
+                    u32 i0 = cbi[cslot];
+                    pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
+                    pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
+                    if (q4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, b, d0, i0);
+                    cbd[cslot] = INF;
+                    cbi[cslot] = TG_NO_ID;
+                }
+            }
+        }
+    }
+}
+
 static size_t join_lds_bytes(int DK, int rows) { return JOIN_HDR_BYTES + (size_t)rows * (DK + 4) * sizeof(float); }
 
 // LDS beyond 64 KB per workgroup has to be asked for once per kernel
@@ -281,33 +433,56 @@ static void allow_large_lds(K kernel, size_t bytes)
 }
 
 template <int DK, int NGR, int NGC>
-static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, hipStream_t s)
+static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int skip_le,
+                          hipStream_t s)
 {
     static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
     (void)once;
-    // rows of a stored block never exceed BC (16-row tiles may read a little further: keep a tile of slack)
-    const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;
+    const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;   // a stored block never exceeds BC rows
     hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3((unsigned)g.n), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s,
-                       g, sm, c, hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr);
+                       g, sm, c, hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, skip_le);
 }
 template <int DK>
 static void launch_join_dk(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
-                           u64* stat_bins, hipStream_t s)
+                           u64* stat_bins, int skip_le, hipStream_t s)
 {
-    if (ngr == 2 && ngc == 2) launch_join_t<DK, 2, 2>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 2 && ngc == 4) launch_join_t<DK, 2, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 2 && ngc == 8) launch_join_t<DK, 2, 8>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 4 && ngc == 2) launch_join_t<DK, 4, 2>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 4 && ngc == 4) launch_join_t<DK, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else launch_join_t<DK, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
+    if (ngr == 2 && ngc == 2) launch_join_t<DK, 2, 2>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    else if (ngr == 2 && ngc == 4) launch_join_t<DK, 2, 4>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    else if (ngr == 2 && ngc == 8) launch_join_t<DK, 2, 8>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    else if (ngr == 4 && ngc == 2) launch_join_t<DK, 4, 2>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    else if (ngr == 4 && ngc == 4) launch_join_t<DK, 4, 4>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    else launch_join_t<DK, 4, 8>(g, sm, c, hs_slot, stat_bins, skip_le, s);
 }
-static int join_slab(int ld) { (void)ld; return 64; }
+
+template <int GMAX, int NGR>
+static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int gmin,
+                          hipStream_t s)
+{
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, NGR, 0>), dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, c, hs_slot,
+                       stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, g.n, gmin);
+}
+
+// Small blocks (at most 64 rows) of low-dimensional data go to the register-resident wave
+// kernel, split by size so that each launch gets the occupancy its register count allows;
+// everything else to the workgroup kernel.
+#define WAVE_GMAX 4
+static bool wave_path(const TgGraph& g, int ng_col) { return g.ld <= 128 && ng_col == 8; }
 
 void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col, uint64_t hs_slot,
                     unsigned long long* stat_bins, hipStream_t s)
 {
-    if (join_slab(g.ld) == 64) launch_join_dk<64>(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, s);
-    else launch_join_dk<128>(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, s);
+    int skip_le = 0;
+    if (wave_path(g, ng_col)) {
+        if (ng_row == 4) {
+            launch_wave_t<3, 4>(g, sm, c, hs_slot, stat_bins, 0, s);
+            launch_wave_t<4, 4>(g, sm, c, hs_slot, stat_bins, 4, s);
+        } else {
+            launch_wave_t<3, 2>(g, sm, c, hs_slot, stat_bins, 0, s);
+            launch_wave_t<4, 2>(g, sm, c, hs_slot, stat_bins, 4, s);
+        }
+        skip_le = WAVE_GMAX;
+    }
+    launch_join_dk<64>(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, skip_le, s);
 }
 
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out,
@@ -315,13 +490,16 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
 {
     TgSample sm = {};
     TgCand c = {};
-    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)),
-                        allow_large_lds(join_kernel<128, 2, 2, 1>, join_lds_bytes(128, TG_BLOCK_COLS)), true);
+    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)), true);
     (void)once;
-    if (join_slab(g.ld) == 64)
-        hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm,
-                           c, 0ull, (u64*)nullptr, blk, sizes, out);
-    else
-        hipLaunchKernelGGL((join_kernel<128, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(128, TG_BLOCK_COLS), s, g,
-                           sm, c, 0ull, (u64*)nullptr, blk, sizes, out);
+    int skip_le = 0;
+    if (wave_path(g, 8)) {      // same routing as the production join
+        hipLaunchKernelGGL((join_wave_kernel<3, 4, 1>), dim3((unsigned)((nb + 3) / 4)), dim3(256), 0, s, g, sm, c, 0ull,
+                           (u64*)nullptr, blk, sizes, out, nb, 0);
+        hipLaunchKernelGGL((join_wave_kernel<4, 4, 1>), dim3((unsigned)((nb + 3) / 4)), dim3(256), 0, s, g, sm, c, 0ull,
+                           (u64*)nullptr, blk, sizes, out, nb, 4);
+        skip_le = WAVE_GMAX;
+    }
+    hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(64, TG_BLOCK_COLS), s,
+                       g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, skip_le);
 }
