@@ -316,13 +316,28 @@ static void clear_candidates(onnd_t *o)
     }
 }
 
+/* Slot of candidate c at target t: a per-(round, target) 32-bit salt from the
+ * tagged hash, then a 32-bit multiply-xorshift-multiply of (c + salt); the top
+ * log2(C) bits are the slot. */
+static uint32_t slot_of(uint64_t seed, int round, int32_t t, int32_t c, int C)
+{
+    uint32_t salt = (uint32_t)mix64(mix64(seed + TAG_SLOT(round) * TG_GOLDEN) + (uint64_t)t);
+    uint32_t h = ((uint32_t)c + salt) * 0x9E3779B1u;
+    h ^= h >> 15;
+    h *= 0x85EBCA77u;
+    int bits = 0;
+    while ((1 << bits) < C) ++bits;
+    return h >> (32 - bits);
+}
+uint32_t oracle_slot_of(uint64_t seed, int round, int32_t t, int32_t c, int C) { return slot_of(seed, round, t, c, C); }
+
 /* A candidate for target t.  With bounded storage the candidate goes to
- * slot hash(round, t, c) mod C and a slot keeps the smaller (dist, id). */
+ * slot_of(round, t, c) and a slot keeps the smaller (dist, id). */
 static void emit(onnd_t *o, int32_t t, int32_t c, double dist)
 {
     o->offered++;
     if (o->C == 0) { bag_push(&o->bag[t], dist, c); return; }
-    uint64_t s = (hash3(o->seed, TAG_SLOT(o->round), (uint64_t)t, (uint64_t)c) >> 32) & (uint64_t)(o->C - 1);
+    uint32_t s = slot_of(o->seed, o->round, t, c, o->C);
     cand_t *slot = o->slots + (int64_t)t * o->C + (int64_t)s;
     if (slot->id < 0 || key_less(dist, c, slot->dist, slot->id)) { slot->dist = dist; slot->id = c; }
 }

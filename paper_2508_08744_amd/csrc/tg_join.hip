@@ -1,7 +1,8 @@
-// Phase-1 local join (section 4.2, first part): one workgroup per anchor v.
-//   1. one wave assembles the anchor's block from the shared samples:
-//        NEW = new_fwd ++ (new_rev not yet there), OLD = (old_fwd not in NEW) ++ (old_rev in neither)
-//   2. the block's vectors are gathered into LDS, a slab of DK columns at a time;
+// Phase-1 local join (section 4.2, first part).  The sampling kernel has stored every
+// anchor's block (NEW ids, then OLD ids).  Anchors are first sorted into work lists by block
+// size; small blocks of low-dimensional data go to a register-resident one-wave-per-anchor
+// kernel, the rest to a workgroup kernel that
+//   2. gathers the block's vectors into LDS, a slab of DK columns at a time;
 //   3. the Gram tile NEW x (NEW ++ OLD) is accumulated with v_mfma_f32_16x16x4_f32 and turned
 //      into distances |x|^2 + |y|^2 - 2<x,y>  (or -<x,y>, or 1 - cos);
 //   4. retention: for every row node and column-tile group, and every column node and row-tile
@@ -13,7 +14,7 @@
 #include "tg_kernels.h"
 
 #define JOIN_THREADS 256
-#define JOIN_HDR_BYTES 3072   // hA[128] u64, kd[128], kid[128], ids[128], aux[128]
+#define JOIN_HDR_BYTES 2560   // salt[128], kd[128], kid[128], ids[128], aux[128]
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -53,10 +54,16 @@ __device__ inline void pairmin(float& bd, u32& bi, float d, u32 i)
     bi = take ? i : bi;
 }
 
-__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u64* s_hA, int tpos, float dist, u32 c)
+// Candidate c of the member at block position tpos goes to slot
+// top_bits((c + salt) * K1, xorshift, * K2) of that member's slot row and stays if it is the
+// smaller (dist, id): one 64-bit atomic minimum, no order dependence.
+__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, float dist, u32 c)
 {
     const u32 t = (u32)s_ids[tpos];
-    const u32 slot = (u32)(tg_mix64(s_hA[tpos] + (u64)c) >> 32) & (u32)(cd.C - 1);
+    u32 h = (c + s_salt[tpos]) * 0x9E3779B1u;
+    h ^= h >> 15;
+    h *= 0x85EBCA77u;
+    const u32 slot = h >> (33 - __ffs(cd.C));
     atomicMin(cd.slots + (int64_t)t * cd.C + slot, tg_key(dist, c, 3u));
 }
 
@@ -64,11 +71,12 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
 template <int DK, int NGR, int NGC, int MODE>
 __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
-                                                            const int32_t* xsizes, float* xout, int skip_le)
+                                                            const int32_t* xsizes, float* xout, const u32* wl,
+                                                            const u32* wl_cnt, int64_t direct_count, int skip_le)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    u64* s_hA = reinterpret_cast<u64*>(smem_raw);                       // slot-hash prefix of each member
-    float* s_kd = reinterpret_cast<float*>(s_hA + TG_BLOCK_COLS);       // threshold: distance of the member's last entry
+    u32* s_salt = reinterpret_cast<u32*>(smem_raw);                     // slot-hash salt of each member
+    float* s_kd = reinterpret_cast<float*>(s_salt + TG_BLOCK_COLS);     // threshold: distance of the member's last entry
     u32* s_kid = reinterpret_cast<u32*>(s_kd + TG_BLOCK_COLS);          //            and its id
     int* s_ids = reinterpret_cast<int*>(s_kid + TG_BLOCK_COLS);
     float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);     // squared norm (or 1/|x| for cosine)
@@ -78,7 +86,9 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int64_t v = blockIdx.x;
+    const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
+    for (int64_t w = blockIdx.x; w < count; w += gridDim.x) {
+    const int64_t v = wl ? (int64_t)wl[w] : w;
     int nN, nT;
     const u32* bids;
     if (MODE == 0) {
@@ -91,7 +101,8 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
         nT = nN + xsizes[v * 2 + 1];
         bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
     }
-    if (nN == 0 || nT < 2 || ((nT + 15) >> 4) <= skip_le) return;
+    if (nN == 0 || nT < 2 || ((nT + 15) >> 4) <= skip_le) continue;
+    __syncthreads();                       // the previous block's epilogue has left the LDS header
 
     // gather of one slab: global -> registers now, registers -> LDS once the tile is free
     float4 pre[PER];
@@ -122,13 +133,13 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
             const u64 kth = g.kth[id];
             s_kd[tid] = tg_unord((u32)(kth >> 32));
             s_kid[tid] = ((u32)kth) >> 2;
-            s_hA[tid] = tg_mix64(hs_slot + (u64)id);
+            s_salt[tid] = (u32)tg_mix64(hs_slot + (u64)id);
         }
     }
     if (MODE == 0 && stat_bins && tid == 0) {
         const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
-        atomicAdd(stat_bins + (blockIdx.x & (TG_STAT_BINS - 1)), pairs);
-        atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)nT);
+        atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
+        atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)nT);
     }
 
     const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
@@ -249,7 +260,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 const float md = c16 == 0 ? rbd[0] : c16 == 1 ? rbd[1] : c16 == 2 ? rbd[2] : rbd[3];
                 const u32 mi = c16 == 0 ? rbi[0] : c16 == 1 ? rbi[1] : c16 == 2 ? rbi[2] : rbi[3];
                 const int a = 16 * i + 4 * g4 + c16;
-                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, a, md, mi);
+                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, md, mi);
             }
         }
     }
@@ -265,10 +276,11 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
                 pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
                 const int b = 16 * j + c16;
-                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, b, d0, i0);
+                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, d0, i0);
             }
         }
     }
+    }   // work-list loop
 }
 
 
@@ -278,148 +290,200 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 // (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX and column step
 // s < 8, the four columns 16 s + 4 q .. + 3 of row 16 t + r.  Tile (i, j) is then 32
 // v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s].  Retention is per 16 x 16 tile
-// (ng_col = 8; ng_row = 4, or 2 with the column side combined over row groups i and i + 2).
-// Blocks with more than GMAX groups, or fewer than GMIN, are left to other launches.
-// MODE as in join_kernel.
+// (ng_row = 4, ng_col = 8), so every tile hands its survivors over at once.  Waves walk a
+// work list of anchors whose blocks have at most GMAX row groups.  MODE as in join_kernel.
 // ---------------------------------------------------------------------------------------
-template <int GMAX, int NGR, int MODE>
-__global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
+template <int GMAX, int MODE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ? 3 : 2))) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
                                                         const int32_t* xblk, const int32_t* xsizes, float* xout,
-                                                        int64_t nblocks, int gmin)
+                                                        const u32* wl, const u32* wl_cnt, int64_t direct_count, int gmin)
 {
-    __shared__ u64 sh_hA[4][64];
+    __shared__ u32 sh_salt[4][64];
     __shared__ float sh_kd[4][64];
     __shared__ u32 sh_kid[4][64];
     __shared__ int sh_ids[4][64];
     __shared__ float sh_aux[4][64];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * 4 + wave;
-    if (v >= nblocks) return;
-    int nN, nT;
-    const u32* bids;
-    if (MODE == 0) {
-        const u32 z = sm.bsz[v];
-        nN = (int)(z & 0xFFu);
-        nT = (int)(z >> 8);
-        bids = sm.blk + v * (int64_t)sm.BC;
-    } else {
-        nN = xsizes[v * 2];
-        nT = nN + xsizes[v * 2 + 1];
-        bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
-    }
-    const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
-    if (nN == 0 || nT < 2 || NT > GMAX || NT < gmin) return;
-    u64* s_hA = sh_hA[wave];
+    u32* s_salt = sh_salt[wave];
     float* s_kd = sh_kd[wave];
     u32* s_kid = sh_kid[wave];
     int* s_ids = sh_ids[wave];
     float* s_aux = sh_aux[wave];
-
     const int r16 = lane & 15, q4 = lane >> 4;
-    // the block's rows, straight into MFMA operand registers (rows past the block repeat row 0
-    // and are masked in the epilogue)
-    float4 X[GMAX][8];
-#pragma unroll
-    for (int t = 0; t < GMAX; ++t) {
-        const int row = 16 * t + r16;
-        const u32 id = bids[(t < NT && row < nT) ? row : 0];
-        const float* x = g.X + (int64_t)id * g.ld + 4 * q4;
-#pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) {
-            X[t][s8] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < NT && 16 * s8 + 4 * q4 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 16 * s8);
-        }
-    }
-    if (lane < nT) {
-        const int id = (int)bids[lane];
-        s_ids[lane] = id;
-        s_aux[lane] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
-        if (MODE == 0) {
-            const u64 kth = g.kth[id];
-            s_kd[lane] = tg_unord((u32)(kth >> 32));
-            s_kid[lane] = ((u32)kth) >> 2;
-            s_hA[lane] = tg_mix64(hs_slot + (u64)id);
-        }
-    }
-    if (MODE == 0 && stat_bins && lane == 0) {
-        const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
-        atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
-        atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)nT);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
     const float INF = __builtin_inff();
     const int ksteps = (g.ld + 15) >> 4;
+    const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+
+    for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < count; w += nwaves) {
+        const int64_t v = wl ? (int64_t)wl[w] : w;
+        int nN, nT;
+        const u32* bids;
+        if (MODE == 0) {
+            const u32 z = sm.bsz[v];
+            nN = (int)(z & 0xFFu);
+            nT = (int)(z >> 8);
+            bids = sm.blk + v * (int64_t)sm.BC;
+        } else {
+            nN = xsizes[v * 2];
+            nT = nN + xsizes[v * 2 + 1];
+            bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
+        }
+        const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
+        if (nN == 0 || nT < 2 || NT > GMAX || NT < gmin) continue;
+
+        // the block's rows, straight into MFMA operand registers (rows past the block repeat
+        // row 0 and are masked in the epilogue)
+        float4 X[GMAX][8];
 #pragma unroll
-    for (int j = 0; j < GMAX; ++j) {
-        if (j >= NT) continue;
-        // column side of this tile column
-        const int b = 16 * j + r16;
-        const bool b_ok = b < nT;
-        const int bb = b_ok ? b : 0;
-        const float aux_b = s_aux[bb];
-        const u32 id_b = (u32)s_ids[bb];
-        const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
-        const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
-        float cbd[2] = {INF, INF};
-        u32 cbi[2] = {TG_NO_ID, TG_NO_ID};
-#pragma unroll
-        for (int i = 0; i <= j; ++i) {
-            if (i >= MT) continue;
-            floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < GMAX; ++t) {
+            const int row = 16 * t + r16;
+            const u32 id = bids[(t < NT && row < nT) ? row : 0];
+            const float* x = g.X + (int64_t)id * g.ld + 4 * q4;
 #pragma unroll
             for (int s8 = 0; s8 < 8; ++s8) {
-                if (s8 < ksteps) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
-                }
+                X[t][s8] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (t < NT && 16 * s8 + 4 * q4 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 16 * s8);
             }
-            // accumulator element e in lane (r16, q4): row a = 16 i + 4 q4 + e, column b = 16 j + r16
-            float rbd[4] = {INF, INF, INF, INF};
-            u32 rbi[4] = {TG_NO_ID, TG_NO_ID, TG_NO_ID, TG_NO_ID};
-            const int cslot = NGR == 4 ? 0 : (i & 1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < nT) {
+            const int id = (int)bids[lane];
+            s_ids[lane] = id;
+            s_aux[lane] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
+            if (MODE == 0) {
+                const u64 kth = g.kth[id];
+                s_kd[lane] = tg_unord((u32)(kth >> 32));
+                s_kid[lane] = ((u32)kth) >> 2;
+                s_salt[lane] = (u32)tg_mix64(hs_slot + (u64)id);
+            }
+        }
+        if (MODE == 0 && stat_bins && lane == 0) {
+            const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
+            atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
+            atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)nT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+#pragma unroll
+        for (int i = 0; i < GMAX; ++i) {
+            if (i >= MT) continue;
+            // row side of this tile row: accumulator element e of lane (r16, q4) is row 16 i + 4 q4 + e
+            float aux_a[4], kd_a[4];
+            u32 id_a[4], kid_a[4];
+            bool a_ok[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int a = 16 * i + 4 * q4 + e;
-                const bool ok = b_ok && a < nN && b > a;
-                const int aa = a < nN ? a : 0;
-                const float gram = acc[e];
-                float dist;
-                if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, gram, s_aux[aa] + aux_b));
-                else if (g.metric == 1) dist = -gram + 0.0f;
-                else dist = 1.0f - gram * s_aux[aa] * aux_b + 0.0f;
-                if (MODE == 1) {
-                    if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + a) * TG_BLOCK_COLS + b] = dist;
-                } else {
-                    const u32 id_a = (u32)s_ids[aa];
-                    const float kd_a = s_kd[aa];
-                    const bool pr = ok && (dist < kd_a || (dist == kd_a && id_b < s_kid[aa]));
-                    const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a < kid_b));
-                    if (pr) { rbd[e] = dist; rbi[e] = id_b; }
-                    if (pc) pairmin(cbd[cslot], cbi[cslot], dist, id_a);
-                }
+                a_ok[e] = a < nN;
+                const int aa = a_ok[e] ? a : 0;
+                aux_a[e] = s_aux[aa];
+                id_a[e] = (u32)s_ids[aa];
+                kd_a[e] = MODE == 0 ? s_kd[aa] : 0.f;
+                kid_a[e] = MODE == 0 ? s_kid[aa] : 0u;
             }
-            if (MODE == 0) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
-                const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
-                const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
-                if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, 16 * i + 4 * q4 + r16, md, mi);
-                if (NGR == 4 || i + 2 > j || i + 2 >= MT) {
-                    // last tile of this row-tile group in this column: hand the column side over
-                    float d0 = cbd[cslot];
-                    u32 i0 = cbi[cslot];
-                    pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
-                    pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
-                    if (q4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_hA, b, d0, i0);
-                    cbd[cslot] = INF;
-                    cbi[cslot] = TG_NO_ID;
+            for (int j = i; j < GMAX; ++j) {
+                if (j >= NT) continue;
+                floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s8 = 0; s8 < 8; ++s8) {
+                    if (s8 < ksteps) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
+                    }
+                }
+                // column side: lane (r16, .) is column 16 j + r16
+                const int b = 16 * j + r16;
+                const bool b_ok = b < nT;
+                const int bb = b_ok ? b : 0;
+                const float aux_b = s_aux[bb];
+                const u32 id_b = (u32)s_ids[bb];
+                const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
+                const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
+                float rbd[4], cbd = INF;
+                u32 rbi[4], cbi = TG_NO_ID;
+                bool any_r = false;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // only the diagonal tile has pairs below the diagonal to mask
+                    const bool ok = b_ok && a_ok[e] && (i != j || b > 16 * i + 4 * q4 + e);
+                    float dist;
+                    if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, acc[e], aux_a[e] + aux_b));
+                    else if (g.metric == 1) dist = -acc[e] + 0.0f;
+                    else dist = 1.0f - acc[e] * aux_a[e] * aux_b + 0.0f;
+                    if (MODE == 1) {
+                        if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
+                    } else {
+                        // b is a candidate of a and a of b, each only if it would precede the
+                        // last entry of the target's list
+                        const bool pr = ok && (dist < kd_a[e] || (dist == kd_a[e] && id_b < kid_a[e]));
+                        const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a[e] < kid_b));
+                        rbd[e] = pr ? dist : INF;
+                        rbi[e] = pr ? id_b : TG_NO_ID;
+                        any_r |= pr;
+                        if (pc) pairmin(cbd, cbi, dist, id_a[e]);
+                    }
+                }
+                if (MODE == 0) {
+                    if (__ballot(any_r)) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
+                        const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
+                        const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
+                        if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, 16 * i + 4 * q4 + r16, md, mi);
+                    }
+                    if (__ballot(cbi != TG_NO_ID)) {
+                        pairmin(cbd, cbi, __shfl_xor(cbd, 16), (u32)__shfl_xor((int)cbi, 16));
+                        pairmin(cbd, cbi, __shfl_xor(cbd, 32), (u32)__shfl_xor((int)cbi, 32));
+                        if (q4 == 0 && cbi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, cbd, cbi);
+                    }
                 }
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Work lists: anchors with something to join, by block size.  List 0: at most 3 row groups,
+// list 1: exactly 4, list 2: more (or everything when the wave kernel does not apply).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wave_ok)
+{
+    __shared__ u32 wcnt[3][4];
+    __shared__ u32 base[3];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t v = (int64_t)blockIdx.x * 256 + tid;
+    int bin = -1;
+    if (v < n) {
+        const u32 z = sm.bsz[v];
+        const int nN = (int)(z & 0xFFu), nT = (int)(z >> 8);
+        if (nN > 0 && nT >= 2) {
+            const int NT = (nT + 15) >> 4;
+            bin = !wave_ok ? 2 : NT <= 3 ? 0 : NT == 4 ? 1 : 2;
+        }
+    }
+    u32 mypos = 0;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const u64 m = __ballot(bin == b);
+        if (lane == 0) wcnt[b][wave] = (u32)__popcll(m);
+        if (bin == b) mypos = (u32)__popcll(m & tg_lanemask_lt());
+    }
+    __syncthreads();
+    if (tid < 3) {
+        const u32 tot = wcnt[tid][0] + wcnt[tid][1] + wcnt[tid][2] + wcnt[tid][3];
+        base[tid] = tot ? atomicAdd(sm.wl_cnt + tid, tot) : 0u;
+    }
+    __syncthreads();
+    if (bin >= 0) {
+        u32 pos = base[bin] + mypos;
+        for (int w2 = 0; w2 < wave; ++w2) pos += wcnt[bin][w2];
+        sm.wl[(int64_t)bin * n + pos] = (u32)v;
     }
 }
 
@@ -432,57 +496,55 @@ static void allow_large_lds(K kernel, size_t bytes)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+#define JOIN_GRID 2048     // persistent launches: workgroups walk the work list with this stride
+
 template <int DK, int NGR, int NGC>
-static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int skip_le,
-                          hipStream_t s)
+static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, hipStream_t s)
 {
     static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
     (void)once;
     const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;   // a stored block never exceeds BC rows
-    hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3((unsigned)g.n), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s,
-                       g, sm, c, hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, skip_le);
+    const unsigned grid = (unsigned)(g.n < JOIN_GRID ? g.n : JOIN_GRID);
+    hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
+                       hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
+                       (const u32*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
 }
-template <int DK>
-static void launch_join_dk(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
-                           u64* stat_bins, int skip_le, hipStream_t s)
+static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
+                           u64* stat_bins, hipStream_t s)
 {
-    if (ngr == 2 && ngc == 2) launch_join_t<DK, 2, 2>(g, sm, c, hs_slot, stat_bins, skip_le, s);
-    else if (ngr == 2 && ngc == 4) launch_join_t<DK, 2, 4>(g, sm, c, hs_slot, stat_bins, skip_le, s);
-    else if (ngr == 2 && ngc == 8) launch_join_t<DK, 2, 8>(g, sm, c, hs_slot, stat_bins, skip_le, s);
-    else if (ngr == 4 && ngc == 2) launch_join_t<DK, 4, 2>(g, sm, c, hs_slot, stat_bins, skip_le, s);
-    else if (ngr == 4 && ngc == 4) launch_join_t<DK, 4, 4>(g, sm, c, hs_slot, stat_bins, skip_le, s);
-    else launch_join_t<DK, 4, 8>(g, sm, c, hs_slot, stat_bins, skip_le, s);
+    if (ngr == 2 && ngc == 2) launch_join_t<64, 2, 2>(g, sm, c, hs_slot, stat_bins, s);
+    else if (ngr == 2 && ngc == 4) launch_join_t<64, 2, 4>(g, sm, c, hs_slot, stat_bins, s);
+    else if (ngr == 2 && ngc == 8) launch_join_t<64, 2, 8>(g, sm, c, hs_slot, stat_bins, s);
+    else if (ngr == 4 && ngc == 2) launch_join_t<64, 4, 2>(g, sm, c, hs_slot, stat_bins, s);
+    else if (ngr == 4 && ngc == 4) launch_join_t<64, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
+    else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
 
-template <int GMAX, int NGR>
-static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int gmin,
+template <int GMAX>
+static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
                           hipStream_t s)
 {
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, NGR, 0>), dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, c, hs_slot,
-                       stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, g.n, gmin);
+    const int64_t wgs = (g.n + 3) / 4;
+    const unsigned grid = (unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID);
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+                       (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u32*)(sm.wl + (int64_t)list * g.n),
+                       (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
 }
 
-// Small blocks (at most 64 rows) of low-dimensional data go to the register-resident wave
-// kernel, split by size so that each launch gets the occupancy its register count allows;
-// everything else to the workgroup kernel.
-#define WAVE_GMAX 4
-static bool wave_path(const TgGraph& g, int ng_col) { return g.ld <= 128 && ng_col == 8; }
+// The register-resident kernel applies to rows of at most 128 floats with per-tile retention.
+static bool wave_path(const TgGraph& g, int ng_row, int ng_col) { return g.ld <= 128 && ng_row == 4 && ng_col == 8; }
 
 void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col, uint64_t hs_slot,
                     unsigned long long* stat_bins, hipStream_t s)
 {
-    int skip_le = 0;
-    if (wave_path(g, ng_col)) {
-        if (ng_row == 4) {
-            launch_wave_t<3, 4>(g, sm, c, hs_slot, stat_bins, 0, s);
-            launch_wave_t<4, 4>(g, sm, c, hs_slot, stat_bins, 4, s);
-        } else {
-            launch_wave_t<3, 2>(g, sm, c, hs_slot, stat_bins, 0, s);
-            launch_wave_t<4, 2>(g, sm, c, hs_slot, stat_bins, 4, s);
-        }
-        skip_le = WAVE_GMAX;
+    const bool wv = wave_path(g, ng_row, ng_col);
+    tg_launch_fill_u32(sm.wl_cnt, 4, 0u, s);
+    hipLaunchKernelGGL(bin_kernel, dim3((unsigned)((g.n + 255) / 256)), dim3(256), 0, s, sm, g.n, wv ? 1 : 0);
+    if (wv) {
+        launch_wave_t<3>(g, sm, c, hs_slot, stat_bins, 0, s);
+        launch_wave_t<4>(g, sm, c, hs_slot, stat_bins, 1, s);
     }
-    launch_join_dk<64>(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, skip_le, s);
+    launch_join_ng(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, s);
 }
 
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out,
@@ -493,13 +555,15 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
     static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)), true);
     (void)once;
     int skip_le = 0;
-    if (wave_path(g, 8)) {      // same routing as the production join
-        hipLaunchKernelGGL((join_wave_kernel<3, 4, 1>), dim3((unsigned)((nb + 3) / 4)), dim3(256), 0, s, g, sm, c, 0ull,
-                           (u64*)nullptr, blk, sizes, out, nb, 0);
-        hipLaunchKernelGGL((join_wave_kernel<4, 4, 1>), dim3((unsigned)((nb + 3) / 4)), dim3(256), 0, s, g, sm, c, 0ull,
-                           (u64*)nullptr, blk, sizes, out, nb, 4);
-        skip_le = WAVE_GMAX;
+    const int64_t wgs = (nb + 3) / 4;
+    if (wave_path(g, 4, 8)) {      // same routing by block size as the production join
+        hipLaunchKernelGGL((join_wave_kernel<3, 1>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s, g, sm, c,
+                           0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, 0);
+        hipLaunchKernelGGL((join_wave_kernel<4, 1>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s, g, sm, c,
+                           0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, 4);
+        skip_le = 4;
     }
-    hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)nb), dim3(JOIN_THREADS), join_lds_bytes(64, TG_BLOCK_COLS), s,
-                       g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, skip_le);
+    hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
+                       join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr,
+                       (const u32*)nullptr, nb, skip_le);
 }

@@ -384,3 +384,18 @@ def test_phase2_semantics():
                     assert f == 0
                 else:
                     assert f == f0[v][ids0[v].tolist().index(u)]
+
+
+def test_candidate_slots_spread_evenly():
+    # the slot function must use all C slots about equally for any one target, and two
+    # candidates that collide at one target or round must not collide at all of them
+    for C in (16, 64, 128):
+        counts = np.zeros(C)
+        for c in range(4000):
+            s = oracle.slot_of(7, 3, 123, c, C)
+            assert 0 <= s < C
+            counts[s] += 1
+        mean = 4000 / C                              # counts behave like Poisson(mean)
+        assert counts.min() > mean - 5 * mean ** 0.5 and counts.max() < mean + 5 * mean ** 0.5
+    same = sum(oracle.slot_of(7, r, t, 10, 64) == oracle.slot_of(7, r, t, 77, 64) for r in range(20) for t in range(50))
+    assert 2 <= same <= 40          # about 1000 / 64 by chance
