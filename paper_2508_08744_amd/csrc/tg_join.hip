@@ -49,9 +49,22 @@ __device__ inline void rowmin16(float& dist, u32& id)
 }
 __device__ inline void pairmin(float& bd, u32& bi, float d, u32 i)
 {
-    const bool take = d < bd || (d == bd && i < bi);
+    const bool take = (d < bd) | ((d == bd) & (i < bi));
     bd = take ? d : bd;
     bi = take ? i : bi;
+}
+// Gram value -> distance.  aux = squared norms (L2) or inverse norms (cosine).
+template <int METRIC>
+__device__ inline float gram_to_dist(float gram, float aux_a, float aux_b)
+{
+    if (METRIC == 0) return fmaxf(0.0f, fmaf(-2.0f, gram, aux_a + aux_b));
+    if (METRIC == 1) return -gram + 0.0f;
+    return 1.0f - gram * aux_a * aux_b + 0.0f;
+}
+// (dist, id) precedes the target's last list entry (kd, kid)?
+__device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
+{
+    return (dist < kd) | ((dist == kd) & (id < kid));
 }
 
 // Candidate c of the member at block position tpos goes to slot
@@ -236,21 +249,20 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int a = 16 * i + 4 * g4 + e;
-                    const bool ok = b_ok && a < nN && b > a;
+                    const bool ok = b_ok & (a < nN) & (b > a);
                     const float gram = acc[ti][tj][e];
-                    float dist;
-                    if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, gram, aux_a[e] + aux_b));
-                    else if (g.metric == 1) dist = -gram + 0.0f;
-                    else dist = 1.0f - gram * aux_a[e] * aux_b + 0.0f;
+                    const float dist = g.metric == 0 ? gram_to_dist<0>(gram, aux_a[e], aux_b)
+                                     : g.metric == 1 ? gram_to_dist<1>(gram, aux_a[e], aux_b)
+                                                     : gram_to_dist<2>(gram, aux_a[e], aux_b);
                     if (MODE == 1) {
                         if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + a) * TG_BLOCK_COLS + b] = dist;
                     } else {
                         // row node a meets column node b: b is a candidate of a and a of b, each
                         // only if it would precede the last entry of the target's list
-                        const bool pr = ok && (dist < kd_a[e] || (dist == kd_a[e] && id_b < kid_a[e]));
-                        const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a[e] < kid_b));
-                        if (pr) pairmin(rbd[e], rbi[e], dist, id_b);
-                        if (pc) pairmin(cbd[tj][ti & (NGR / 2 - 1)], cbi[tj][ti & (NGR / 2 - 1)], dist, id_a[e]);
+                        const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
+                        const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
+                        pairmin(rbd[e], rbi[e], pr ? dist : INF, pr ? id_b : TG_NO_ID);
+                        pairmin(cbd[tj][ti & (NGR / 2 - 1)], cbi[tj][ti & (NGR / 2 - 1)], pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
                     }
                 }
             }
@@ -287,13 +299,14 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 // ---------------------------------------------------------------------------------------
 // Register-resident variant for small blocks and d <= 128: one wave per anchor, no LDS tile
 // and no barrier.  The wave keeps the whole block in VGPRs in MFMA operand layout: lane
-// (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX and column step
-// s < 8, the four columns 16 s + 4 q .. + 3 of row 16 t + r.  Tile (i, j) is then 32
-// v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s].  Retention is per 16 x 16 tile
+// (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX, the q-th quarter
+// of row 16 t + r (column step s < 8 = four consecutive columns of that quarter).  Tile
+// (i, j) is then 32 v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s]: both operands use
+// the same column permutation, so the sum is the full dot product.  Retention is per 16 x 16 tile
 // (ng_row = 4, ng_col = 8), so every tile hands its survivors over at once.  Waves walk a
 // work list of anchors whose blocks have at most GMAX row groups.  MODE as in join_kernel.
 // ---------------------------------------------------------------------------------------
-template <int GMAX, int MODE>
+template <int GMAX, int MODE, int METRIC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ? 3 : 2))) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
                                                         const int32_t* xblk, const int32_t* xsizes, float* xout,
                                                         const u32* wl, const u32* wl_cnt, int64_t direct_count, int gmin)
@@ -311,7 +324,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ?
     float* s_aux = sh_aux[wave];
     const int r16 = lane & 15, q4 = lane >> 4;
     const float INF = __builtin_inff();
-    const int ksteps = (g.ld + 15) >> 4;
+    const int cw = (((g.ld + 3) >> 2) + 3) & ~3;     // columns per lane quarter, a multiple of 4
+    const int ksteps = cw >> 2;
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     const int64_t nwaves = (int64_t)gridDim.x * 4;
 
@@ -333,17 +347,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ?
         if (nN == 0 || nT < 2 || NT > GMAX || NT < gmin) continue;
 
         // the block's rows, straight into MFMA operand registers (rows past the block repeat
-        // row 0 and are masked in the epilogue)
+        // row 0 and are masked in the epilogue).  Lane (r, q) owns the q-th quarter of row r:
+        // cw contiguous columns, so the four lanes of a row pull the whole row in at once.
         float4 X[GMAX][8];
 #pragma unroll
         for (int t = 0; t < GMAX; ++t) {
             const int row = 16 * t + r16;
             const u32 id = bids[(t < NT && row < nT) ? row : 0];
-            const float* x = g.X + (int64_t)id * g.ld + 4 * q4;
+            const float* x = g.X + (int64_t)id * g.ld + cw * q4;
 #pragma unroll
             for (int s8 = 0; s8 < 8; ++s8) {
                 X[t][s8] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (t < NT && 16 * s8 + 4 * q4 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 16 * s8);
+                if (t < NT && 4 * s8 < cw && cw * q4 + 4 * s8 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 4 * s8);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -351,7 +366,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ?
         if (lane < nT) {
             const int id = (int)bids[lane];
             s_ids[lane] = id;
-            s_aux[lane] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
+            s_aux[lane] = METRIC == 2 ? g.rnorm[id] : g.nrm[id];
             if (MODE == 0) {
                 const u64 kth = g.kth[id];
                 s_kd[lane] = tg_unord((u32)(kth >> 32));
@@ -411,22 +426,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ?
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     // only the diagonal tile has pairs below the diagonal to mask
-                    const bool ok = b_ok && a_ok[e] && (i != j || b > 16 * i + 4 * q4 + e);
-                    float dist;
-                    if (g.metric == 0) dist = fmaxf(0.0f, fmaf(-2.0f, acc[e], aux_a[e] + aux_b));
-                    else if (g.metric == 1) dist = -acc[e] + 0.0f;
-                    else dist = 1.0f - acc[e] * aux_a[e] * aux_b + 0.0f;
+                    const bool ok = b_ok & a_ok[e] & ((i != j) | (b > 16 * i + 4 * q4 + e));
+                    const float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b);
                     if (MODE == 1) {
                         if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
                     } else {
                         // b is a candidate of a and a of b, each only if it would precede the
                         // last entry of the target's list
-                        const bool pr = ok && (dist < kd_a[e] || (dist == kd_a[e] && id_b < kid_a[e]));
-                        const bool pc = ok && (dist < kd_b || (dist == kd_b && id_a[e] < kid_b));
+                        const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
+                        const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
                         rbd[e] = pr ? dist : INF;
                         rbi[e] = pr ? id_b : TG_NO_ID;
                         any_r |= pr;
-                        if (pc) pairmin(cbd, cbi, dist, id_a[e]);
+                        pairmin(cbd, cbi, pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
                     }
                 }
                 if (MODE == 0) {
@@ -520,15 +532,33 @@ static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c
     else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
 
-template <int GMAX>
-static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
+template <int GMAX, int METRIC>
+static void launch_wave_m(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
                           hipStream_t s)
 {
     const int64_t wgs = (g.n + 3) / 4;
     const unsigned grid = (unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID);
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
                        (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u32*)(sm.wl + (int64_t)list * g.n),
                        (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+}
+template <int GMAX>
+static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
+                          hipStream_t s)
+{
+    if (g.metric == 0) launch_wave_m<GMAX, 0>(g, sm, c, hs_slot, stat_bins, list, s);
+    else if (g.metric == 1) launch_wave_m<GMAX, 1>(g, sm, c, hs_slot, stat_bins, list, s);
+    else launch_wave_m<GMAX, 2>(g, sm, c, hs_slot, stat_bins, list, s);
+}
+template <int GMAX, int METRIC>
+static void launch_wave_dump(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out, int gmin,
+                             hipStream_t s)
+{
+    TgSample sm = {};
+    TgCand c = {};
+    const int64_t wgs = (nb + 3) / 4;
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s,
+                       g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, gmin);
 }
 
 // The register-resident kernel applies to rows of at most 128 floats with per-tile retention.
@@ -555,12 +585,10 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
     static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)), true);
     (void)once;
     int skip_le = 0;
-    const int64_t wgs = (nb + 3) / 4;
     if (wave_path(g, 4, 8)) {      // same routing by block size as the production join
-        hipLaunchKernelGGL((join_wave_kernel<3, 1>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s, g, sm, c,
-                           0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, 0);
-        hipLaunchKernelGGL((join_wave_kernel<4, 1>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s, g, sm, c,
-                           0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, 4);
+        if (g.metric == 0) { launch_wave_dump<3, 0>(g, blk, sizes, nb, out, 0, s); launch_wave_dump<4, 0>(g, blk, sizes, nb, out, 4, s); }
+        else if (g.metric == 1) { launch_wave_dump<3, 1>(g, blk, sizes, nb, out, 0, s); launch_wave_dump<4, 1>(g, blk, sizes, nb, out, 4, s); }
+        else { launch_wave_dump<3, 2>(g, blk, sizes, nb, out, 0, s); launch_wave_dump<4, 2>(g, blk, sizes, nb, out, 4, s); }
         skip_le = 4;
     }
     hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
