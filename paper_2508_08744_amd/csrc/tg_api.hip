@@ -129,7 +129,7 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     }
     h->sm.blk = c.take<u32>((size_t)n * h->sm.BC);
     h->sm.bsz = c.take<u32>(n);
-    h->sm.wl = c.take<u32>((size_t)3 * n);
+    h->sm.wl = c.take<u64>((size_t)3 * n);
     h->sm.wl_cnt = c.take<u32>(4);
     h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(n));
     h->cd.C = p.C;

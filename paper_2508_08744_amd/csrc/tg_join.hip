@@ -84,7 +84,7 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
 template <int DK, int NGR, int NGC, int MODE>
 __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
-                                                            const int32_t* xsizes, float* xout, const u32* wl,
+                                                            const int32_t* xsizes, float* xout, const u64* wl,
                                                             const u32* wl_cnt, int64_t direct_count, int skip_le)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     for (int64_t w = blockIdx.x; w < count; w += gridDim.x) {
-    const int64_t v = wl ? (int64_t)wl[w] : w;
+    const int64_t v = wl ? (int64_t)(u32)wl[w] : w;
     int nN, nT;
     const u32* bids;
     if (MODE == 0) {
@@ -302,161 +302,234 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 // (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX, the q-th quarter
 // of row 16 t + r (column step s < 8 = four consecutive columns of that quarter).  Tile
 // (i, j) is then 32 v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s]: both operands use
-// the same column permutation, so the sum is the full dot product.  Retention is per 16 x 16 tile
-// (ng_row = 4, ng_col = 8), so every tile hands its survivors over at once.  Waves walk a
-// work list of anchors whose blocks have at most GMAX row groups.  MODE as in join_kernel.
+// the same column permutation, so the sum is the full dot product.  Retention is per
+// 16 x 16 tile (ng_row = 4, ng_col = 8), so every tile hands its survivors over at once.
+//
+// Waves walk a work list of anchors whose blocks have at most GMAX row groups, and the walk
+// is software pipelined: while block w is multiplied, the ids, thresholds and norms of block
+// w + 1 are fetched, and as soon as tile row i of block w is finished its registers X[i] are
+// refilled with row group i of block w + 1.  MODE as in join_kernel.
 // ---------------------------------------------------------------------------------------
-template <int GMAX, int MODE, int METRIC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GMAX <= 3 ? 3 : 2))) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
+struct WaveItem {
+    int64_t v;
+    const u32* bids;
+    int nN, nT, MT, NT;       // MT = NT = 0: nothing to do for this item
+};
+// work record: anchor | |NEW| << 32 | (|NEW|+|OLD|) << 40
+__device__ inline u64 pack_rec(u32 v, int nN, int nT) { return (u64)v | ((u64)nN << 32) | ((u64)nT << 40); }
+
+template <int GMAX, int MODE, int METRIC, int KS>
+__global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
                                                         const int32_t* xblk, const int32_t* xsizes, float* xout,
-                                                        const u32* wl, const u32* wl_cnt, int64_t direct_count, int gmin)
+                                                        const u64* __restrict__ wl, const u32* __restrict__ wl_cnt,
+                                                        int64_t direct_count, int gmin)
 {
-    __shared__ u32 sh_salt[4][64];
-    __shared__ float sh_kd[4][64];
-    __shared__ u32 sh_kid[4][64];
-    __shared__ int sh_ids[4][64];
-    __shared__ float sh_aux[4][64];
-    const int wave = threadIdx.x >> 6, lane = tg_lane();
-    u32* s_salt = sh_salt[wave];
-    float* s_kd = sh_kd[wave];
-    u32* s_kid = sh_kid[wave];
-    int* s_ids = sh_ids[wave];
-    float* s_aux = sh_aux[wave];
+    __shared__ u32 sh_salt[4][2][64];
+    __shared__ float sh_kd[4][2][64];
+    __shared__ u32 sh_kid[4][2][64];
+    __shared__ int sh_ids[4][2][64];
+    __shared__ float sh_aux[4][2][64];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     const float INF = __builtin_inff();
-    const int cw = (((g.ld + 3) >> 2) + 3) & ~3;     // columns per lane quarter, a multiple of 4
-    const int ksteps = cw >> 2;
+    constexpr int cw = 4 * KS;                       // columns per lane quarter: rows of at most 16 KS floats
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     const int64_t nwaves = (int64_t)gridDim.x * 4;
 
-    for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < count; w += nwaves) {
-        const int64_t v = wl ? (int64_t)wl[w] : w;
-        int nN, nT;
-        const u32* bids;
-        if (MODE == 0) {
-            const u32 z = sm.bsz[v];
-            nN = (int)(z & 0xFFu);
-            nT = (int)(z >> 8);
-            bids = sm.blk + v * (int64_t)sm.BC;
-        } else {
-            nN = xsizes[v * 2];
-            nT = nN + xsizes[v * 2 + 1];
-            bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
-        }
-        const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
-        if (nN == 0 || nT < 2 || NT > GMAX || NT < gmin) continue;
-
-        // the block's rows, straight into MFMA operand registers (rows past the block repeat
-        // row 0 and are masked in the epilogue).  Lane (r, q) owns the q-th quarter of row r:
-        // cw contiguous columns, so the four lanes of a row pull the whole row in at once.
-        float4 X[GMAX][8];
+    // A record past the end of the list becomes an empty block at anchor 0, so that every load
+    // below can be issued unconditionally (the load counters then stay exact and nothing has to
+    // wait for more than it needs).
+    auto load_rec = [&](int64_t w) -> u64 {
+        const int64_t wc = w < count ? w : count - 1;
+        u64 rec;
+        if (MODE == 0) rec = wl[wc];
+        else rec = pack_rec((u32)wc, xsizes[wc * 2], xsizes[wc * 2] + xsizes[wc * 2 + 1]);
+        return w < count ? rec : 0ull;
+    };
+    auto decode = [&](u64 rec) {
+        WaveItem it;
+        it.v = (int64_t)(u32)rec;
+        const int nN = (int)((rec >> 32) & 0xFFu), nT = (int)((rec >> 40) & 0xFFu);
+        it.bids = MODE == 0 ? sm.blk + it.v * (int64_t)sm.BC : reinterpret_cast<const u32*>(xblk) + it.v * TG_BLOCK_COLS;
+        const int NT = (nT + 15) >> 4;
+        const bool serve = nN > 0 && nT >= 2 && NT <= GMAX && NT >= gmin;
+        it.nN = serve ? nN : 0;
+        it.nT = serve ? nT : 0;
+        it.MT = serve ? (nN + 15) >> 4 : 0;
+        it.NT = serve ? NT : 0;
+        return it;
+    };
+    // ids of this lane's row in every group (rows past the block repeat row 0: they are masked later)
+    auto fetch_row_ids = [&](const WaveItem& it, u32 (&idr)[GMAX]) {
 #pragma unroll
         for (int t = 0; t < GMAX; ++t) {
             const int row = 16 * t + r16;
-            const u32 id = bids[(t < NT && row < nT) ? row : 0];
-            const float* x = g.X + (int64_t)id * g.ld + cw * q4;
+            idr[t] = it.bids[row < it.nT ? row : 0];
+        }
+    };
+    float4 X[GMAX][KS];
+    auto load_group = [&](int t, u32 id) {      // t is a compile-time constant at every call site
+        const float* x = g.X + (int64_t)id * g.ld;
 #pragma unroll
-            for (int s8 = 0; s8 < 8; ++s8) {
-                X[t][s8] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (t < NT && 4 * s8 < cw && cw * q4 + 4 * s8 < g.ld) X[t][s8] = *reinterpret_cast<const float4*>(x + 4 * s8);
+        for (int s8 = 0; s8 < KS; ++s8) {
+            // unconditional load at a clamped column, zeroed afterwards when the column is padding
+            const int col = cw * q4 + 4 * s8;
+            const bool real = col < g.ld;
+            const float4 val = *reinterpret_cast<const float4*>(x + (real ? col : 0));
+            X[t][s8] = real ? val : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    // per-member data (one member per lane): fetched into registers, parked in LDS one block ahead
+    auto park_member = [&](const WaveItem& it, int id, float aux, u64 kth, int buf) {
+        if (lane < it.nT) {
+            sh_ids[wave][buf][lane] = id;
+            sh_aux[wave][buf][lane] = aux;
+            if (MODE == 0) {
+                sh_kd[wave][buf][lane] = tg_unord((u32)(kth >> 32));
+                sh_kid[wave][buf][lane] = ((u32)kth) >> 2;
+                sh_salt[wave][buf][lane] = (u32)tg_mix64(hs_slot + (u64)id);
             }
         }
+    };
+
+    int64_t w = (int64_t)blockIdx.x * 4 + wave;
+    if (w >= count) return;
+    WaveItem cur = decode(load_rec(w));
+    WaveItem nxt = decode(load_rec(w + nwaves));
+    u64 rec2 = load_rec(w + 2 * nwaves);
+    u32 idn[GMAX];
+    int mid;
+    {
+        u32 idr[GMAX];
+        fetch_row_ids(cur, idr);
+#pragma unroll
+        for (int t = 0; t < GMAX; ++t) load_group(t, idr[t]);
+        const int m0 = (int)cur.bids[lane < cur.nT ? lane : 0];
+        park_member(cur, m0, METRIC == 2 ? g.rnorm[m0] : g.nrm[m0], MODE == 0 ? g.kth[m0] : 0ull, 0);
+        fetch_row_ids(nxt, idn);
+        mid = (int)nxt.bids[lane < nxt.nT ? lane : 0];
+    }
+    int buf = 0;
+
+    // In round w: block w is multiplied, the rows, norms and thresholds of block w + 1 are
+    // fetched (their ids came in one round earlier), and the ids of block w + 2 start travelling.
+    for (; w < count; w += nwaves) {
+        const WaveItem nxt2 = decode(rec2);
+        rec2 = load_rec(w + 3 * nwaves);
+        u32 idn2[GMAX];
+        fetch_row_ids(nxt2, idn2);
+        const int mid2 = (int)nxt2.bids[lane < nxt2.nT ? lane : 0];
+        float m_aux = 0.f;
+        u64 m_kth = 0;
+
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        if (lane < nT) {
-            const int id = (int)bids[lane];
-            s_ids[lane] = id;
-            s_aux[lane] = METRIC == 2 ? g.rnorm[id] : g.nrm[id];
-            if (MODE == 0) {
-                const u64 kth = g.kth[id];
-                s_kd[lane] = tg_unord((u32)(kth >> 32));
-                s_kid[lane] = ((u32)kth) >> 2;
-                s_salt[lane] = (u32)tg_mix64(hs_slot + (u64)id);
-            }
-        }
-        if (MODE == 0 && stat_bins && lane == 0) {
+        const u32* s_salt = sh_salt[wave][buf];
+        const float* s_kd = sh_kd[wave][buf];
+        const u32* s_kid = sh_kid[wave][buf];
+        const int* s_ids = sh_ids[wave][buf];
+        const float* s_aux = sh_aux[wave][buf];
+        const int64_t v = cur.v;
+        const int nN = cur.nN, nT = cur.nT, MT = cur.MT, NT = cur.NT;
+        if (MODE == 0 && stat_bins && lane == 0 && MT > 0) {
             const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
             atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
             atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)nT);
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
 
 #pragma unroll
         for (int i = 0; i < GMAX; ++i) {
-            if (i >= MT) continue;
-            // row side of this tile row: accumulator element e of lane (r16, q4) is row 16 i + 4 q4 + e
-            float aux_a[4], kd_a[4];
-            u32 id_a[4], kid_a[4];
-            bool a_ok[4];
+            if (i < MT) {
+                // row side of this tile row: accumulator element e of lane (r16, q4) is row 16 i + 4 q4 + e
+                float aux_a[4], kd_a[4];
+                u32 id_a[4], kid_a[4];
+                bool a_ok[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int a = 16 * i + 4 * q4 + e;
-                a_ok[e] = a < nN;
-                const int aa = a_ok[e] ? a : 0;
-                aux_a[e] = s_aux[aa];
-                id_a[e] = (u32)s_ids[aa];
-                kd_a[e] = MODE == 0 ? s_kd[aa] : 0.f;
-                kid_a[e] = MODE == 0 ? s_kid[aa] : 0u;
-            }
+                for (int e = 0; e < 4; ++e) {
+                    const int a = 16 * i + 4 * q4 + e;
+                    a_ok[e] = a < nN;
+                    const int aa = a_ok[e] ? a : 0;
+                    aux_a[e] = s_aux[aa];
+                    id_a[e] = (u32)s_ids[aa];
+                    kd_a[e] = MODE == 0 ? s_kd[aa] : 0.f;
+                    kid_a[e] = MODE == 0 ? s_kid[aa] : 0u;
+                }
 #pragma unroll
-            for (int j = i; j < GMAX; ++j) {
-                if (j >= NT) continue;
-                floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
+                for (int j = i; j < GMAX; ++j) {
+                    if (j >= NT) continue;
+                    floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s8 = 0; s8 < 8; ++s8) {
-                    if (s8 < ksteps) {
+                    for (int s8 = 0; s8 < KS; ++s8) {
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
                     }
-                }
-                // column side: lane (r16, .) is column 16 j + r16
-                const int b = 16 * j + r16;
-                const bool b_ok = b < nT;
-                const int bb = b_ok ? b : 0;
-                const float aux_b = s_aux[bb];
-                const u32 id_b = (u32)s_ids[bb];
-                const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
-                const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
-                float rbd[4], cbd = INF;
-                u32 rbi[4], cbi = TG_NO_ID;
-                bool any_r = false;
+                    // column side: lane (r16, .) is column 16 j + r16
+                    const int b = 16 * j + r16;
+                    const bool b_ok = b < nT;
+                    const int bb = b_ok ? b : 0;
+                    const float aux_b = s_aux[bb];
+                    const u32 id_b = (u32)s_ids[bb];
+                    const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
+                    const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
+                    float rbd[4], cbd = INF;
+                    u32 rbi[4], cbi = TG_NO_ID;
+                    bool any_r = false;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    // only the diagonal tile has pairs below the diagonal to mask
-                    const bool ok = b_ok & a_ok[e] & ((i != j) | (b > 16 * i + 4 * q4 + e));
-                    const float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b);
-                    if (MODE == 1) {
-                        if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
-                    } else {
-                        // b is a candidate of a and a of b, each only if it would precede the
-                        // last entry of the target's list
-                        const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
-                        const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
-                        rbd[e] = pr ? dist : INF;
-                        rbi[e] = pr ? id_b : TG_NO_ID;
-                        any_r |= pr;
-                        pairmin(cbd, cbi, pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
+                    for (int e = 0; e < 4; ++e) {
+                        // only the diagonal tile has pairs below the diagonal to mask
+                        const bool ok = b_ok & a_ok[e] & ((i != j) | (b > 16 * i + 4 * q4 + e));
+                        const float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b);
+                        if (MODE == 1) {
+                            if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
+                        } else {
+                            // b is a candidate of a and a of b, each only if it would precede the
+                            // last entry of the target's list
+                            const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
+                            const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
+                            rbd[e] = pr ? dist : INF;
+                            rbi[e] = pr ? id_b : TG_NO_ID;
+                            any_r |= pr;
+                            pairmin(cbd, cbi, pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
+                        }
                     }
-                }
-                if (MODE == 0) {
-                    if (__ballot(any_r)) {
+                    if (MODE == 0) {
+                        if (__ballot(any_r)) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
-                        const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
-                        const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
-                        if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, 16 * i + 4 * q4 + r16, md, mi);
-                    }
-                    if (__ballot(cbi != TG_NO_ID)) {
-                        pairmin(cbd, cbi, __shfl_xor(cbd, 16), (u32)__shfl_xor((int)cbi, 16));
-                        pairmin(cbd, cbi, __shfl_xor(cbd, 32), (u32)__shfl_xor((int)cbi, 32));
-                        if (q4 == 0 && cbi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, cbd, cbi);
+                            for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
+                            const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
+                            const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
+                            if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, 16 * i + 4 * q4 + r16, md, mi);
+                        }
+                        if (__ballot(cbi != TG_NO_ID)) {
+                            pairmin(cbd, cbi, __shfl_xor(cbd, 16), (u32)__shfl_xor((int)cbi, 16));
+                            pairmin(cbd, cbi, __shfl_xor(cbd, 32), (u32)__shfl_xor((int)cbi, 32));
+                            if (q4 == 0 && cbi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, cbd, cbi);
+                        }
                     }
                 }
             }
+            if (i == 0) {
+                // the next block's ids have arrived behind the first tile row: ask for its norms and thresholds
+                m_aux = METRIC == 2 ? g.rnorm[mid] : g.nrm[mid];
+                m_kth = MODE == 0 ? g.kth[mid] : 0ull;
+            }
+            // Row group i is used by tile rows min(i, MT - 1) and earlier: once tile row i is done
+            // (and it is not the last one) its registers can take in the next block.
+            if (i + 1 < MT) load_group(i, idn[i]);
         }
+        // whatever the last tile row still needed
+#pragma unroll
+        for (int i = 0; i < GMAX; ++i)
+            if (i + 1 >= MT) load_group(i, idn[i]);
+        park_member(nxt, mid, m_aux, m_kth, buf ^ 1);
+        cur = nxt;
+        nxt = nxt2;
+#pragma unroll
+        for (int t = 0; t < GMAX; ++t) idn[t] = idn2[t];
+        mid = mid2;
+        buf ^= 1;
     }
 }
 
@@ -470,10 +543,12 @@ __global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wa
     __shared__ u32 base[3];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t v = (int64_t)blockIdx.x * 256 + tid;
-    int bin = -1;
+    int bin = -1, rec_nN = 0, rec_nT = 0;
     if (v < n) {
         const u32 z = sm.bsz[v];
         const int nN = (int)(z & 0xFFu), nT = (int)(z >> 8);
+        rec_nN = nN;
+        rec_nT = nT;
         if (nN > 0 && nT >= 2) {
             const int NT = (nT + 15) >> 4;
             bin = !wave_ok ? 2 : NT <= 3 ? 0 : NT == 4 ? 1 : 2;
@@ -495,7 +570,7 @@ __global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wa
     if (bin >= 0) {
         u32 pos = base[bin] + mypos;
         for (int w2 = 0; w2 < wave; ++w2) pos += wcnt[bin][w2];
-        sm.wl[(int64_t)bin * n + pos] = (u32)v;
+        sm.wl[(int64_t)bin * n + pos] = pack_rec((u32)v, rec_nN, rec_nT);
     }
 }
 
@@ -519,7 +594,7 @@ static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c,
     const unsigned grid = (unsigned)(g.n < JOIN_GRID ? g.n : JOIN_GRID);
     hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
                        hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
-                       (const u32*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
+                       (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
 }
 static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
                            u64* stat_bins, hipStream_t s)
@@ -532,15 +607,34 @@ static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c
     else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
 
-template <int GMAX, int METRIC>
-static void launch_wave_m(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
+template <int GMAX, int METRIC, int KS>
+static void launch_wave_k(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
                           hipStream_t s)
 {
     const int64_t wgs = (g.n + 3) / 4;
     const unsigned grid = (unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID);
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
-                       (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u32*)(sm.wl + (int64_t)list * g.n),
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+                       (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
                        (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+}
+template <int GMAX, int METRIC, int KS>
+static void launch_wave_dump_k(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out, int gmin,
+                               hipStream_t s)
+{
+    TgSample sm = {};
+    TgCand c = {};
+    const int64_t wgs = (nb + 3) / 4;
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0,
+                       s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
+}
+// rows of at most 64 / 96 / 128 floats take 4 / 6 / 8 column steps per lane quarter
+template <int GMAX, int METRIC>
+static void launch_wave_m(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
+                          hipStream_t s)
+{
+    if (g.ld <= 64) launch_wave_k<GMAX, METRIC, 4>(g, sm, c, hs_slot, stat_bins, list, s);
+    else if (g.ld <= 96) launch_wave_k<GMAX, METRIC, 6>(g, sm, c, hs_slot, stat_bins, list, s);
+    else launch_wave_k<GMAX, METRIC, 8>(g, sm, c, hs_slot, stat_bins, list, s);
 }
 template <int GMAX>
 static void launch_wave_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list,
@@ -554,11 +648,9 @@ template <int GMAX, int METRIC>
 static void launch_wave_dump(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out, int gmin,
                              hipStream_t s)
 {
-    TgSample sm = {};
-    TgCand c = {};
-    const int64_t wgs = (nb + 3) / 4;
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0, s,
-                       g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr, (const u32*)nullptr, nb, gmin);
+    if (g.ld <= 64) launch_wave_dump_k<GMAX, METRIC, 4>(g, blk, sizes, nb, out, gmin, s);
+    else if (g.ld <= 96) launch_wave_dump_k<GMAX, METRIC, 6>(g, blk, sizes, nb, out, gmin, s);
+    else launch_wave_dump_k<GMAX, METRIC, 8>(g, blk, sizes, nb, out, gmin, s);
 }
 
 // The register-resident kernel applies to rows of at most 128 floats with per-tile retention.
@@ -592,6 +684,6 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
         skip_le = 4;
     }
     hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
-                       join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u32*)nullptr,
+                       join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
                        (const u32*)nullptr, nb, skip_le);
 }

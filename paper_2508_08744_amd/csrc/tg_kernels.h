@@ -31,7 +31,7 @@ struct TgSample {
     int32_t BC;               // row stride of blk: min(k, 2S) + 2R rounded up to 16
     uint32_t* blk;            // n x BC: this round's block of every anchor, NEW ids then OLD ids
     uint32_t* bsz;            // n: |NEW| | (|NEW|+|OLD|) << 8
-    uint32_t* wl;             // 3 x n: this round's join work lists (anchors by block size)
+    unsigned long long* wl;   // 3 x n: this round's join work lists (anchor | sizes, by block size)
     uint32_t* wl_cnt;         // 4: their lengths
     unsigned long long* scan_tmp; // block sums of the prefix sum
 };
