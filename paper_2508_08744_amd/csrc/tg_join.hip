@@ -32,13 +32,29 @@ __device__ inline u32 ror16_u(u32 x)
 }
 #define TG_NO_ID 0x7FFFFFFFu
 // minimum of (dist, id) pairs over the 16 lanes of a row; every lane gets the result
-__device__ inline void rowmin16(float& dist, u32& id)
+__device__ inline void rowmin16f(float& dist, u32& id)
 {
     float m = dist;
     m = fminf(m, ror16_f<8>(m));
     m = fminf(m, ror16_f<4>(m));
     m = fminf(m, ror16_f<2>(m));
     m = fminf(m, ror16_f<1>(m));
+    u32 c = dist == m ? id : TG_NO_ID;
+    c = min(c, ror16_u<8>(c));
+    c = min(c, ror16_u<4>(c));
+    c = min(c, ror16_u<2>(c));
+    c = min(c, ror16_u<1>(c));
+    dist = m;
+    id = c;
+}
+// the same on ordered distances (tg_ord: unsigned order = float order)
+__device__ inline void rowmin16(u32& dist, u32& id)
+{
+    u32 m = dist;
+    m = min(m, ror16_u<8>(m));
+    m = min(m, ror16_u<4>(m));
+    m = min(m, ror16_u<2>(m));
+    m = min(m, ror16_u<1>(m));
     u32 c = dist == m ? id : TG_NO_ID;
     c = min(c, ror16_u<8>(c));
     c = min(c, ror16_u<4>(c));
@@ -70,14 +86,14 @@ __device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
 // Candidate c of the member at block position tpos goes to slot
 // top_bits((c + salt) * K1, xorshift, * K2) of that member's slot row and stays if it is the
 // smaller (dist, id): one 64-bit atomic minimum, no order dependence.
-__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, float dist, u32 c)
+__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, u32 odist, u32 c)
 {
     const u32 t = (u32)s_ids[tpos];
     u32 h = (c + s_salt[tpos]) * 0x9E3779B1u;
     h ^= h >> 15;
     h *= 0x85EBCA77u;
     const u32 slot = h >> (33 - __ffs(cd.C));
-    atomicMin(cd.slots + (int64_t)t * cd.C + slot, tg_key(dist, c, 3u));
+    atomicMin(cd.slots + (int64_t)t * cd.C + slot, ((u64)odist << 32) | (u64)((c << 2) | 3u));
 }
 
 // MODE 0: emit candidates for the stored blocks.  MODE 1: write the distance tile of caller-given blocks.
@@ -268,11 +284,11 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
             }
             if (MODE == 0 && any) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
+                for (int e = 0; e < 4; ++e) rowmin16f(rbd[e], rbi[e]);
                 const float md = c16 == 0 ? rbd[0] : c16 == 1 ? rbd[1] : c16 == 2 ? rbd[2] : rbd[3];
                 const u32 mi = c16 == 0 ? rbi[0] : c16 == 1 ? rbi[1] : c16 == 2 ? rbi[2] : rbi[3];
                 const int a = 16 * i + 4 * g4 + c16;
-                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, md, mi);
+                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, tg_ord(md), mi);
             }
         }
     }
@@ -288,7 +304,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
                 pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
                 const int b = 16 * j + c16;
-                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, d0, i0);
+                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, tg_ord(d0), i0);
             }
         }
     }
@@ -325,7 +341,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                                                         int64_t direct_count, int gmin)
 {
     __shared__ u32 sh_salt[4][2][64];
-    __shared__ float sh_kd[4][2][64];
+    __shared__ u32 sh_okd[4][2][64];
     __shared__ u32 sh_kid[4][2][64];
     __shared__ int sh_ids[4][2][64];
     __shared__ float sh_aux[4][2][64];
@@ -385,7 +401,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
             sh_ids[wave][buf][lane] = id;
             sh_aux[wave][buf][lane] = aux;
             if (MODE == 0) {
-                sh_kd[wave][buf][lane] = tg_unord((u32)(kth >> 32));
+                sh_okd[wave][buf][lane] = (u32)(kth >> 32);
                 sh_kid[wave][buf][lane] = ((u32)kth) >> 2;
                 sh_salt[wave][buf][lane] = (u32)tg_mix64(hs_slot + (u64)id);
             }
@@ -425,7 +441,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const u32* s_salt = sh_salt[wave][buf];
-        const float* s_kd = sh_kd[wave][buf];
+        const u32* s_okd = sh_okd[wave][buf];
         const u32* s_kid = sh_kid[wave][buf];
         const int* s_ids = sh_ids[wave][buf];
         const float* s_aux = sh_aux[wave][buf];
@@ -440,20 +456,25 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 #pragma unroll
         for (int i = 0; i < GMAX; ++i) {
             if (i < MT) {
-                // row side of this tile row: accumulator element e of lane (r16, q4) is row 16 i + 4 q4 + e
-                float aux_a[4], kd_a[4];
-                u32 id_a[4], kid_a[4];
-                bool a_ok[4];
+                // Row side of this tile row: accumulator element e of lane (r16, q4) is row
+                // a = 16 i + 4 q4 + e.  Everything below works on "ordered" distances (tg_ord:
+                // unsigned order = float order); a pair that must not count gets +inf added, so
+                // no validity masks have to be carried around.
+                float aux_a[4], pen_a[4];
+                u32 id_a[4], okd_max = 0u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int a = 16 * i + 4 * q4 + e;
-                    a_ok[e] = a < nN;
-                    const int aa = a_ok[e] ? a : 0;
+                    const int aa = a < nN ? a : 0;
                     aux_a[e] = s_aux[aa];
                     id_a[e] = (u32)s_ids[aa];
-                    kd_a[e] = MODE == 0 ? s_kd[aa] : 0.f;
-                    kid_a[e] = MODE == 0 ? s_kid[aa] : 0u;
+                    pen_a[e] = a < nN ? 0.f : INF;
+                    if (MODE == 0) okd_max = max(okd_max, s_okd[aa]);
                 }
+                // the lane that will speak for row 16 i + 4 q4 + (r16 & 3) keeps that row's threshold
+                const int a_mine = 16 * i + 4 * q4 + (r16 & 3);
+                const u32 okd_mine = MODE == 0 ? s_okd[a_mine < nN ? a_mine : 0] : 0u;
+                const u32 kid_mine = MODE == 0 ? s_kid[a_mine < nN ? a_mine : 0] : 0u;
 #pragma unroll
                 for (int j = i; j < GMAX; ++j) {
                     if (j >= NT) continue;
@@ -465,48 +486,53 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
                     }
-                    // column side: lane (r16, .) is column 16 j + r16
+                    // column side: lane (r16, .) is column b = 16 j + r16
                     const int b = 16 * j + r16;
-                    const bool b_ok = b < nT;
-                    const int bb = b_ok ? b : 0;
+                    const int bb = b < nT ? b : 0;
                     const float aux_b = s_aux[bb];
                     const u32 id_b = (u32)s_ids[bb];
-                    const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
-                    const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
-                    float rbd[4], cbd = INF;
-                    u32 rbi[4], cbi = TG_NO_ID;
-                    bool any_r = false;
+                    const float pen_b = b < nT ? 0.f : INF;
+                    u32 o[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        // only the diagonal tile has pairs below the diagonal to mask
-                        const bool ok = b_ok & a_ok[e] & ((i != j) | (b > 16 * i + 4 * q4 + e));
-                        const float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b);
+                        float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b) + (pen_a[e] + pen_b);
+                        // only the diagonal tile has pairs on or below the diagonal to drop
+                        if (i == j) dist += (r16 > 4 * q4 + e) ? 0.f : INF;
                         if (MODE == 1) {
-                            if (ok) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
-                        } else {
-                            // b is a candidate of a and a of b, each only if it would precede the
-                            // last entry of the target's list
-                            const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
-                            const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
-                            rbd[e] = pr ? dist : INF;
-                            rbi[e] = pr ? id_b : TG_NO_ID;
-                            any_r |= pr;
-                            pairmin(cbd, cbi, pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
+                            if (dist < INF) xout[((int64_t)v * TG_BLOCK_ROWS + 16 * i + 4 * q4 + e) * TG_BLOCK_COLS + b] = dist;
                         }
+                        o[e] = METRIC == 0 ? (__float_as_uint(dist) | 0x80000000u) : tg_ord(dist);
                     }
                     if (MODE == 0) {
-                        if (__ballot(any_r)) {
+                        const u32 okd_b = s_okd[bb];
+                        // nothing in this tile can precede any threshold: the common case in late rounds
+                        const u32 omin = min(min(o[0], o[1]), min(o[2], o[3]));
+                        if (__ballot(omin <= max(okd_max, okd_b)) == 0) continue;
+                        // Row nodes: closest column node of the tile for each of the lane's four rows,
+                        // reduced over the 16 lanes of the row group; then one threshold test by the
+                        // lane that speaks for the row (if the closest fails, every other pair fails).
+                        u32 ro[4], ri[4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) rowmin16(rbd[e], rbi[e]);
-                            const float md = r16 == 0 ? rbd[0] : r16 == 1 ? rbd[1] : r16 == 2 ? rbd[2] : rbd[3];
-                            const u32 mi = r16 == 0 ? rbi[0] : r16 == 1 ? rbi[1] : r16 == 2 ? rbi[2] : rbi[3];
-                            if (r16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, 16 * i + 4 * q4 + r16, md, mi);
+                        for (int e = 0; e < 4; ++e) {
+                            ro[e] = o[e];
+                            ri[e] = id_b;
+                            rowmin16(ro[e], ri[e]);
                         }
-                        if (__ballot(cbi != TG_NO_ID)) {
-                            pairmin(cbd, cbi, __shfl_xor(cbd, 16), (u32)__shfl_xor((int)cbi, 16));
-                            pairmin(cbd, cbi, __shfl_xor(cbd, 32), (u32)__shfl_xor((int)cbi, 32));
-                            if (q4 == 0 && cbi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, cbd, cbi);
-                        }
+                        const int e_mine = r16 & 3;
+                        const u32 mo = e_mine == 0 ? ro[0] : e_mine == 1 ? ro[1] : e_mine == 2 ? ro[2] : ro[3];
+                        const u32 mi = e_mine == 0 ? ri[0] : e_mine == 1 ? ri[1] : e_mine == 2 ? ri[2] : ri[3];
+                        if (r16 < 4 && ((mo < okd_mine) | ((mo == okd_mine) & (mi < kid_mine))))
+                            emit_candidate(cd, s_ids, s_salt, a_mine, mo, mi);
+                        // Column node b: closest row node of the tile, over the lane's four rows and
+                        // then over the four row quarters.
+                        u64 cb = ((u64)o[0] << 32) | id_a[0];
+#pragma unroll
+                        for (int e = 1; e < 4; ++e) cb = tg_min64(cb, ((u64)o[e] << 32) | id_a[e]);
+                        cb = tg_min64(cb, tg_shfl_xor64(cb, 16));
+                        cb = tg_min64(cb, tg_shfl_xor64(cb, 32));
+                        const u32 co = (u32)(cb >> 32), ci = (u32)cb;
+                        if (q4 == 0 && ((co < okd_b) | ((co == okd_b) & (ci < s_kid[bb]))))
+                            emit_candidate(cd, s_ids, s_salt, b, co, ci);
                     }
                 }
             }
