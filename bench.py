@@ -106,6 +106,14 @@ def main():
     gather_gbs = (4.0 * d * sum(sum(s["join_vectors"][:r1]) for s in stats) / max(launches, 1)) / (avg_launch_ms * 1e-3) / 1e9 \
         if avg_launch_ms > 0 else 0.0
     last = stats[-1]
+    # HBM bytes per join launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/ (calibrated
+    # against a plain copy); only quoted for the workload those runs were made on
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "join_C2_1Mx128_k32_hbm_traffic.txt")
+    if args.config == "C2" and n == cfg["n"] and os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("join_traffic_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
     out = {
         "metric": "k-NN graph build points/sec at recall@32>=0.95 (1Mx128 fp32); join MFMA %",
         "value": n / (ms_per_step * 1e-3),
@@ -125,10 +133,11 @@ def main():
         "recall_at_k": recall,
         "recall_ok": bool(recall >= 0.95),
         "join_mfma_pct": 100.0 * achieved / MFMA_FP32_PEAK_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "join_kernel (phase-1 local join)", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": "phase-1 local join (join_wave_kernel<3>, <4> and join_kernel of one round)",
+                     "achieved": achieved,
                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK_TFLOPS,
                      "avg_launch_ms": avg_launch_ms, "launches": launches, "gather_GBps": gather_gbs,
-                     "traffic": None},
+                     "hbm_gather_frac": gather_gbs / HBM_PEAK_GBS, "traffic": traffic},
         "breakdown_ms": {"norms": last["ms_norms"], "init": last["ms_init"], "finalize": last["ms_finalize"],
                          "sample": sum(last["ms_sample"]), "join": sum(last["ms_join"][:r1]),
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
