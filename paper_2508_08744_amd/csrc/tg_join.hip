@@ -315,10 +315,11 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 // ---------------------------------------------------------------------------------------
 // Register-resident variant for small blocks and d <= 128: one wave per anchor, no LDS tile
 // and no barrier.  The wave keeps the whole block in VGPRs in MFMA operand layout: lane
-// (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX, the q-th quarter
-// of row 16 t + r (column step s < 8 = four consecutive columns of that quarter).  Tile
-// (i, j) is then 32 v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s]: both operands use
-// the same column permutation, so the sum is the full dot product.  Retention is per
+// (r, q) = (lane % 16, lane / 16) holds, for every 16-row group t < GMAX and column step
+// s < KS, columns 16 s + 4 q .. + 3 of row 16 t + r, so that one load instruction reads 64
+// contiguous bytes of each of 16 rows (a step-major split would touch four lines per row).
+// Tile (i, j) is then 4 KS v_mfma_f32_16x16x4_f32 on registers X[i][s], X[j][s]: both operands
+// use the same column permutation, so the sum is the full dot product.  Retention is per
 // 16 x 16 tile (ng_row = 4, ng_col = 8), so every tile hands its survivors over at once.
 //
 // Waves walk a work list of anchors whose blocks have at most GMAX row groups, and the walk
@@ -348,7 +349,6 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     const float INF = __builtin_inff();
-    constexpr int cw = 4 * KS;                       // columns per lane quarter: rows of at most 16 KS floats
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     const int64_t nwaves = (int64_t)gridDim.x * 4;
 
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 #pragma unroll
         for (int s8 = 0; s8 < KS; ++s8) {
             // unconditional load at a clamped column, zeroed afterwards when the column is padding
-            const int col = cw * q4 + 4 * s8;
+            const int col = 16 * s8 + 4 * q4;
             const bool real = col < g.ld;
             const float4 val = *reinterpret_cast<const float4*>(x + (real ? col : 0));
             X[t][s8] = real ? val : make_float4(0.f, 0.f, 0.f, 0.f);

@@ -93,10 +93,65 @@ void tg_launch_norms(const TgGraph& g, hipStream_t s)
 // ---------------------------------------------------------------------------------------
 // Distances from node v (its vector staged in LDS at xs, ld floats) to one candidate id per
 // lane (cid < 0: none), computed directly from the vectors: sum (x-y)^2, -<x,y> or
-// 1 - <x,y>/(|x||y|).  16 lanes share one candidate row, so the wave works on 4 rows at a
-// time; candidates are compacted first so that only live rows are fetched.
+// 1 - <x,y>/(|x||y|).  Candidates are compacted first so that only live rows are fetched.
+// 16 lanes share one candidate row; a pass covers 32 candidates (8 per lane quarter) and
+// 128 columns, with all 16 row loads of a lane in flight before the first is used: the wave
+// is latency bound, so the number of dependent round trips is what counts.
 // wscr: 128 words of LDS private to this wave.
 // ---------------------------------------------------------------------------------------
+template <int N>
+__device__ inline float row16_ror(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xF, 0xF, false));
+}
+template <bool L2>
+__device__ inline void direct_pass(const float* X, int ld, const float* xs, const u32* wscr, int p0, int nv, float (&acc)[8])
+{
+    const int lane = tg_lane();
+    const int grp = lane >> 4, sub = lane & 15;
+    const float* y[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int p = p0 + 4 * q + grp;
+        y[q] = X + (int64_t)wscr[p < nv ? p : nv - 1] * ld;   // rows past the end repeat the last one
+        acc[q] = 0.0f;
+    }
+    for (int cb = 0; cb < ld; cb += 128) {
+        // two column chunks per pass; a chunk past the row is read at column 0 and not counted
+        const int c0 = cb + 4 * sub, c1 = c0 + 64;
+        const bool r0 = c0 < ld, r1 = c1 < ld;
+        const int cc0 = r0 ? c0 : 0, cc1 = r1 ? c1 : 0;
+        float4 b0[8], b1[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            b0[q] = *reinterpret_cast<const float4*>(y[q] + cc0);
+            b1[q] = *reinterpret_cast<const float4*>(y[q] + cc1);
+        }
+        const float4 a0 = *reinterpret_cast<const float4*>(xs + cc0);
+        const float4 a1 = *reinterpret_cast<const float4*>(xs + cc1);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float s0, s1;
+            if (L2) {
+                const float t0 = a0.x - b0[q].x, t1 = a0.y - b0[q].y, t2 = a0.z - b0[q].z, t3 = a0.w - b0[q].w;
+                const float u0 = a1.x - b1[q].x, u1 = a1.y - b1[q].y, u2 = a1.z - b1[q].z, u3 = a1.w - b1[q].w;
+                s0 = t0 * t0 + t1 * t1 + t2 * t2 + t3 * t3;
+                s1 = u0 * u0 + u1 * u1 + u2 * u2 + u3 * u3;
+            } else {
+                s0 = a0.x * b0[q].x + a0.y * b0[q].y + a0.z * b0[q].z + a0.w * b0[q].w;
+                s1 = a1.x * b1[q].x + a1.y * b1[q].y + a1.z * b1[q].z + a1.w * b1[q].w;
+            }
+            acc[q] += (r0 ? s0 : 0.0f) + (r1 ? s1 : 0.0f);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        acc[q] += row16_ror<8>(acc[q]);
+        acc[q] += row16_ror<4>(acc[q]);
+        acc[q] += row16_ror<2>(acc[q]);
+        acc[q] += row16_ror<1>(acc[q]);
+    }
+}
 __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, float rn_v, int cid, u32* wscr)
 {
     const int lane = tg_lane();
@@ -109,36 +164,19 @@ __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, floa
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     float* wd = reinterpret_cast<float*>(wscr + 64);
-    for (int p0 = 0; p0 < nv; p0 += 4) {
-        const int p = p0 + grp;
-        float acc = 0.0f;
-        int c = -1;
-        if (p < nv) {
-            c = (int)wscr[p];
-            const float* y = g.X + (int64_t)c * g.ld;
-            if (g.metric == 0) {
-                for (int col = sub * 4; col < g.ld; col += 64) {
-                    float4 a = *reinterpret_cast<const float4*>(xs + col);
-                    float4 b = *reinterpret_cast<const float4*>(y + col);
-                    float t0 = a.x - b.x, t1 = a.y - b.y, t2 = a.z - b.z, t3 = a.w - b.w;
-                    acc += t0 * t0 + t1 * t1 + t2 * t2 + t3 * t3;
-                }
-            } else {
-                for (int col = sub * 4; col < g.ld; col += 64) {
-                    float4 a = *reinterpret_cast<const float4*>(xs + col);
-                    float4 b = *reinterpret_cast<const float4*>(y + col);
-                    acc += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
-                }
-            }
-        }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
-        acc += __shfl_xor(acc, 8);
-        if (p < nv && sub == 0) {
-            float dist = acc;
-            if (g.metric == 1) dist = -acc;
-            else if (g.metric == 2) dist = 1.0f - acc * rn_v * g.rnorm[c];
+    for (int p0 = 0; p0 < nv; p0 += 32) {
+        float acc[8];
+        if (g.metric == 0) direct_pass<true>(g.X, g.ld, xs, wscr, p0, nv, acc);
+        else direct_pass<false>(g.X, g.ld, xs, wscr, p0, nv, acc);
+        // lane `sub` of each quarter speaks for candidate p0 + 4 sub + grp (sub < 8)
+        float mine = acc[0];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) mine = sub == q ? acc[q] : mine;
+        const int p = p0 + 4 * sub + grp;
+        if (sub < 8 && p < nv) {
+            float dist = mine;
+            if (g.metric == 1) dist = -mine;
+            else if (g.metric == 2) dist = 1.0f - mine * rn_v * g.rnorm[wscr[p]];
             wd[p] = dist;
         }
     }
@@ -291,7 +329,9 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 // Algorithm 1 lines 9-12, one wave per node v: take the first m unvisited entries u of
 // G[v], mark them visited, read G[u] from the lists as they stood when the round began
 // (g.gid; this round writes g.gid_next), measure v against the ids that are neither v nor
-// listed, and merge them into G[v].  One candidate per lane: k <= 64.
+// listed nor met earlier in this round, and merge them into G[v].
+// floor(64 / k) neighbour lists are handled per pass, one candidate per lane (k <= 64), so
+// the usual m = 2, k <= 32 round is one gather of ids, one of vectors, one sort, one merge.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, u64* updates, u64* stat_bins)
 {
@@ -302,6 +342,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
     const int k = g.k;
     float* xs = smem + (size_t)wave * g.ld;
     u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+    u32* hist = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + LISTS_WAVES * 128 + wave * (m * k);
 
     u32 w = 0;
     float dist = 0.0f;
@@ -309,27 +350,48 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
+    stage_row(g, v, xs);
     u32 fresh = w >> 31;
     u64 mf = __ballot(lane < k && fresh);
     if (fresh && __popcll(mf & tg_lanemask_lt()) < m) fresh = 0;   // non-revisitation
     u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
+    const u64 L0 = L;                                              // the list as the round found it
     const u32 my_id = w & TG_ID_MASK;
     const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
     const int nexp = min(m, __popcll(mf));
-    if (nexp > 0) stage_row(g, v, xs);
+    const int per = 64 / k;
 
-    int evaluated = 0;
-    for (int e = 0; e < nexp; ++e) {
-        const int src = __ffsll((long long)mf) - 1;
-        mf &= mf - 1;
-        const u32 u = (u32)__builtin_amdgcn_readlane((int)my_id, src);
-        int cid = -1;
-        if (lane < k) cid = (int)(g.gid[(int64_t)u * k + lane] & TG_ID_MASK);
-        const bool listed = id_in_list((u32)cid, L, k);  // all lanes take part
-        if (cid == (int)v || listed) cid = -1;
-        evaluated += __popcll(__ballot(cid >= 0));
-        const float cdist = wave_direct_dist(g, xs, rn_v, cid, wscr);
-        u64 ck = cid >= 0 ? tg_key(cdist, (u32)cid, 3u) : TG_EMPTY_KEY;
+    int evaluated = 0, nhist = 0;
+    for (int e0 = 0; e0 < nexp; e0 += per) {
+        const int nb = min(per, nexp - e0);
+        const int my_e = lane / k, j = lane - my_e * k;
+        const bool in = my_e < nb;
+        int src = 0;
+        for (int q = 0; q < nb; ++q) {
+            const int sbit = __ffsll((long long)mf) - 1;
+            mf &= mf - 1;
+            if (q == my_e) src = sbit;
+        }
+        const u32 u = (u32)__shfl((int)my_id, src);
+        u32 cid = in ? (g.gid[(int64_t)u * k + j] & TG_ID_MASK) : 0xFFFFFFFFu;
+        bool drop = !in || cid == (u32)v;
+        drop |= id_in_list(cid, L0, k);                            // all lanes take part
+        for (int q = 0; q < (nb - 1) * k; ++q) {                   // the same id from an earlier list of this pass
+            const u32 cq = (u32)__builtin_amdgcn_readlane((int)cid, q);
+            drop |= (q < my_e * k) & (cq == cid);
+        }
+        for (int q = 0; q < nhist; ++q) drop |= (hist[q] == cid);  // ... or of an earlier pass
+        const u64 live = __ballot(!drop);
+        const int nlive = __popcll(live);
+        evaluated += nlive;
+        if (e0 + per < nexp) {
+            if (!drop) hist[nhist + __popcll(live & tg_lanemask_lt())] = cid;
+            nhist += nlive;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        const float cdist = wave_direct_dist(g, xs, rn_v, drop ? -1 : (int)cid, wscr);
+        u64 ck = drop ? TG_EMPTY_KEY : tg_key(cdist, cid, 3u);
         ck = tg_wave_sort(ck);
         L = tg_wave_merge_low(L, ck);
         if (lane >= k) L = TG_EMPTY_KEY;
@@ -350,7 +412,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
 }
 void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
 {
-    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
+    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)m * g.k) * sizeof(u32);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
     hipLaunchKernelGGL(phase2_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, updates, stat_bins);
 }
