@@ -57,6 +57,10 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *   seed     seed of every random decision (initial lists, reverse sampling, slots)
  *   finalize 1: recompute the reported distances directly from the vectors and
  *            re-sort each list before writing the outputs
+ *   screen   1: a phase-2 round first bounds every candidate's distance from below on an
+ *            8-bit copy of the vectors (n x (d + 47) bytes of workspace) and measures in fp32
+ *            only those that may still enter the list; the bound is rigorous, so the graph is
+ *            the same as with 0, which measures every candidate (section 4.1 as written)
  */
 typedef struct tg_knn_params {
     int32_t k;
@@ -67,6 +71,7 @@ typedef struct tg_knn_params {
     int32_t m;
     float delta;
     int32_t finalize;
+    int32_t screen;
     uint64_t seed;
 } tg_knn_params;
 
@@ -76,7 +81,7 @@ typedef struct tg_knn_params {
 typedef struct tg_knn_stats {
     int32_t rounds_phase1, rounds_phase2;
     int64_t updates[TG_MAX_ROUNDS];      /* list entries replaced in round r (both phases, in order) */
-    float ms_norms, ms_init, ms_finalize;
+    float ms_norms, ms_init, ms_finalize; /* ms_norms: norms plus the 8-bit screening copy (screen = 1) */
     float ms_sample[TG_MAX_ROUNDS];      /* reverse-sample build of round r (phase 1)               */
     float ms_join[TG_MAX_ROUNDS];        /* local join (phase 1) or expand+update (phase 2)         */
     float ms_update[TG_MAX_ROUNDS];      /* list update kernel (phase 1)                            */
@@ -88,7 +93,7 @@ typedef struct tg_knn_handle tg_knn_handle;
 
 /* Defaults for a given k and total round budget: it1 = ceil(iters/2), it2 = iters - it1
  * (section 7.3: it1 = it2), S = min(k,32), R = 32, C = 64, ng_row = 4, ng_col = 8, m = 2,
- * delta = 0, finalize = 1, seed = 1.  iters <= 0 selects 16 rounds with delta = 0.001. */
+ * delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with delta = 0.001. */
 int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);
 
 /* Device bytes a build of this size needs as workspace. 0 if the arguments are invalid. */

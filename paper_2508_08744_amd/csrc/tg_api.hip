@@ -45,6 +45,7 @@ static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
     if (p->ng_col != 2 && p->ng_col != 4 && p->ng_col != 8) return fail(TG_ERR_INVALID_ARG, "ng_col = %d must be 2, 4 or 8", p->ng_col);
     if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);
     if (!(p->delta >= 0.0f && p->delta < 1.0f)) return fail(TG_ERR_INVALID_ARG, "delta must be in [0, 1)");
+    if (p->screen != 0 && p->screen != 1) return fail(TG_ERR_INVALID_ARG, "screen = %d must be 0 or 1", p->screen);
     return TG_OK;
 }
 
@@ -65,6 +66,7 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->ng_col = 8;
     p->m = 2;
     p->finalize = 1;
+    p->screen = 1;
     p->seed = 1;
     return TG_OK;
 }
@@ -91,6 +93,7 @@ struct tg_knn_handle {
     u64* d_updates;      // TG_MAX_ROUNDS x TG_STAT_BINS partial counters (spread to avoid one hot address)
     u64* d_stat_bins;    // TG_MAX_ROUNDS x 2 x TG_STAT_BINS
     float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
+    uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -119,6 +122,9 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.gid_next = c.take<u32>((size_t)n * p.k);
     h->g.gdist = c.take<float>((size_t)n * p.k);
     h->g.kth = c.take<u64>(n);
+    h->g.ldq = ((d + 15) & ~15) + 32;
+    h->xq = p.screen ? c.take<uint8_t>((size_t)n * h->g.ldq) : nullptr;
+    h->g.Xq = h->xq;
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);
     h->sm.off = c.take<u64>(n + 1);
@@ -277,6 +283,12 @@ extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     tg_launch_mark_all_fresh(h->g, h->stream);
+    if (!h->phase2 && h->xq) {
+        ensure_norms(h);
+        int sp = begin_span(h, SPAN_NORMS, 0);
+        tg_launch_quantize(h->g, h->xq, h->stream);
+        end_span(h, sp);
+    }
     h->phase2 = true;
     return launch_status("phase switch");
 }

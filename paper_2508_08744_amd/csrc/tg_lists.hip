@@ -91,12 +91,85 @@ void tg_launch_norms(const TgGraph& g, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------------
+// 8-bit screening copy of X for phase 2.  Row x becomes codes q_i = round((x_i - lo) / s) in
+// 0..255 with lo = min x_i, s = (max x_i - lo) / 255, i.e. the vector xq_i = lo + s q_i, and
+// eight row constants: lo, s, err >= |x - xq|, sum q_i, |xq|^2, sum (|lo| + s q_i)^2,
+// 1/|x| (cosine) and a spare.  With them <xq, yq> follows from the integer dot product of
+// the codes, and |x - y| >= |xq - yq| - err_x - err_y bounds the true distance from below.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq)
+{
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int sub = threadIdx.x & 15;
+    const bool live = row < g.n;
+    const float* x = g.X + (live ? row : 0) * (int64_t)g.ld;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    for (int c = sub * 4; c < g.ld; c += 64) {
+        const float4 v = *reinterpret_cast<const float4*>(x + c);
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (c + i < g.d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }
+    }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, o));
+        hi = fmaxf(hi, __shfl_xor(hi, o));
+    }
+    const float s = hi > lo ? (hi - lo) / 255.0f : 1.0f;
+    const float inv = 1.0f / s;
+    const float alo = fabsf(lo);
+    const int dq = g.ldq - 32;
+    uint8_t* out = Xq + (live ? row : 0) * (int64_t)g.ldq;
+    float err2 = 0.0f, qn2 = 0.0f, an2 = 0.0f, sumq = 0.0f;
+    for (int c = sub * 4; c < dq; c += 64) {
+        u32 packed = 0u;
+        if (c < g.ld) {
+            const float4 v = *reinterpret_cast<const float4*>(x + c);
+            const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (c + i < g.d) {
+                    const float q = fminf(255.0f, fmaxf(0.0f, rintf((e[i] - lo) * inv)));
+                    const float r = fmaf(s, q, lo);
+                    const float t = e[i] - r, a = fmaf(s, q, alo);
+                    err2 = fmaf(t, t, err2);
+                    qn2 = fmaf(r, r, qn2);
+                    an2 = fmaf(a, a, an2);
+                    sumq += q;
+                    packed |= (u32)q << (8 * i);
+                }
+            }
+        }
+        if (live) *reinterpret_cast<u32*>(out + c) = packed;
+    }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+        err2 += __shfl_xor(err2, o);
+        qn2 += __shfl_xor(qn2, o);
+        an2 += __shfl_xor(an2, o);
+        sumq += __shfl_xor(sumq, o);
+    }
+    if (live && sub == 0) {
+        float4* m = reinterpret_cast<float4*>(out + dq);
+        m[0] = make_float4(lo, s, sqrtf(err2) * 1.0001f, sumq);
+        m[1] = make_float4(qn2, an2, g.metric == 2 ? g.rnorm[row] : 0.0f, 0.0f);
+    }
+}
+void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, hipStream_t s)
+{
+    int64_t blocks = (g.n + 15) / 16;
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g, Xq);
+}
+
+// ---------------------------------------------------------------------------------------
 // Distances from node v (its vector staged in LDS at xs, ld floats) to one candidate id per
 // lane (cid < 0: none), computed directly from the vectors: sum (x-y)^2, -<x,y> or
 // 1 - <x,y>/(|x||y|).  Candidates are compacted first so that only live rows are fetched.
-// 16 lanes share one candidate row; a pass covers 32 candidates (8 per lane quarter) and
-// 128 columns, with all 16 row loads of a lane in flight before the first is used: the wave
-// is latency bound, so the number of dependent round trips is what counts.
+// 16 lanes share one candidate row; a pass covers 4 NB candidates (NB per lane quarter) and
+// 128 columns, with all 2 NB row loads of a lane in flight before the first is used: the wave
+// is latency bound, so the number of dependent round trips is what counts.  NB = 8 suits
+// full lists (initial lists, finalize), NB = 1 the few survivors of the phase-2 screening.
 // wscr: 128 words of LDS private to this wave.
 // ---------------------------------------------------------------------------------------
 template <int N>
@@ -104,14 +177,14 @@ __device__ inline float row16_ror(float x)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xF, 0xF, false));
 }
-template <bool L2>
-__device__ inline void direct_pass(const float* X, int ld, const float* xs, const u32* wscr, int p0, int nv, float (&acc)[8])
+template <bool L2, int NB>
+__device__ inline void direct_pass(const float* X, int ld, const float* xs, const u32* wscr, int p0, int nv, float (&acc)[NB])
 {
     const int lane = tg_lane();
     const int grp = lane >> 4, sub = lane & 15;
-    const float* y[8];
+    const float* y[NB];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < NB; ++q) {
         const int p = p0 + 4 * q + grp;
         y[q] = X + (int64_t)wscr[p < nv ? p : nv - 1] * ld;   // rows past the end repeat the last one
         acc[q] = 0.0f;
@@ -121,16 +194,16 @@ __device__ inline void direct_pass(const float* X, int ld, const float* xs, cons
         const int c0 = cb + 4 * sub, c1 = c0 + 64;
         const bool r0 = c0 < ld, r1 = c1 < ld;
         const int cc0 = r0 ? c0 : 0, cc1 = r1 ? c1 : 0;
-        float4 b0[8], b1[8];
+        float4 b0[NB], b1[NB];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < NB; ++q) {
             b0[q] = *reinterpret_cast<const float4*>(y[q] + cc0);
             b1[q] = *reinterpret_cast<const float4*>(y[q] + cc1);
         }
         const float4 a0 = *reinterpret_cast<const float4*>(xs + cc0);
         const float4 a1 = *reinterpret_cast<const float4*>(xs + cc1);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < NB; ++q) {
             float s0, s1;
             if (L2) {
                 const float t0 = a0.x - b0[q].x, t1 = a0.y - b0[q].y, t2 = a0.z - b0[q].z, t3 = a0.w - b0[q].w;
@@ -145,13 +218,14 @@ __device__ inline void direct_pass(const float* X, int ld, const float* xs, cons
         }
     }
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < NB; ++q) {
         acc[q] += row16_ror<8>(acc[q]);
         acc[q] += row16_ror<4>(acc[q]);
         acc[q] += row16_ror<2>(acc[q]);
         acc[q] += row16_ror<1>(acc[q]);
     }
 }
+template <int NB>
 __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, float rn_v, int cid, u32* wscr)
 {
     const int lane = tg_lane();
@@ -164,16 +238,16 @@ __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, floa
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     float* wd = reinterpret_cast<float*>(wscr + 64);
-    for (int p0 = 0; p0 < nv; p0 += 32) {
-        float acc[8];
-        if (g.metric == 0) direct_pass<true>(g.X, g.ld, xs, wscr, p0, nv, acc);
-        else direct_pass<false>(g.X, g.ld, xs, wscr, p0, nv, acc);
-        // lane `sub` of each quarter speaks for candidate p0 + 4 sub + grp (sub < 8)
+    for (int p0 = 0; p0 < nv; p0 += 4 * NB) {
+        float acc[NB];
+        if (g.metric == 0) direct_pass<true, NB>(g.X, g.ld, xs, wscr, p0, nv, acc);
+        else direct_pass<false, NB>(g.X, g.ld, xs, wscr, p0, nv, acc);
+        // lane `sub` of each quarter speaks for candidate p0 + 4 sub + grp (sub < NB)
         float mine = acc[0];
 #pragma unroll
-        for (int q = 1; q < 8; ++q) mine = sub == q ? acc[q] : mine;
+        for (int q = 1; q < NB; ++q) mine = sub == q ? acc[q] : mine;
         const int p = p0 + 4 * sub + grp;
-        if (sub < 8 && p < nv) {
+        if (sub < NB && p < nv) {
             float dist = mine;
             if (g.metric == 1) dist = -mine;
             else if (g.metric == 2) dist = 1.0f - mine * rn_v * g.rnorm[wscr[p]];
@@ -186,6 +260,98 @@ __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, floa
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     return out;
+}
+
+// ---------------------------------------------------------------------------------------
+// Screening for phase 2: of one candidate id per lane (cid < 0: none) keep those whose
+// distance to node v may still precede kd, judged on the 8-bit copy: the bound
+// |x - y| >= |xq - yq| - err_x - err_y (and its inner-product forms) is rigorous, the margins
+// below cover the fp32 rounding of both this estimate and the exact evaluation that follows,
+// so a dropped candidate could never have entered the list.  Eight lanes share a candidate
+// row (16 bytes each per 128 columns); survivors come back one per lane in a new order.
+// xq_s: v's codes and constants in LDS; wscr: 64 words of LDS private to this wave.
+// ---------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ inline u32 dpp_u32(u32 x)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
+}
+__device__ inline int wave_screen(const TgGraph& g, const uint4* xq_s, float norm_v, int cid, u32* wscr, float kd)
+{
+    const int lane = tg_lane();
+    const int sub = lane & 7, c8 = lane >> 3;
+    const bool valid = cid >= 0;
+    const u64 mask = __ballot(valid);
+    const int nv = __popcll(mask);
+    if (nv == 0) return -1;
+    if (valid) wscr[__popcll(mask & tg_lanemask_lt())] = (u32)cid;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int nch = (g.ldq - 32) >> 4;
+    u32 rows[8], dot[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int p = 8 * q + c8;
+        rows[q] = wscr[p < nv ? p : nv - 1];      // candidates past the end repeat the last one
+        dot[q] = 0u;
+    }
+    for (int ch0 = 0; ch0 < nch; ch0 += 8) {
+        const int ch = ch0 + sub;
+        const bool real = ch < nch;
+        const int cc = real ? ch : 0;
+        uint4 a = xq_s[cc];
+        if (!real) a = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int h = 0; h < 8; h += 4) {
+            uint4 b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                b[q] = *reinterpret_cast<const uint4*>(g.Xq + (int64_t)rows[h + q] * g.ldq + 16 * cc);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32 t = dot[h + q];
+                t = __builtin_amdgcn_udot4(a.x, b[q].x, t, false);
+                t = __builtin_amdgcn_udot4(a.y, b[q].y, t, false);
+                t = __builtin_amdgcn_udot4(a.z, b[q].z, t, false);
+                t = __builtin_amdgcn_udot4(a.w, b[q].w, t, false);
+                dot[h + q] = t;
+            }
+        }
+    }
+    // the lane (c8, sub) speaks for candidate 8 sub + c8
+    const int p = 8 * sub + c8;
+    const bool mine = p < nv;
+    const u32 row = wscr[mine ? p : nv - 1];
+    const float4* my = reinterpret_cast<const float4*>(g.Xq + (int64_t)row * g.ldq + (g.ldq - 32));
+    const float4 m0 = my[0], m1 = my[1];
+    u32 d8 = 0u;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        u32 t = dot[q];
+        t += dpp_u32<0xB1>(t);     // lane ^ 1
+        t += dpp_u32<0x4E>(t);     // lane ^ 2
+        t += dpp_u32<0x141>(t);    // mirror inside 8 lanes: the other quad
+        d8 = sub == q ? t : d8;
+    }
+    const float4 v0 = reinterpret_cast<const float4*>(xq_s + nch)[0], v1 = reinterpret_cast<const float4*>(xq_s + nch)[1];
+    // <xq, yq> = d lo lo' + lo s' sum q' + lo' s sum q + s s' <q, q'>
+    const float dotq = (float)g.d * v0.x * m0.x + v0.x * m0.y * m0.w + m0.x * v0.y * v0.w + v0.y * m0.y * (float)d8;
+    const float slack = 2e-5f * (v1.y + m1.y);
+    bool reject;
+    if (g.metric == 0) {
+        const float r = sqrtf(fmaxf(v1.x + m1.x - 2.0f * dotq - slack, 0.0f)) - (v0.z + m0.z);
+        const float lb = r > 0.0f ? r * r : 0.0f;
+        reject = lb * (1.0f - 1e-4f) > kd;
+    } else {
+        // <x, y> <= <xq, yq> + err_x |yq| + |x| err_y
+        const float yn = sqrtf(m1.x);
+        const float ub = dotq + slack + (v0.z * yn + norm_v * m0.z) * 1.0001f;
+        if (g.metric == 1) reject = -ub - 1e-5f * norm_v * (yn + m0.z) > kd;
+        else reject = 1.0f - ub * v1.z * m1.z - 1e-4f > kd;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return (mine && !reject) ? (int)row : -1;
 }
 
 // stage row v of X into this wave's LDS slice
@@ -243,7 +409,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
-    const float dist = wave_direct_dist(g, xs, rn_v, cid, wscr);
+    const float dist = wave_direct_dist<8>(g, xs, rn_v, cid, wscr);
     u64 key = lane < g.k ? tg_key(dist, (u32)cid, 1u) : TG_EMPTY_KEY;
     key = tg_wave_sort(key);
     if (lane < g.k) {
@@ -333,7 +499,8 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 // floor(64 / k) neighbour lists are handled per pass, one candidate per lane (k <= 64), so
 // the usual m = 2, k <= 32 round is one gather of ids, one of vectors, one sort, one merge.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, u64* updates, u64* stat_bins)
+template <bool SCREEN>
+__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, int hist_words, u64* updates, u64* stat_bins)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -341,8 +508,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
     if (v >= g.n) return;
     const int k = g.k;
     float* xs = smem + (size_t)wave * g.ld;
-    u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
-    u32* hist = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + LISTS_WAVES * 128 + wave * (m * k);
+    u32* wbase = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld);
+    u32* wscr = wbase + wave * 128;
+    u32* hist = wbase + LISTS_WAVES * 128 + wave * hist_words;
+    uint4* xq_s = reinterpret_cast<uint4*>(wbase + LISTS_WAVES * (128 + hist_words)) + wave * (g.ldq >> 4);
 
     u32 w = 0;
     float dist = 0.0f;
@@ -350,7 +519,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
-    stage_row(g, v, xs);
+    if (SCREEN) {
+        const uint4* src = reinterpret_cast<const uint4*>(g.Xq + v * (int64_t)g.ldq);
+        for (int i = lane; i < (g.ldq >> 4); i += 64) xq_s[i] = src[i];
+    }
     u32 fresh = w >> 31;
     u64 mf = __ballot(lane < k && fresh);
     if (fresh && __popcll(mf & tg_lanemask_lt()) < m) fresh = 0;   // non-revisitation
@@ -358,10 +530,12 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
     const u64 L0 = L;                                              // the list as the round found it
     const u32 my_id = w & TG_ID_MASK;
     const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
+    const float norm_v = g.metric != 0 ? sqrtf(g.nrm[v]) : 0.0f;
     const int nexp = min(m, __popcll(mf));
     const int per = 64 / k;
+    bool staged = false;
 
-    int evaluated = 0, nhist = 0;
+    int evaluated = 0, measured = 0, nhist = 0;
     for (int e0 = 0; e0 < nexp; e0 += per) {
         const int nb = min(per, nexp - e0);
         const int my_e = lane / k, j = lane - my_e * k;
@@ -387,11 +561,24 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         if (e0 + per < nexp) {
             if (!drop) hist[nhist + __popcll(live & tg_lanemask_lt())] = cid;
             nhist += nlive;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
-        const float cdist = wave_direct_dist(g, xs, rn_v, drop ? -1 : (int)cid, wscr);
-        u64 ck = drop ? TG_EMPTY_KEY : tg_key(cdist, cid, 3u);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // candidates that provably cannot precede the list's last entry are dropped on the 8-bit copy
+        int cand = drop ? -1 : (int)cid;
+        if (SCREEN) {
+            const float kd = tg_key_dist((u64)__builtin_amdgcn_readlane((int)(L >> 32), k - 1) << 32);
+            cand = wave_screen(g, xq_s, norm_v, cand, wscr, kd);
+        }
+        const u64 alive = __ballot(cand >= 0);
+        if (alive == 0) continue;
+        measured += __popcll(alive);
+        if (!staged) {
+            stage_row(g, v, xs);
+            staged = true;
+        }
+        const float cdist = wave_direct_dist<SCREEN ? 1 : 8>(g, xs, rn_v, cand, wscr);
+        u64 ck = cand >= 0 ? tg_key(cdist, (u32)cand, 3u) : TG_EMPTY_KEY;
         ck = tg_wave_sort(ck);
         L = tg_wave_merge_low(L, ck);
         if (lane >= k) L = TG_EMPTY_KEY;
@@ -406,15 +593,18 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         if (ins) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
         if (stat_bins && evaluated) {
             atomicAdd(stat_bins + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);                 // pairs
-            atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);  // vectors
+            if (measured) atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)measured);  // fp32 vectors
         }
     }
 }
 void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
 {
-    size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)m * g.k) * sizeof(u32);
+    const int hist_words = (m * g.k + 3) & ~3;
+    const size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)hist_words) * sizeof(u32) +
+                       (size_t)LISTS_WAVES * (g.Xq ? g.ldq : 0);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(phase2_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, updates, stat_bins);
+    if (g.Xq) hipLaunchKernelGGL(phase2_kernel<true>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, hist_words, updates, stat_bins);
+    else hipLaunchKernelGGL(phase2_kernel<false>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, hist_words, updates, stat_bins);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -439,7 +629,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, i
     if (recompute) {
         stage_row(g, v, xs);
         const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
-        dist = wave_direct_dist(g, xs, rn_v, id, wscr);
+        dist = wave_direct_dist<8>(g, xs, rn_v, id, wscr);
         u64 key = lane < k ? tg_key(dist, (u32)id, 0u) : TG_EMPTY_KEY;
         key = tg_wave_sort(key);
         id = (int)tg_key_id(key);

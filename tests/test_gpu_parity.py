@@ -160,6 +160,46 @@ def test_join_statistics_count_the_needed_pairs():
     b.close()
 
 
+@pytest.mark.parametrize("k,m", [(16, 2), (24, 3), (40, 2)])
+def test_phase2_counts_every_candidate_once(k, m):
+    """Algorithm 1 lines 9-12: the candidates of a round are the ids listed by the m expanded
+    neighbours that are neither v, nor in G[v], nor met before in the same round."""
+    X = inputs.make("C2", n=2000, d=32, comps=4)
+    prm = knn.default_params(k, 6, seed=2, m=m)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    b.init(); o.init()
+    for r in range(2):
+        b.phase1_round(); o.phase1_round()
+    b.begin_phase2(); o.begin_phase2()
+    for r in range(2, 5):
+        assert b.phase2_round() == o.phase2_round()
+        assert b.stats()["join_pairs"][r] == o.counters()["pairs"], r
+        assert _same(b.graph(), o.graph())
+    b.close()
+
+
+@pytest.mark.parametrize("metric", ["l2", "ip", "cosine"])
+@pytest.mark.parametrize("d", [40, 200])
+def test_screening_never_changes_the_graph(metric, d):
+    """The 8-bit lower bound of phase 2 may only drop candidates that could not enter the list:
+    on real-valued data of mixed sign and scale the graph with screening equals the one without."""
+    rng = np.random.default_rng(77 + d)
+    n, k = 6000, 20
+    centres = rng.normal(size=(12, d)) * 3.0
+    X = (centres[rng.integers(0, 12, n)] + rng.normal(size=(n, d)) * rng.uniform(0.2, 1.5, size=(n, 1))).astype(np.float32)
+    X[: n // 3] += 5.0                         # a shifted part: codes with a large offset
+    X[n // 3: n // 2] *= 1e-3                  # and a tiny-scale part
+    Xg = torch.from_numpy(X).cuda()
+    out = []
+    for screen in (1, 0):
+        prm = knn.default_params(k, 8, metric=metric, seed=9, screen=screen)
+        ids, dist, st = knn.knn_build_ex(Xg, prm)
+        out.append((ids.cpu().numpy(), dist.cpu().numpy(), st))
+    assert (out[0][0] == out[1][0]).all() and (out[0][1] == out[1][1]).all()
+    assert out[0][2]["updates"] == out[1][2]["updates"]
+
+
 @pytest.mark.parametrize("iters", [1, 6, 9])
 def test_whole_build_identical_to_oracle(iters):
     X = inputs.make("C2", n=2000, d=48, comps=4)
