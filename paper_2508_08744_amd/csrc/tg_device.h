@@ -66,20 +66,57 @@ __device__ inline u64 tg_shfl_xor64(u64 x, int mask)
 __device__ inline u64 tg_min64(u64 a, u64 b) { return a < b ? a : b; }
 __device__ inline u64 tg_max64(u64 a, u64 b) { return a < b ? b : a; }
 
+// Value held by lane (lane ^ XOR).  Inside a row of 16 lanes this is one or two DPP moves
+// (quad permutations, mirrors of 8 and 16 lanes, rotation by 8); across rows it goes through
+// the LDS crossbar.
+template <int CTRL>
+__device__ inline u64 tg_dpp64(u64 x)
+{
+    // every lane has a source inside its row for the controls used here, so no fill value is needed
+    const u32 lo = (u32)__builtin_amdgcn_mov_dpp((int)(u32)x, CTRL, 0xF, 0xF, true);
+    const u32 hi = (u32)__builtin_amdgcn_mov_dpp((int)(u32)(x >> 32), CTRL, 0xF, 0xF, true);
+    return ((u64)hi << 32) | lo;
+}
+template <int XOR>
+__device__ inline u64 tg_partner(u64 x)
+{
+    if (XOR == 1) return tg_dpp64<0xB1>(x);                     // quad_perm 1,0,3,2
+    if (XOR == 2) return tg_dpp64<0x4E>(x);                     // quad_perm 2,3,0,1
+    if (XOR == 3) return tg_dpp64<0x1B>(x);                     // quad_perm 3,2,1,0
+    if (XOR == 4) return tg_dpp64<0x1B>(tg_dpp64<0x141>(x));    // mirror of 8, then of 4: 7 ^ 3
+    if (XOR == 7) return tg_dpp64<0x141>(x);                    // row_half_mirror
+    if (XOR == 8) return tg_dpp64<0x128>(x);                    // row_ror 8
+    if (XOR == 15) return tg_dpp64<0x140>(x);                   // row_mirror
+    return tg_shfl_xor64(x, XOR);
+}
+// one compare-exchange: the lane keeps the smaller of (key, other) if keep_min, else the larger
+__device__ inline u64 tg_cmpx(u64 key, u64 other, bool keep_min)
+{
+    const bool lt = key < other;
+    return (lt != keep_min) ? other : key;
+}
+template <int SIZE>
+__device__ inline u64 tg_sort_level(u64 key, int lane)
+{
+    // blocks of SIZE lanes: fold each block onto itself, then clean its halves
+    key = tg_cmpx(key, tg_partner<SIZE - 1>(key), (lane & (SIZE >> 1)) == 0);
+    if (SIZE >= 64) key = tg_cmpx(key, tg_partner<16>(key), (lane & 16) == 0);
+    if (SIZE >= 32) key = tg_cmpx(key, tg_partner<8>(key), (lane & 8) == 0);
+    if (SIZE >= 16) key = tg_cmpx(key, tg_partner<4>(key), (lane & 4) == 0);
+    if (SIZE >= 8) key = tg_cmpx(key, tg_partner<2>(key), (lane & 2) == 0);
+    if (SIZE >= 4) key = tg_cmpx(key, tg_partner<1>(key), (lane & 1) == 0);
+    return key;
+}
 // Ascending bitonic sort of one key per lane across the wave.
 __device__ inline u64 tg_wave_sort(u64 key)
 {
     const int lane = tg_lane();
-#pragma unroll
-    for (int size = 2; size <= TG_WAVE; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            u64 other = tg_shfl_xor64(key, stride);
-            bool up = (lane & size) == 0;
-            bool lower = (lane & stride) == 0;
-            key = (up == lower) ? tg_min64(key, other) : tg_max64(key, other);
-        }
-    }
+    key = tg_sort_level<2>(key, lane);
+    key = tg_sort_level<4>(key, lane);
+    key = tg_sort_level<8>(key, lane);
+    key = tg_sort_level<16>(key, lane);
+    key = tg_sort_level<32>(key, lane);
+    key = tg_sort_level<64>(key, lane);
     return key;
 }
 
@@ -88,12 +125,13 @@ __device__ inline u64 tg_wave_sort(u64 key)
 __device__ inline u64 tg_wave_merge_low(u64 a, u64 b)
 {
     const int lane = tg_lane();
-    u64 x = tg_min64(a, tg_shfl64(b, TG_WAVE - 1 - lane));
-#pragma unroll
-    for (int stride = TG_WAVE / 2; stride > 0; stride >>= 1) {
-        u64 other = tg_shfl_xor64(x, stride);
-        x = ((lane & stride) == 0) ? tg_min64(x, other) : tg_max64(x, other);
-    }
+    u64 x = tg_min64(a, tg_partner<63>(b));
+    x = tg_cmpx(x, tg_partner<32>(x), (lane & 32) == 0);
+    x = tg_cmpx(x, tg_partner<16>(x), (lane & 16) == 0);
+    x = tg_cmpx(x, tg_partner<8>(x), (lane & 8) == 0);
+    x = tg_cmpx(x, tg_partner<4>(x), (lane & 4) == 0);
+    x = tg_cmpx(x, tg_partner<2>(x), (lane & 2) == 0);
+    x = tg_cmpx(x, tg_partner<1>(x), (lane & 1) == 0);
     return x;
 }
 
