@@ -98,6 +98,7 @@ struct tg_knn_handle {
     int rounds1, rounds2;
     bool phase2;
     bool norms_done;
+    bool edges_numbered; // the kernel that wrote the current lists has numbered their sampled edges (deg, gid_next)
     // timing
     std::vector<hipEvent_t> ev;
     struct Span { int kind, round, e0, e1; };
@@ -194,6 +195,7 @@ extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
     h->norms_done = false;
+    h->edges_numbered = false;
     if (h->x_padded) tg_launch_pad_rows(X, n, d, h->x_padded, h->g.ld, h->stream);
     tg_launch_fill_u32(h->sm.deg, (size_t)n, 0u, h->stream);
     tg_launch_fill_u64(h->cd.slots, (size_t)n * p->C, TG_EMPTY_KEY, h->stream);
@@ -237,8 +239,10 @@ extern "C" int tg_knn_init(tg_knn_handle* h)
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     ensure_norms(h);
     int sp = begin_span(h, SPAN_INIT, 0);
-    tg_launch_init(h->g, tg_hash_seed(h->p.seed, TG_TAG_INIT), h->stream);
+    if (h->edges_numbered) tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);   // numbers nobody used
+    tg_launch_init(h->g, tg_hash_seed(h->p.seed, TG_TAG_INIT), &h->sm, h->stream);
     end_span(h, sp);
+    h->edges_numbered = true;
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
     return launch_status("init");
@@ -256,33 +260,42 @@ static int read_updates(tg_knn_handle* h, int round, int64_t* updates)
     return TG_OK;
 }
 
-extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates)
+// number_next: the list update also numbers the sampled edges of the lists it writes, which
+// saves the next phase-1 round its counting pass (pointless after the last one)
+static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     if (h->phase2) return fail(TG_ERR_INVALID_ARG, "phase 1 round after the switch to phase 2");
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
     int sp = begin_span(h, SPAN_SAMPLE, r);
-    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->stream);
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->edges_numbered, h->stream);
+    h->edges_numbered = false;
     end_span(h, sp);
     sp = begin_span(h, SPAN_JOIN, r);
     tg_launch_join(h->g, h->sm, h->cd, h->p.ng_row, h->p.ng_col, tg_hash_seed(h->p.seed, TG_TAG_SLOT(r)),
                    h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
     end_span(h, sp);
     sp = begin_span(h, SPAN_UPDATE, r);
-    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, h->stream);
+    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, number_next, h->stream);
     end_span(h, sp);
+    h->edges_numbered = number_next;
     h->round++;
     h->rounds1++;
     int rc = launch_status("phase-1 round");
     if (rc != TG_OK) return rc;
     return updates ? read_updates(h, r, updates) : TG_OK;
 }
+extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates) { return phase1_round(h, updates, true); }
 
 extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     tg_launch_mark_all_fresh(h->g, h->stream);
+    if (h->edges_numbered) {   // phase 2 reuses the buffer that holds the numbers
+        tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
+        h->edges_numbered = false;
+    }
     if (!h->phase2 && h->xq) {
         ensure_norms(h);
         int sp = begin_span(h, SPAN_NORMS, 0);
@@ -375,6 +388,8 @@ extern "C" int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* 
 {
     if (!h || !ids || !dist || !fresh) return fail(TG_ERR_INVALID_ARG, "NULL argument");
     ensure_norms(h);
+    if (h->edges_numbered) tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
+    h->edges_numbered = false;
     tg_launch_import(h->g, ids, dist, fresh, h->stream);
     return launch_status("import");
 }
@@ -382,7 +397,8 @@ extern "C" int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* 
 extern "C" int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* sizes)
 {
     if (!h || !blk || !sizes) return fail(TG_ERR_INVALID_ARG, "NULL argument");
-    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->stream);
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->edges_numbered, h->stream);
+    h->edges_numbered = false;
     tg_launch_dump_blocks(h->g, h->sm, blk, sizes, h->stream);
     return launch_status("sample");
 }
@@ -420,7 +436,7 @@ static int run_all(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
     if (rc != TG_OK) return rc;
     for (int r = 0; r < p.it1; ++r) {
         int64_t upd = 0;
-        rc = tg_knn_phase1_round(h, p.delta > 0.0f ? &upd : nullptr);
+        rc = phase1_round(h, p.delta > 0.0f ? &upd : nullptr, r + 1 < p.it1);
         if (rc != TG_OK) return rc;
         if (p.delta > 0.0f && (double)upd < stop) break;
     }

@@ -18,7 +18,7 @@ struct TgGraph {
     float* nrm;       // n: squared norms
     float* rnorm;     // n: 1/|x| (cosine only, else unused)
     uint32_t* gid;    // n x k list words of the current round: id | fresh << 31
-    uint32_t* gid_next; // n x k, written by a phase-2 round
+    uint32_t* gid_next; // n x k, written by a phase-2 round; in phase 1 it holds the arrival number of every sampled edge
     float* gdist;     // n x k
     unsigned long long* kth;   // n: key of each list's last entry with both low bits set
     const uint8_t* Xq;  // n x ldq bytes: 8-bit codes of every row followed by 32 bytes of row constants (phase-2 screening), or null
@@ -27,7 +27,7 @@ struct TgGraph {
 
 struct TgSample {
     int32_t S, R;
-    uint32_t* deg;            // n, zero between rounds
+    uint32_t* deg;            // n: arrivals per node, zero once the prefix sum has used it
     unsigned long long* off;  // n + 1
     uint32_t* csr;            // n x k: source | class << 31
     int32_t BC;               // row stride of blk: min(k, 2S) + 2R rounded up to 16
@@ -44,11 +44,11 @@ struct TgCand {
 };
 
 void tg_launch_norms(const TgGraph& g, hipStream_t s);
-void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s);
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges /* or null */, hipStream_t s);
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, hipStream_t s);
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
-void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s);
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool edges_numbered, hipStream_t s);
 void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col,
                     uint64_t hs_slot, unsigned long long* stat_bins /* 2 x TG_STAT_BINS or null */,
                     hipStream_t s);
@@ -56,7 +56,7 @@ void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, i
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb,
                               float* out, hipStream_t s);
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, unsigned long long* updates,
-                      hipStream_t s);
+                      bool number_edges, hipStream_t s);
 void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
 void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates,
                       unsigned long long* stat_bins, hipStream_t s);

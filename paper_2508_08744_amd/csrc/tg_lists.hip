@@ -373,11 +373,25 @@ __device__ inline bool id_in_list(u32 id, u64 list_key, int k)
     return hit;
 }
 
+// The wave has just written list v (entry `id`, mark `fresh` in lanes < k).  The next round
+// samples its first S new and first S old entries; each of those edges v -> id takes its
+// arrival number at id here (deg counts arrivals, epos keeps the number per list entry), so
+// that the reverse lists of the next round can be laid out without a counting pass.
+__device__ inline void number_sampled_edges(int64_t v, int k, int S, u32 id, bool fresh, u32* deg, u32* epos)
+{
+    const int lane = tg_lane();
+    const bool live = lane < k;
+    const u64 lt = tg_lanemask_lt();
+    const u64 mf = __ballot(live && fresh), mo = __ballot(live && !fresh);
+    const bool take = live && __popcll((fresh ? mf : mo) & lt) < S;
+    if (take) epos[v * k + lane] = atomicAdd(deg + id, 1u);
+}
+
 // ---------------------------------------------------------------------------------------
 // Algorithm 1 lines 1-2.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
 // hash and keeps the first k that differ from v and from all earlier draws.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int S, u32* deg)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -417,12 +431,14 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
         g.gdist[v * g.k + lane] = tg_key_dist(key);
         if (lane == g.k - 1) g.kth[v] = key | 3ull;
     }
+    if (deg) number_sampled_edges(v, g.k, S, tg_key_id(key), true, deg, g.gid_next);
 }
-void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s)
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges, hipStream_t s)
 {
     size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(init_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, hs_init);
+    hipLaunchKernelGGL(init_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, hs_init,
+                       number_edges ? number_edges->S : 0, number_edges ? number_edges->deg : (u32*)nullptr);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -431,7 +447,7 @@ void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s)
 // ascending sequences and keeps the first k.  Entries sampled as "new" this round become
 // old; arrivals are new.  Used slots are handed back empty.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg)
 {
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
@@ -463,6 +479,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         L = tg_wave_merge_low(L, ck);
         if (lane >= k) L = TG_EMPTY_KEY;
     }
+    if (deg) number_sampled_edges(v, k, S, tg_key_id(L), ((u32)L & 1u) != 0, deg, g.gid_next);
     if (!any_cand && mf == 0) return;
     const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
     if (lane < k) {
@@ -472,10 +489,11 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     }
     if (ins && lane == 0) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
 }
-void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, hipStream_t s)
+void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool number_edges, hipStream_t s)
 {
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates);
+    hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
+                       number_edges ? sm.deg : (u32*)nullptr);
 }
 
 // phase switch: every entry unvisited

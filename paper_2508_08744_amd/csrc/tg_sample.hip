@@ -1,7 +1,8 @@
 // Phase-1 sampling (step (1) of section 3.1.1): forward samples are read straight from
 // the lists (first S new and first S old entries in list order); this file builds the
-// bounded reverse samples.  Every sampled edge v -> u is counted at u, a prefix sum turns
-// the counts into segments, the edges are scattered into their segments, and the wave
+// bounded reverse samples.  Every sampled edge v -> u is numbered at u (one atomic add, done
+// by the kernel that wrote the list where possible), a prefix sum turns the counts into
+// segments, the edges are stored at their numbers inside the segments, and the wave
 // that owns node u keeps, per class, the R arrivals with the smallest
 // (hash(round, source, u), source): a uniform subset that does not depend on arrival order.
 // The same wave then assembles the anchor's block and stores it for the join.
@@ -29,17 +30,23 @@ __device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, F 
     if (take_new || take_old) f((u32)v, w & TG_ID_MASK, take_old ? 1u : 0u);
 }
 
-__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg)
+// Arrival numbers: every sampled edge v -> u takes the next number at u (deg[u] counts the
+// arrivals) and remembers it in epos, so that the scatter below needs no second atomic.  The
+// kernels that write the lists (initial lists, list update) number the edges of the lists they
+// have just written in the same way; this kernel serves the cases where that has not happened.
+__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg, u32* epos)
 {
-    for_each_sampled_edge(g, S, kp, [&](u32, u32 u, u32) { atomicAdd(deg + u, 1u); });
+    const int sub = tg_lane() & (kp - 1);
+    for_each_sampled_edge(g, S, kp, [&](u32 v, u32 u, u32) { epos[(int64_t)v * g.k + sub] = atomicAdd(deg + u, 1u); });
 }
 
-// fills segments from their ends: deg[u] counts down to zero again
-__global__ __launch_bounds__(256) void rev_fill_kernel(TgGraph g, int S, int kp, u32* deg, const u64* off, u32* csr)
+// edge v -> u with arrival number a goes to csr[off[u] + a]
+__global__ __launch_bounds__(256) void rev_fill_kernel(TgGraph g, int S, int kp, const u32* __restrict__ epos,
+                                                       const u64* __restrict__ off, u32* __restrict__ csr)
 {
+    const int sub = tg_lane() & (kp - 1);
     for_each_sampled_edge(g, S, kp, [&](u32 v, u32 u, u32 cls) {
-        u32 left = atomicSub(deg + u, 1u);
-        csr[off[u] + left - 1] = v | (cls << 31);
+        csr[off[u] + epos[(int64_t)v * g.k + sub]] = v | (cls << 31);
     });
 }
 
@@ -83,7 +90,7 @@ __global__ __launch_bounds__(256) void scan_sums_kernel(u64* block_sums, int64_t
     }
     if (threadIdx.x == 0) *off_total = carry_s;
 }
-__global__ __launch_bounds__(256) void scan_final_kernel(const u32* deg, int64_t n, const u64* block_sums, u64* off)
+__global__ __launch_bounds__(256) void scan_final_kernel(u32* deg, int64_t n, const u64* block_sums, u64* off)
 {
     __shared__ u64 wsum[4];
     int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * 4;
@@ -101,7 +108,10 @@ __global__ __launch_bounds__(256) void scan_final_kernel(const u32* deg, int64_t
     for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pre += wsum[w];
     u64 run = pre + incl - s;
     for (int i = 0; i < 4; ++i) {
-        if (base + i < n) off[base + i] = run;
+        if (base + i < n) {
+            off[base + i] = run;
+            deg[base + i] = 0u;     // counted anew for the next round
+        }
         run += x[i];
     }
 }
@@ -197,7 +207,7 @@ void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, i
     hipLaunchKernelGGL(dump_blocks_kernel, dim3((unsigned)grid), dim3(256), 0, s, g, sm, blk, sizes);
 }
 
-void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s)
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool counted, hipStream_t s)
 {
     int kp = 1;
     while (kp < g.k) kp <<= 1;
@@ -205,10 +215,10 @@ void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hi
     const int64_t waves = (g.n + per_wave - 1) / per_wave;
     const unsigned edge_blocks = (unsigned)((waves + 3) / 4);
     const int64_t nsb = (g.n + SCAN_BLOCK - 1) / SCAN_BLOCK;
-    hipLaunchKernelGGL(rev_count_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg);
+    if (!counted) hipLaunchKernelGGL(rev_count_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg, g.gid_next);
     hipLaunchKernelGGL(scan_partial_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp);
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sm.scan_tmp, nsb, sm.off + g.n);
     hipLaunchKernelGGL(scan_final_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp, sm.off);
-    hipLaunchKernelGGL(rev_fill_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg, sm.off, sm.csr);
+    hipLaunchKernelGGL(rev_fill_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, (const u32*)g.gid_next, (const u64*)sm.off, sm.csr);
     hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, hs_rev);
 }
