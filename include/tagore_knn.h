@@ -48,7 +48,7 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *   S        forward sample cap per class (new / old) in phase 1, 1 <= S <= 32
  *   R        reverse sample cap per class in phase 1, 0 <= R <= 32
  *   C        candidate slots per node and round (section 4.2 "candidate list"),
- *            a power of two, 16 <= C <= 128
+ *            a power of two, 16 <= C <= 256
  *   ng_row   retention groups of row tiles  (2 or 4)  } section 4.2: per node one closest
  *   ng_col   retention groups of column tiles (2,4,8) } candidate per sub-tile group
  *   m        neighbours expanded per node and phase-2 round (the paper: m = 2), 1..4

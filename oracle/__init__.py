@@ -42,7 +42,7 @@ def lib():
         L.oracle_hash3.restype = u64
         L.oracle_hash3.argtypes = [u64, u64, u64, u64]
         L.oracle_slot_of.restype = ctypes.c_uint32
-        L.oracle_slot_of.argtypes = [u64, i32, i32, i32, i32]
+        L.oracle_slot_of.argtypes = [u64, i32, i32, i32, i32, i32]
         L.oracle_distance.restype = dbl
         L.oracle_distance.argtypes = [vp, i64, i32, i64, i64]
         L.obf_knn.restype = i32
@@ -84,8 +84,9 @@ def hash3(seed: int, tag: int, x: int, y: int) -> int:
     return lib().oracle_hash3(seed, tag, x, y)
 
 
-def slot_of(seed: int, round_: int, t: int, c: int, C: int) -> int:
-    return lib().oracle_slot_of(seed, round_, t, c, C)
+def slot_of(seed: int, round_: int, t: int, v: int, g: int, C: int) -> int:
+    """Slot (of target t's C) that takes the candidate anchor v's block found in opponent group g."""
+    return lib().oracle_slot_of(seed, round_, t, v, g, C)
 
 
 def distance(X, metric: int, a: int, b: int) -> float:

@@ -316,28 +316,33 @@ static void clear_candidates(onnd_t *o)
     }
 }
 
-/* Slot of candidate c at target t: a per-(round, target) 32-bit salt from the
- * tagged hash, then a 32-bit multiply-xorshift-multiply of (c + salt); the top
- * log2(C) bits are the slot. */
-static uint32_t slot_of(uint64_t seed, int round, int32_t t, int32_t c, int C)
+/* Slot of a candidate at target t that anchor v's block found in opponent group g.
+ * The C slots of t are C/8 lines of 8; the pair (t, v) picks its line and a rotation from
+ * a 32-bit multiply-xorshift hash of v plus a per-(round, target) salt (tagged hash), and
+ * group g takes word (g + rotation) mod 8 of that line. */
+static uint32_t slot_of(uint64_t seed, int round, int32_t t, int32_t v, int g, int C)
 {
     uint32_t salt = (uint32_t)mix64(mix64(seed + TAG_SLOT(round) * TG_GOLDEN) + (uint64_t)t);
-    uint32_t h = ((uint32_t)c + salt) * 0x9E3779B1u;
+    uint32_t h = ((uint32_t)v + salt) * 0x9E3779B1u;
     h ^= h >> 15;
     h *= 0x85EBCA77u;
+    h ^= h >> 13;
     int bits = 0;
-    while ((1 << bits) < C) ++bits;
-    return h >> (32 - bits);
+    while ((8 << bits) < C) ++bits;
+    uint32_t line = bits ? h >> (32 - bits) : 0u;
+    return line * 8u + (((uint32_t)g + (h & 7u)) & 7u);
 }
-uint32_t oracle_slot_of(uint64_t seed, int round, int32_t t, int32_t c, int C) { return slot_of(seed, round, t, c, C); }
+uint32_t oracle_slot_of(uint64_t seed, int round, int32_t t, int32_t v, int g, int C) { return slot_of(seed, round, t, v, g, C); }
 
-/* A candidate for target t.  With bounded storage the candidate goes to
- * slot_of(round, t, c) and a slot keeps the smaller (dist, id). */
-static void emit(onnd_t *o, int32_t t, int32_t c, double dist)
+/* A candidate c for target t, found by anchor v's block in opponent group g.  With bounded
+ * storage it goes to slot_of(round, t, v, g) and a slot keeps the smaller (dist, id); the
+ * same candidate may reach t through several blocks and then sits in several slots (the
+ * list update drops the repeats). */
+static void emit(onnd_t *o, int32_t t, int32_t c, double dist, int32_t v, int g)
 {
     o->offered++;
     if (o->C == 0) { bag_push(&o->bag[t], dist, c); return; }
-    uint32_t s = slot_of(o->seed, o->round, t, c, o->C);
+    uint32_t s = slot_of(o->seed, o->round, t, v, g, o->C);
     cand_t *slot = o->slots + (int64_t)t * o->C + (int64_t)s;
     if (slot->id < 0 || key_less(dist, c, slot->dist, slot->id)) { slot->dist = dist; slot->id = c; }
 }
@@ -447,7 +452,7 @@ static int contains(const int32_t *a, int na, int32_t x)
 /* The local join of one block.  Positions 0..nN-1 are the NEW nodes,
  * nN..nN+nO-1 the OLD nodes.  Every pair (a,b), a<b, with a NEW is
  * evaluated once; both endpoints are targets of the result. */
-static void local_join(onnd_t *o, const int32_t *blk, int nN, int nO)
+static void local_join(onnd_t *o, int32_t v, const int32_t *blk, int nN, int nO)
 {
     int nT = nN + nO;
     if (nN == 0 || nT < 2) return;
@@ -456,8 +461,8 @@ static void local_join(onnd_t *o, const int32_t *blk, int nN, int nO)
             for (int b = a + 1; b < nT; ++b) {
                 double dist = distance(o->X, o->d, o->metric, blk[a], blk[b]);
                 o->pairs++;
-                if (passes(o, blk[a], blk[b], dist)) emit(o, blk[a], blk[b], dist);
-                if (passes(o, blk[b], blk[a], dist)) emit(o, blk[b], blk[a], dist);
+                if (passes(o, blk[a], blk[b], dist)) emit(o, blk[a], blk[b], dist, v, (b / o->tile) % 8);
+                if (passes(o, blk[b], blk[a], dist)) emit(o, blk[b], blk[a], dist, v, (a / o->tile) % 8);
             }
         return;
     }
@@ -485,10 +490,10 @@ static void local_join(onnd_t *o, const int32_t *blk, int nN, int nO)
         }
     for (int a = 0; a < nN; ++a)
         for (int g = 0; g < ngc; ++g)
-            if (best_row[a * ngc + g].id >= 0) emit(o, blk[a], best_row[a * ngc + g].id, best_row[a * ngc + g].dist);
+            if (best_row[a * ngc + g].id >= 0) emit(o, blk[a], best_row[a * ngc + g].id, best_row[a * ngc + g].dist, v, g);
     for (int b = 0; b < nT; ++b)
         for (int g = 0; g < ngr; ++g)
-            if (best_col[b * ngr + g].id >= 0) emit(o, blk[b], best_col[b * ngr + g].id, best_col[b * ngr + g].dist);
+            if (best_col[b * ngr + g].id >= 0) emit(o, blk[b], best_col[b * ngr + g].id, best_col[b * ngr + g].dist, v, g);
     free(best_row); free(best_col);
 }
 
@@ -569,7 +574,7 @@ int64_t onnd_phase1_round(void *h)
         /* pin mode: every node meets every other node as NEW */
         int32_t *all = (int32_t *)malloc((size_t)n * sizeof(int32_t));
         for (int64_t i = 0; i < n; ++i) all[i] = (int32_t)i;
-        local_join(o, all, (int)n, 0);
+        local_join(o, 0, all, (int)n, 0);
         free(all);
         for (int64_t i = 0; i < n * k; ++i) o->G[i].fresh = 0;
         o->updates = merge_all(o);
@@ -585,7 +590,7 @@ int64_t onnd_phase1_round(void *h)
     for (int64_t v = 0; v < n; ++v) {
         int sizes[2];
         onnd_block(h, v, blk, sizes);
-        local_join(o, blk, sizes[0], sizes[1]);
+        local_join(o, (int32_t)v, blk, sizes[0], sizes[1]);
     }
     free(blk);
 

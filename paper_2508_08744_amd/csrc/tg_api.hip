@@ -40,7 +40,7 @@ static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
         return fail(TG_ERR_INVALID_ARG, "it1 = %d, it2 = %d: need 0 <= it1 + it2 <= %d", p->it1, p->it2, TG_MAX_ROUNDS);
     if (p->S < 1 || p->S > 32) return fail(TG_ERR_INVALID_ARG, "S = %d outside 1..32", p->S);
     if (p->R < 0 || p->R > 32) return fail(TG_ERR_INVALID_ARG, "R = %d outside 0..32", p->R);
-    if (p->C < 16 || p->C > 128 || (p->C & (p->C - 1))) return fail(TG_ERR_INVALID_ARG, "C = %d must be 16, 32, 64 or 128", p->C);
+    if (p->C < 16 || p->C > 256 || (p->C & (p->C - 1))) return fail(TG_ERR_INVALID_ARG, "C = %d must be 16, 32, 64, 128 or 256", p->C);
     if (p->ng_row != 2 && p->ng_row != 4) return fail(TG_ERR_INVALID_ARG, "ng_row = %d must be 2 or 4", p->ng_row);
     if (p->ng_col != 2 && p->ng_col != 4 && p->ng_col != 8) return fail(TG_ERR_INVALID_ARG, "ng_col = %d must be 2, 4 or 8", p->ng_col);
     if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);

@@ -75,7 +75,7 @@ __device__ inline float gram_to_dist(float gram, float aux_a, float aux_b)
 {
     if (METRIC == 0) return fmaxf(0.0f, fmaf(-2.0f, gram, aux_a + aux_b));
     if (METRIC == 1) return -gram + 0.0f;
-    return 1.0f - gram * aux_a * aux_b + 0.0f;
+    return 1.0f - gram * (aux_a * aux_b) + 0.0f;   // symmetric in the two nodes, bit for bit
 }
 // (dist, id) precedes the target's last list entry (kd, kid)?
 __device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
@@ -83,16 +83,21 @@ __device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
     return (dist < kd) | ((dist == kd) & (id < kid));
 }
 
-// Candidate c of the member at block position tpos goes to slot
-// top_bits((c + salt) * K1, xorshift, * K2) of that member's slot row and stays if it is the
-// smaller (dist, id): one 64-bit atomic minimum, no order dependence.
-__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, u32 odist, u32 c)
+// Candidate c of the member at block position tpos (node t), found by anchor v's block in
+// partner group q < 8.  A (t, v) pair owns one 64-byte line of t's slot row, picked by a hash,
+// and the candidate of group q goes to word (q + rotation) % 8 of it, where it stays if it is
+// the smaller (dist, id): one 64-bit atomic minimum, no order dependence.  All candidates one
+// block has for t share a line, so they can travel in one memory transaction.
+__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, u32 odist, u32 c,
+                                      u32 v, int q)
 {
     const u32 t = (u32)s_ids[tpos];
-    u32 h = (c + s_salt[tpos]) * 0x9E3779B1u;
+    u32 h = (s_salt[tpos] + v) * 0x9E3779B1u;
     h ^= h >> 15;
     h *= 0x85EBCA77u;
-    const u32 slot = h >> (33 - __ffs(cd.C));
+    h ^= h >> 13;
+    const u32 line = h >> (36 - __ffs(cd.C));        // C / 8 lines
+    const u32 slot = line * 8u + ((u32)(q + (int)(h & 7u)) & 7u);
     atomicMin(cd.slots + (int64_t)t * cd.C + slot, ((u64)odist << 32) | (u64)((c << 2) | 3u));
 }
 
@@ -288,7 +293,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 const float md = c16 == 0 ? rbd[0] : c16 == 1 ? rbd[1] : c16 == 2 ? rbd[2] : rbd[3];
                 const u32 mi = c16 == 0 ? rbi[0] : c16 == 1 ? rbi[1] : c16 == 2 ? rbi[2] : rbi[3];
                 const int a = 16 * i + 4 * g4 + c16;
-                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, tg_ord(md), mi);
+                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, tg_ord(md), mi, (u32)v, wc + 2 * cg);
             }
         }
     }
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
                 pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
                 const int b = 16 * j + c16;
-                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, tg_ord(d0), i0);
+                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, tg_ord(d0), i0, (u32)v, wr + 2 * rg);
             }
         }
     }
@@ -346,6 +351,8 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
     __shared__ u32 sh_kid[4][2][64];
     __shared__ int sh_ids[4][2][64];
     __shared__ float sh_aux[4][2][64];
+    // candidates of one block, one cell per (member, partner group); handed over a block later
+    __shared__ u64 sh_cell[4][2][64 * GMAX];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     const float INF = __builtin_inff();
@@ -408,6 +415,38 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         }
     };
 
+    // Hand the cells of a finished block to the slot rows.  Lanes q = 0..GMAX-1 of a member sit
+    // side by side and their slots share a 64-byte line, so the atomics of one member travel
+    // as one transaction.
+    constexpr int CELLS = 64 * GMAX;
+    auto flush_cells = [&](int fbuf, u32 fv, int fnT) {
+        const u64* cells = sh_cell[wave][fbuf];
+        const u32* f_salt = sh_salt[wave][fbuf];
+        const int* f_ids = sh_ids[wave][fbuf];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int p = 16 * s4 + (lane >> 2), q = lane & 3;
+            if (16 * s4 < fnT) {
+                const bool in = p < fnT && q < GMAX;
+                const u64 key = in ? cells[p * GMAX + (q < GMAX ? q : 0)] : TG_EMPTY_KEY;
+                if (key != TG_EMPTY_KEY) {
+                    const u32 t = (u32)f_ids[p];
+                    u32 h = (f_salt[p] + fv) * 0x9E3779B1u;
+                    h ^= h >> 15;
+                    h *= 0x85EBCA77u;
+                    h ^= h >> 13;
+                    const u32 line = h >> (36 - __ffs(cd.C));
+                    const u32 slot = line * 8u + ((u32)(q + (int)(h & 7u)) & 7u);
+                    atomicMin(cd.slots + (int64_t)t * cd.C + slot, key);
+                }
+            }
+        }
+    };
+    auto clear_cells = [&](int cbuf) {
+#pragma unroll
+        for (int c = 0; c < CELLS; c += 64) sh_cell[wave][cbuf][c + lane] = TG_EMPTY_KEY;
+    };
+
     int64_t w = (int64_t)blockIdx.x * 4 + wave;
     if (w >= count) return;
     WaveItem cur = decode(load_rec(w));
@@ -426,6 +465,8 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         mid = (int)nxt.bids[lane < nxt.nT ? lane : 0];
     }
     int buf = 0;
+    u32 prev_v = 0;
+    int prev_nT = 0;      // members of the block whose cells still wait in LDS
 
     // In round w: block w is multiplied, the rows, norms and thresholds of block w + 1 are
     // fetched (their ids came in one round earlier), and the ids of block w + 2 start travelling.
@@ -447,6 +488,13 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         const float* s_aux = sh_aux[wave][buf];
         const int64_t v = cur.v;
         const int nN = cur.nN, nT = cur.nT, MT = cur.MT, NT = cur.NT;
+        u64* cells = sh_cell[wave][buf];
+        if (MODE == 0) {
+            if (prev_nT > 0) flush_cells(buf ^ 1, prev_v, prev_nT);
+            clear_cells(buf);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
         if (MODE == 0 && stat_bins && lane == 0 && MT > 0) {
             const u64 pairs = (u64)nN * (u64)(nN - 1) / 2 + (u64)nN * (u64)(nT - nN);
             atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), pairs);
@@ -522,7 +570,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         const u32 mo = e_mine == 0 ? ro[0] : e_mine == 1 ? ro[1] : e_mine == 2 ? ro[2] : ro[3];
                         const u32 mi = e_mine == 0 ? ri[0] : e_mine == 1 ? ri[1] : e_mine == 2 ? ri[2] : ri[3];
                         if (r16 < 4 && ((mo < okd_mine) | ((mo == okd_mine) & (mi < kid_mine))))
-                            emit_candidate(cd, s_ids, s_salt, a_mine, mo, mi);
+                            atomicMin(cells + a_mine * GMAX + j, ((u64)mo << 32) | (u64)((mi << 2) | 3u));
                         // Column node b: closest row node of the tile, over the lane's four rows and
                         // then over the four row quarters.
                         u64 cb = ((u64)o[0] << 32) | id_a[0];
@@ -532,7 +580,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         cb = tg_min64(cb, tg_shfl_xor64(cb, 32));
                         const u32 co = (u32)(cb >> 32), ci = (u32)cb;
                         if (q4 == 0 && ((co < okd_b) | ((co == okd_b) & (ci < s_kid[bb]))))
-                            emit_candidate(cd, s_ids, s_salt, b, co, ci);
+                            atomicMin(cells + b * GMAX + i, ((u64)co << 32) | (u64)((ci << 2) | 3u));
                     }
                 }
             }
@@ -549,6 +597,14 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 #pragma unroll
         for (int i = 0; i < GMAX; ++i)
             if (i + 1 >= MT) load_group(i, idn[i]);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (MODE == 0) {
+            // the block's cells wait in LDS for one more round; its member data are needed for
+            // that, so the next block's member data go to the buffer of the block before
+            prev_v = (u32)v;
+            prev_nT = MT > 0 ? nT : 0;
+        }
         park_member(nxt, mid, m_aux, m_kth, buf ^ 1);
         cur = nxt;
         nxt = nxt2;
@@ -557,6 +613,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         mid = mid2;
         buf ^= 1;
     }
+    if (MODE == 0 && prev_nT > 0) flush_cells(buf ^ 1, prev_v, prev_nT);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -449,6 +449,7 @@ void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_e
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg)
 {
+    __shared__ u64 dedup[LISTS_WAVES][64];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
@@ -476,6 +477,22 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         const bool listed = id_in_list(cid, L, k);      // all lanes take part
         if (cid == (u32)v || listed) ck = TG_EMPTY_KEY;
         ck = tg_wave_sort(ck);
+        // The same candidate may sit in several slots (one per block that found it).  The join
+        // computes a pair's distance identically wherever it meets it, so the copies carry
+        // equal keys and are neighbours now: keep the first of each run and close the gaps
+        // before the merge (afterwards the copies could have pushed list entries out).
+        const u64 prev = tg_shfl64(ck, lane > 0 ? lane - 1 : 0);
+        const bool dup = lane > 0 && ck == prev && ck != TG_EMPTY_KEY;
+        const u64 dups = __ballot(dup);
+        if (dups) {
+            const u64 keep = ~dups;
+            if (!dup) dedup[wave][__popcll(keep & tg_lanemask_lt())] = ck;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            ck = lane < __popcll(keep) ? dedup[wave][lane] : TG_EMPTY_KEY;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
         L = tg_wave_merge_low(L, ck);
         if (lane >= k) L = TG_EMPTY_KEY;
     }

@@ -162,24 +162,46 @@ __device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int6
 
 __global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev)
 {
-    const int lane = tg_lane();
+    __shared__ u64 part[4][2][64];
+    const int lane = tg_lane(), wave = threadIdx.x >> 6;
     const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     if (u >= g.n) return;
     const u64 beg = sm.off[u], end = sm.off[u + 1];
+    const u64 lt = tg_lanemask_lt();
     u64 best_new = TG_EMPTY_KEY, best_old = TG_EMPTY_KEY;   // ascending across the wave
     int tot_new = 0, tot_old = 0;
     for (u64 base = beg; base < end; base += 64) {
-        u64 kn = TG_EMPTY_KEY, ko = TG_EMPTY_KEY;
+        // key = priority | class << 31 | source: one sort orders both classes; the class bit sits
+        // below the priority, so inside a class the order is (priority, source)
+        u64 key = TG_EMPTY_KEY;
         if (base + lane < end) {
             const u32 e = sm.csr[base + lane];
             const u32 v = e & TG_ID_MASK;
-            const u64 key = (tg_hash_xy(hs_rev, (u64)v, (u64)u) & 0xFFFFFFFF00000000ull) | (u64)v;
-            if (e >> 31) ko = key; else kn = key;
+            key = (tg_hash_xy(hs_rev, (u64)v, (u64)u) & 0xFFFFFFFF00000000ull) | (u64)e;
         }
-        const int cn = __popcll(__ballot(kn != TG_EMPTY_KEY));
-        const int co = __popcll(__ballot(ko != TG_EMPTY_KEY));
-        if (cn) { best_new = tg_wave_merge_low(best_new, tg_wave_sort(kn)); tot_new += cn; }
-        if (co) { best_old = tg_wave_merge_low(best_old, tg_wave_sort(ko)); tot_old += co; }
+        key = tg_wave_sort(key);
+        const bool is_old = key != TG_EMPTY_KEY && (((u32)key) >> 31);
+        const bool is_new = key != TG_EMPTY_KEY && !(((u32)key) >> 31);
+        const u64 mn = __ballot(is_new), mo = __ballot(is_old);
+        const int cn = __popcll(mn), co = __popcll(mo);
+        // split into two ascending runs through LDS
+        if (is_new) part[wave][0][__popcll(mn & lt)] = key;
+        if (is_old) part[wave][1][__popcll(mo & lt)] = key & ~0x80000000ull;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const u64 kn = lane < cn ? part[wave][0][lane] : TG_EMPTY_KEY;
+        const u64 ko = lane < co ? part[wave][1][lane] : TG_EMPTY_KEY;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (base == beg) {
+            best_new = kn;
+            best_old = ko;
+        } else {
+            if (cn) best_new = tg_wave_merge_low(best_new, kn);
+            if (co) best_old = tg_wave_merge_low(best_old, ko);
+        }
+        tot_new += cn;
+        tot_old += co;
     }
     assemble_block(g, sm, u, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R));
 }

@@ -224,11 +224,18 @@ def test_plain_entry_point_and_early_stop():
     ids0, _ = knn.knn_build(Xg, 16, "l2", iters=0, seed=4)
     prm0 = knn.default_params(16, 0, seed=4)
     o0 = _oracle_for(X, prm0)
-    r1, r2 = o0.run(prm0.it1, prm0.it2, delta=float(np.float32(prm0.delta)))
-    assert r1 < prm0.it1 or r2 < prm0.it2
+    o0.run(prm0.it1, prm0.it2, delta=float(np.float32(prm0.delta)))
     assert (ids0.cpu().numpy() == o0.graph()[0]).all()
     truth, _ = oracle.brute_force_knn(X, 16)
     assert oracle.recall(ids0.cpu().numpy(), truth) > 0.97
+    # a coarser threshold that is certain to end both phases early, at the same rounds as the oracle
+    prm1 = knn.default_params(16, 0, seed=4, delta=0.02)
+    ids1, _, st1 = knn.knn_build_ex(Xg, prm1)
+    o1 = _oracle_for(X, prm1)
+    r1, r2 = o1.run(prm1.it1, prm1.it2, delta=float(np.float32(prm1.delta)))
+    assert r1 < prm1.it1 and r2 < prm1.it2
+    assert (r1, r2) == (st1["rounds_phase1"], st1["rounds_phase2"])
+    assert (ids1.cpu().numpy() == o1.graph()[0]).all()
 
 
 @pytest.mark.parametrize("cfg,metric", [("C1", "l2"), ("C4", "cosine"), ("C4", "ip"), ("C3", "l2")])

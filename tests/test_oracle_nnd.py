@@ -387,15 +387,19 @@ def test_phase2_semantics():
 
 
 def test_candidate_slots_spread_evenly():
-    # the slot function must use all C slots about equally for any one target, and two
-    # candidates that collide at one target or round must not collide at all of them
-    for C in (16, 64, 128):
+    # One (target, anchor) pair owns one line of 8 slots: its opponent groups land in distinct
+    # words of that line.  Over many anchors all C slots of a target are used about equally,
+    # and two anchors that share a line at one target or round do not share it at all of them.
+    for C in (16, 64, 128, 256):
         counts = np.zeros(C)
-        for c in range(4000):
-            s = oracle.slot_of(7, 3, 123, c, C)
-            assert 0 <= s < C
-            counts[s] += 1
+        for v in range(4000):
+            ss = [oracle.slot_of(7, 3, 123, v, g, C) for g in range(8)]
+            assert all(0 <= s < C for s in ss)
+            assert len({s // 8 for s in ss}) == 1 and len(set(ss)) == 8
+            assert [(s - ss[0]) % 8 for s in ss] == list(range(8))     # consecutive words, rotated
+            counts[ss[v % 8]] += 1                                     # one group per anchor, all groups in turn
         mean = 4000 / C                              # counts behave like Poisson(mean)
         assert counts.min() > mean - 5 * mean ** 0.5 and counts.max() < mean + 5 * mean ** 0.5
-    same = sum(oracle.slot_of(7, r, t, 10, 64) == oracle.slot_of(7, r, t, 77, 64) for r in range(20) for t in range(50))
-    assert 2 <= same <= 40          # about 1000 / 64 by chance
+    same = sum(oracle.slot_of(7, r, t, 10, 0, 64) // 8 == oracle.slot_of(7, r, t, 77, 0, 64) // 8
+               for r in range(20) for t in range(50))
+    assert 80 <= same <= 175        # about 1000 / 8 lines by chance
