@@ -447,9 +447,11 @@ void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_e
 // ascending sequences and keeps the first k.  Entries sampled as "new" this round become
 // old; arrivals are new.  Used slots are handed back empty.
 // ---------------------------------------------------------------------------------------
+#define UPDATE_MAX_C 256
 __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg)
 {
     __shared__ u64 dedup[LISTS_WAVES][64];
+    __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
@@ -460,19 +462,32 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
+    // all filled slots of v, closed up in LDS (the slots are handed back empty)
+    const u64 lt = tg_lanemask_lt();
+    int nq = 0;
+    for (int c0 = 0; c0 < cd.C; c0 += 64) {
+        u64* slot = cd.slots + v * (int64_t)cd.C + c0 + lane;
+        const u64 ck = (c0 + lane < cd.C) ? *slot : TG_EMPTY_KEY;
+        const bool filled = ck != TG_EMPTY_KEY;
+        const u64 m = __ballot(filled);
+        if (filled) {
+            *slot = TG_EMPTY_KEY;
+            queue[wave][nq + __popcll(m & lt)] = ck;
+        }
+        nq += __popcll(m);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
     u32 fresh = w >> 31;
     const u64 mf = __ballot(lane < k && fresh);
-    const bool flip = fresh && __popcll(mf & tg_lanemask_lt()) < S;
+    const bool flip = fresh && __popcll(mf & lt) < S;
     if (flip) fresh = 0;
     u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
 
-    bool any_cand = false;
-    for (int c0 = 0; c0 < cd.C; c0 += 64) {
-        u64* slot = cd.slots + v * (int64_t)cd.C + c0 + lane;
-        u64 ck = (c0 + lane < cd.C) ? *slot : TG_EMPTY_KEY;
-        if (__ballot(ck != TG_EMPTY_KEY) == 0) continue;
-        any_cand = true;
-        if (c0 + lane < cd.C) *slot = TG_EMPTY_KEY;
+    const bool any_cand = nq > 0;
+    for (int q0 = 0; q0 < nq; q0 += 64) {
+        u64 ck = q0 + lane < nq ? queue[wave][q0 + lane] : TG_EMPTY_KEY;
         const u32 cid = tg_key_id(ck);
         const bool listed = id_in_list(cid, L, k);      // all lanes take part
         if (cid == (u32)v || listed) ck = TG_EMPTY_KEY;
@@ -486,7 +501,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         const u64 dups = __ballot(dup);
         if (dups) {
             const u64 keep = ~dups;
-            if (!dup) dedup[wave][__popcll(keep & tg_lanemask_lt())] = ck;
+            if (!dup) dedup[wave][__popcll(keep & lt)] = ck;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             ck = lane < __popcll(keep) ? dedup[wave][lane] : TG_EMPTY_KEY;
@@ -508,6 +523,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
 }
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool number_edges, hipStream_t s)
 {
+    if (c.C > UPDATE_MAX_C) return;    // the boundary refuses such C; the queue in LDS holds no more
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
     hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
                        number_edges ? sm.deg : (u32*)nullptr);
