@@ -543,15 +543,39 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------------
+// A set of node ids in LDS (open addressing, linear probing, `mask` + 1 words, always more
+// words than ids, so every probe sequence ends at a free word).  Inserts `id` for the lanes
+// with `active` and tells each whether the id was there already; of several lanes that bring
+// the same new id exactly one is told "new".
+// ---------------------------------------------------------------------------------------
+#define TG_SET_FREE 0xFFFFFFFFu
+__device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, bool active)
+{
+    bool present = false, pending = active;
+    u32 h = (id * 0x9E3779B1u) >> shift;
+    while (__ballot(pending)) {
+        if (pending) {
+            const u32 old = atomicCAS(tab + h, TG_SET_FREE, id);
+            if (old == TG_SET_FREE) pending = false;
+            else if (old == id) { present = true; pending = false; }
+            else h = (h + 1) & mask;
+        }
+    }
+    return present;
+}
+
+// ---------------------------------------------------------------------------------------
 // Algorithm 1 lines 9-12, one wave per node v: take the first m unvisited entries u of
 // G[v], mark them visited, read G[u] from the lists as they stood when the round began
 // (g.gid; this round writes g.gid_next), measure v against the ids that are neither v nor
 // listed nor met earlier in this round, and merge them into G[v].
 // floor(64 / k) neighbour lists are handled per pass, one candidate per lane (k <= 64), so
-// the usual m = 2, k <= 32 round is one gather of ids, one of vectors, one sort, one merge.
+// the usual m = 2, k <= 32 round is one gather of ids and one of vectors.  Membership in G[v]
+// and repeats are settled through an id set in LDS; the few candidates that survive the
+// screening are put into the list one by one (many: sorted and merged).
 // ---------------------------------------------------------------------------------------
 template <bool SCREEN>
-__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, int hist_words, u64* updates, u64* stat_bins)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -561,8 +585,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
     float* xs = smem + (size_t)wave * g.ld;
     u32* wbase = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld);
     u32* wscr = wbase + wave * 128;
-    u32* hist = wbase + LISTS_WAVES * 128 + wave * hist_words;
-    uint4* xq_s = reinterpret_cast<uint4*>(wbase + LISTS_WAVES * (128 + hist_words)) + wave * (g.ldq >> 4);
+    u32* seen = wbase + LISTS_WAVES * 128 + wave * set_words;      // ids of G[v] and of every candidate met this round
+    uint4* xq_s = reinterpret_cast<uint4*>(wbase + LISTS_WAVES * (128 + set_words)) + wave * (g.ldq >> 4);
+    const u32 set_mask = (u32)set_words - 1u;
+    const int set_shift = 33 - __ffs(set_words);                    // top log2(set_words) bits of the hash
 
     u32 w = 0;
     float dist = 0.0f;
@@ -574,19 +600,24 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         const uint4* src = reinterpret_cast<const uint4*>(g.Xq + v * (int64_t)g.ldq);
         for (int i = lane; i < (g.ldq >> 4); i += 64) xq_s[i] = src[i];
     }
+    for (int i = lane; i < set_words; i += 64) seen[i] = TG_SET_FREE;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     u32 fresh = w >> 31;
     u64 mf = __ballot(lane < k && fresh);
     if (fresh && __popcll(mf & tg_lanemask_lt()) < m) fresh = 0;   // non-revisitation
     u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
-    const u64 L0 = L;                                              // the list as the round found it
     const u32 my_id = w & TG_ID_MASK;
+    (void)lds_set_insert(seen, set_mask, set_shift, my_id, lane < k);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
     const float norm_v = g.metric != 0 ? sqrtf(g.nrm[v]) : 0.0f;
     const int nexp = min(m, __popcll(mf));
     const int per = 64 / k;
     bool staged = false;
 
-    int evaluated = 0, measured = 0, nhist = 0;
+    int evaluated = 0, measured = 0;
     for (int e0 = 0; e0 < nexp; e0 += per) {
         const int nb = min(per, nexp - e0);
         const int my_e = lane / k, j = lane - my_e * k;
@@ -598,23 +629,11 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
             if (q == my_e) src = sbit;
         }
         const u32 u = (u32)__shfl((int)my_id, src);
-        u32 cid = in ? (g.gid[(int64_t)u * k + j] & TG_ID_MASK) : 0xFFFFFFFFu;
-        bool drop = !in || cid == (u32)v;
-        drop |= id_in_list(cid, L0, k);                            // all lanes take part
-        for (int q = 0; q < (nb - 1) * k; ++q) {                   // the same id from an earlier list of this pass
-            const u32 cq = (u32)__builtin_amdgcn_readlane((int)cid, q);
-            drop |= (q < my_e * k) & (cq == cid);
-        }
-        for (int q = 0; q < nhist; ++q) drop |= (hist[q] == cid);  // ... or of an earlier pass
-        const u64 live = __ballot(!drop);
-        const int nlive = __popcll(live);
-        evaluated += nlive;
-        if (e0 + per < nexp) {
-            if (!drop) hist[nhist + __popcll(live & tg_lanemask_lt())] = cid;
-            nhist += nlive;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        const u32 cid = in ? (g.gid[(int64_t)u * k + j] & TG_ID_MASK) : 0xFFFFFFFFu;
+        // a candidate counts once per round, and not at all if it is v or sits in G[v]
+        const bool fresh_id = in && cid != (u32)v;
+        const bool drop = !fresh_id | lds_set_insert(seen, set_mask, set_shift, cid, fresh_id);
+        evaluated += __popcll(__ballot(!drop));
         // candidates that provably cannot precede the list's last entry are dropped on the 8-bit copy
         int cand = drop ? -1 : (int)cid;
         if (SCREEN) {
@@ -623,16 +642,32 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         }
         const u64 alive = __ballot(cand >= 0);
         if (alive == 0) continue;
-        measured += __popcll(alive);
+        const int nalive = __popcll(alive);
+        measured += nalive;
         if (!staged) {
             stage_row(g, v, xs);
             staged = true;
         }
         const float cdist = wave_direct_dist<SCREEN ? 1 : 8>(g, xs, rn_v, cand, wscr);
         u64 ck = cand >= 0 ? tg_key(cdist, (u32)cand, 3u) : TG_EMPTY_KEY;
-        ck = tg_wave_sort(ck);
-        L = tg_wave_merge_low(L, ck);
-        if (lane >= k) L = TG_EMPTY_KEY;
+        if (nalive <= 4) {
+            // a few survivors: put each at its rank, entries behind it move up by one
+            u64 rem = alive;
+            while (rem) {
+                const int sl = __ffsll((long long)rem) - 1;
+                rem &= rem - 1;
+                const u64 key = ((u64)(u32)__builtin_amdgcn_readlane((int)(ck >> 32), sl) << 32) |
+                                (u64)(u32)__builtin_amdgcn_readlane((int)(u32)ck, sl);
+                const int pos = __popcll(__ballot(L < key));
+                const u64 up = tg_shfl64(L, lane > 0 ? lane - 1 : 0);
+                L = lane < pos ? L : (lane == pos ? key : up);
+                if (lane >= k) L = TG_EMPTY_KEY;
+            }
+        } else {
+            ck = tg_wave_sort(ck);
+            L = tg_wave_merge_low(L, ck);
+            if (lane >= k) L = TG_EMPTY_KEY;
+        }
     }
     const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
     if (lane < k) {
@@ -650,12 +685,14 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
 }
 void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
 {
-    const int hist_words = (m * g.k + 3) & ~3;
-    const size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)hist_words) * sizeof(u32) +
+    // the id set holds the k listed ids and at most m k candidates; half as many words again, as a power of two
+    int set_words = 64;
+    while (set_words * 2 < 3 * (g.k + m * g.k)) set_words *= 2;
+    const size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)set_words) * sizeof(u32) +
                        (size_t)LISTS_WAVES * (g.Xq ? g.ldq : 0);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    if (g.Xq) hipLaunchKernelGGL(phase2_kernel<true>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, hist_words, updates, stat_bins);
-    else hipLaunchKernelGGL(phase2_kernel<false>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, hist_words, updates, stat_bins);
+    if (g.Xq) hipLaunchKernelGGL(phase2_kernel<true>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
+    else hipLaunchKernelGGL(phase2_kernel<false>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
 }
 
 // ---------------------------------------------------------------------------------------
