@@ -340,7 +340,7 @@ struct WaveItem {
 // work record: anchor | |NEW| << 32 | (|NEW|+|OLD|) << 40
 __device__ inline u64 pack_rec(u32 v, int nN, int nT) { return (u64)v | ((u64)nN << 32) | ((u64)nT << 40); }
 
-template <int GMAX, int MODE, int METRIC, int KS>
+template <int GMAX, int MODE, int METRIC, int KS, bool FULL>
 __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
                                                         const int32_t* xblk, const int32_t* xsizes, float* xout,
                                                         const u64* __restrict__ wl, const u32* __restrict__ wl_cnt,
@@ -395,11 +395,16 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         const float* x = g.X + (int64_t)id * g.ld;
 #pragma unroll
         for (int s8 = 0; s8 < KS; ++s8) {
-            // unconditional load at a clamped column, zeroed afterwards when the column is padding
             const int col = 16 * s8 + 4 * q4;
-            const bool real = col < g.ld;
-            const float4 val = *reinterpret_cast<const float4*>(x + (real ? col : 0));
-            X[t][s8] = real ? val : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (FULL) {
+                // rows of exactly 16 KS floats: nothing to mask
+                X[t][s8] = *reinterpret_cast<const float4*>(x + col);
+            } else {
+                // unconditional load at a clamped column, zeroed afterwards when the column is padding
+                const bool real = col < g.ld;
+                const float4 val = *reinterpret_cast<const float4*>(x + (real ? col : 0));
+                X[t][s8] = real ? val : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
     };
     // per-member data (one member per lane): fetched into registers, parked in LDS one block ahead
@@ -696,9 +701,14 @@ static void launch_wave_k(const TgGraph& g, const TgSample& sm, const TgCand& c,
 {
     const int64_t wgs = (g.n + 3) / 4;
     const unsigned grid = (unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID);
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
-                       (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
-                       (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+    if (g.ld == 16 * KS)
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, true>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+                           (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
+                           (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+    else
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, false>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+                           (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
+                           (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
 }
 template <int GMAX, int METRIC, int KS>
 static void launch_wave_dump_k(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out, int gmin,
@@ -707,7 +717,7 @@ static void launch_wave_dump_k(const TgGraph& g, const int32_t* blk, const int32
     TgSample sm = {};
     TgCand c = {};
     const int64_t wgs = (nb + 3) / 4;
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0,
+    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS, false>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0,
                        s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
 }
 // rows of at most 64 / 96 / 128 floats take 4 / 6 / 8 column steps per lane quarter
