@@ -442,16 +442,39 @@ void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_e
 }
 
 // ---------------------------------------------------------------------------------------
+// A set of node ids in LDS (open addressing, linear probing, `mask` + 1 words, always more
+// words than ids, so every probe sequence ends at a free word).  Inserts `id` for the lanes
+// with `active` and tells each whether the id was there already; of several lanes that bring
+// the same new id exactly one is told "new".
+// ---------------------------------------------------------------------------------------
+#define TG_SET_FREE 0xFFFFFFFFu
+__device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, bool active)
+{
+    bool present = false, pending = active;
+    u32 h = (id * 0x9E3779B1u) >> shift;
+    while (__ballot(pending)) {
+        if (pending) {
+            const u32 old = atomicCAS(tab + h, TG_SET_FREE, id);
+            if (old == TG_SET_FREE) pending = false;
+            else if (old == id) { present = true; pending = false; }
+            else h = (h + 1) & mask;
+        }
+    }
+    return present;
+}
+
+// ---------------------------------------------------------------------------------------
 // Section 4.2 list update (phase 1).  The wave that owns list v reads the list and v's
 // candidate slots, drops candidates the list already holds, sorts the rest, merges the two
 // ascending sequences and keeps the first k.  Entries sampled as "new" this round become
 // old; arrivals are new.  Used slots are handed back empty.
 // ---------------------------------------------------------------------------------------
 #define UPDATE_MAX_C 256
+#define UPDATE_SET_WORDS 512     // more than 64 + UPDATE_MAX_C ids
 __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg)
 {
-    __shared__ u64 dedup[LISTS_WAVES][64];
     __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
+    __shared__ u32 seen_s[LISTS_WAVES][UPDATE_SET_WORDS];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
@@ -476,9 +499,6 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         }
         nq += __popcll(m);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
     u32 fresh = w >> 31;
     const u64 mf = __ballot(lane < k && fresh);
     const bool flip = fresh && __popcll(mf & lt) < S;
@@ -486,30 +506,31 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
 
     const bool any_cand = nq > 0;
-    for (int q0 = 0; q0 < nq; q0 += 64) {
-        u64 ck = q0 + lane < nq ? queue[wave][q0 + lane] : TG_EMPTY_KEY;
-        const u32 cid = tg_key_id(ck);
-        const bool listed = id_in_list(cid, L, k);      // all lanes take part
-        if (cid == (u32)v || listed) ck = TG_EMPTY_KEY;
-        ck = tg_wave_sort(ck);
-        // The same candidate may sit in several slots (one per block that found it).  The join
-        // computes a pair's distance identically wherever it meets it, so the copies carry
-        // equal keys and are neighbours now: keep the first of each run and close the gaps
-        // before the merge (afterwards the copies could have pushed list entries out).
-        const u64 prev = tg_shfl64(ck, lane > 0 ? lane - 1 : 0);
-        const bool dup = lane > 0 && ck == prev && ck != TG_EMPTY_KEY;
-        const u64 dups = __ballot(dup);
-        if (dups) {
-            const u64 keep = ~dups;
-            if (!dup) dedup[wave][__popcll(keep & lt)] = ck;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            ck = lane < __popcll(keep) ? dedup[wave][lane] : TG_EMPTY_KEY;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+    if (any_cand) {
+        // ids of G[v], then every candidate: a candidate that is listed, or a repeat (the same
+        // candidate may sit in several slots, one per block that found it), finds its id there
+        u32* seen = seen_s[wave];
+        int set_words = 128;
+        while (set_words * 2 < 3 * (k + nq)) set_words *= 2;          // at most UPDATE_SET_WORDS
+        const u32 set_mask = (u32)set_words - 1u;
+        const int set_shift = 33 - __ffs(set_words);
+        for (int i = lane; i < set_words; i += 64) seen[i] = TG_SET_FREE;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        (void)lds_set_insert(seen, set_mask, set_shift, w & TG_ID_MASK, lane < k);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int q0 = 0; q0 < nq; q0 += 64) {
+            u64 ck = q0 + lane < nq ? queue[wave][q0 + lane] : TG_EMPTY_KEY;
+            const u32 cid = tg_key_id(ck);
+            const bool cand = ck != TG_EMPTY_KEY && cid != (u32)v;
+            const bool known = lds_set_insert(seen, set_mask, set_shift, cid, cand);
+            if (!cand || known) ck = TG_EMPTY_KEY;
+            if (__ballot(ck != TG_EMPTY_KEY) == 0) continue;
+            ck = tg_wave_sort(ck);
+            L = tg_wave_merge_low(L, ck);
+            if (lane >= k) L = TG_EMPTY_KEY;
         }
-        L = tg_wave_merge_low(L, ck);
-        if (lane >= k) L = TG_EMPTY_KEY;
     }
     if (deg) number_sampled_edges(v, k, S, tg_key_id(L), ((u32)L & 1u) != 0, deg, g.gid_next);
     if (!any_cand && mf == 0) return;
@@ -540,28 +561,6 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 {
     size_t count = (size_t)g.n * g.k;
     hipLaunchKernelGGL(mark_fresh_kernel, dim3(grid_for(count, 256)), dim3(256), 0, s, g.gid, count);
-}
-
-// ---------------------------------------------------------------------------------------
-// A set of node ids in LDS (open addressing, linear probing, `mask` + 1 words, always more
-// words than ids, so every probe sequence ends at a free word).  Inserts `id` for the lanes
-// with `active` and tells each whether the id was there already; of several lanes that bring
-// the same new id exactly one is told "new".
-// ---------------------------------------------------------------------------------------
-#define TG_SET_FREE 0xFFFFFFFFu
-__device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, bool active)
-{
-    bool present = false, pending = active;
-    u32 h = (id * 0x9E3779B1u) >> shift;
-    while (__ballot(pending)) {
-        if (pending) {
-            const u32 old = atomicCAS(tab + h, TG_SET_FREE, id);
-            if (old == TG_SET_FREE) pending = false;
-            else if (old == id) { present = true; pending = false; }
-            else h = (h + 1) & mask;
-        }
-    }
-    return present;
 }
 
 // ---------------------------------------------------------------------------------------
