@@ -94,6 +94,7 @@ struct tg_knn_handle {
     u64* d_stat_bins;    // TG_MAX_ROUNDS x 2 x TG_STAT_BINS
     float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
+    float* xqm;          // its row constants
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -123,9 +124,11 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.gid_next = c.take<u32>((size_t)n * p.k);
     h->g.gdist = c.take<float>((size_t)n * p.k);
     h->g.kth = c.take<u64>(n);
-    h->g.ldq = ((d + 15) & ~15) + 32;
+    h->g.ldq = (d + 15) & ~15;
     h->xq = p.screen ? c.take<uint8_t>((size_t)n * h->g.ldq) : nullptr;
+    h->xqm = p.screen ? c.take<float>((size_t)n * 8) : nullptr;
     h->g.Xq = h->xq;
+    h->g.Xqm = h->xqm;
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);
     h->sm.off = c.take<u64>(n + 1);
@@ -299,7 +302,7 @@ extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
     if (!h->phase2 && h->xq) {
         ensure_norms(h);
         int sp = begin_span(h, SPAN_NORMS, 0);
-        tg_launch_quantize(h->g, h->xq, h->stream);
+        tg_launch_quantize(h->g, h->xq, h->xqm, h->stream);
         end_span(h, sp);
     }
     h->phase2 = true;

@@ -21,8 +21,9 @@ struct TgGraph {
     uint32_t* gid_next; // n x k, written by a phase-2 round; in phase 1 it holds the arrival number of every sampled edge
     float* gdist;     // n x k
     unsigned long long* kth;   // n: key of each list's last entry with both low bits set
-    const uint8_t* Xq;  // n x ldq bytes: 8-bit codes of every row followed by 32 bytes of row constants (phase-2 screening), or null
-    int32_t ldq;        // d rounded up to 16, plus 32
+    const uint8_t* Xq;  // n x ldq bytes: 8-bit codes of every row (phase-2 screening), or null
+    const float* Xqm;   // n x 8: the row constants that go with the codes
+    int32_t ldq;        // d rounded up to 16: a row of codes never straddles more lines than it must
 };
 
 struct TgSample {
@@ -45,7 +46,7 @@ struct TgCand {
 
 void tg_launch_norms(const TgGraph& g, hipStream_t s);
 void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges /* or null */, hipStream_t s);
-void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, hipStream_t s);
+void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s);
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
 void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool edges_numbered, hipStream_t s);

@@ -93,11 +93,11 @@ void tg_launch_norms(const TgGraph& g, hipStream_t s)
 // ---------------------------------------------------------------------------------------
 // 8-bit screening copy of X for phase 2.  Row x becomes codes q_i = round((x_i - lo) / s) in
 // 0..255 with lo = min x_i, s = (max x_i - lo) / 255, i.e. the vector xq_i = lo + s q_i, and
-// eight row constants: lo, s, err >= |x - xq|, sum q_i, |xq|^2, sum (|lo| + s q_i)^2,
+// eight row constants (an array of their own, small enough to stay in cache): lo, s, err >= |x - xq|, sum q_i, |xq|^2, sum (|lo| + s q_i)^2,
 // 1/|x| (cosine) and a spare.  With them <xq, yq> follows from the integer dot product of
 // the codes, and |x - y| >= |xq - yq| - err_x - err_y bounds the true distance from below.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq)
+__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq, float* __restrict__ Xqm)
 {
     const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int sub = threadIdx.x & 15;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __res
     const float s = hi > lo ? (hi - lo) / 255.0f : 1.0f;
     const float inv = 1.0f / s;
     const float alo = fabsf(lo);
-    const int dq = g.ldq - 32;
+    const int dq = g.ldq;
     uint8_t* out = Xq + (live ? row : 0) * (int64_t)g.ldq;
     float err2 = 0.0f, qn2 = 0.0f, an2 = 0.0f, sumq = 0.0f;
     for (int c = sub * 4; c < dq; c += 64) {
@@ -151,15 +151,15 @@ __global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __res
         sumq += __shfl_xor(sumq, o);
     }
     if (live && sub == 0) {
-        float4* m = reinterpret_cast<float4*>(out + dq);
+        float4* m = reinterpret_cast<float4*>(Xqm + row * 8);
         m[0] = make_float4(lo, s, sqrtf(err2) * 1.0001f, sumq);
         m[1] = make_float4(qn2, an2, g.metric == 2 ? g.rnorm[row] : 0.0f, 0.0f);
     }
 }
-void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, hipStream_t s)
+void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s)
 {
     int64_t blocks = (g.n + 15) / 16;
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g, Xq);
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g, Xq, Xqm);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -287,7 +287,7 @@ __device__ inline int wave_screen(const TgGraph& g, const uint4* xq_s, float nor
     if (valid) wscr[__popcll(mask & tg_lanemask_lt())] = (u32)cid;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    const int nch = (g.ldq - 32) >> 4;
+    const int nch = g.ldq >> 4;
     u32 rows[8], dot[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
@@ -322,7 +322,7 @@ __device__ inline int wave_screen(const TgGraph& g, const uint4* xq_s, float nor
     const int p = 8 * sub + c8;
     const bool mine = p < nv;
     const u32 row = wscr[mine ? p : nv - 1];
-    const float4* my = reinterpret_cast<const float4*>(g.Xq + (int64_t)row * g.ldq + (g.ldq - 32));
+    const float4* my = reinterpret_cast<const float4*>(g.Xqm + (int64_t)row * 8);
     const float4 m0 = my[0], m1 = my[1];
     u32 d8 = 0u;
 #pragma unroll
@@ -574,7 +574,7 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 // screening are put into the list one by one (many: sorted and merged).
 // ---------------------------------------------------------------------------------------
 template <bool SCREEN>
-__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
+__device__ __forceinline__ void phase2_body(const TgGraph& g, int m, int set_words, u64* updates, u64* stat_bins)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -585,7 +585,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
     u32* wbase = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld);
     u32* wscr = wbase + wave * 128;
     u32* seen = wbase + LISTS_WAVES * 128 + wave * set_words;      // ids of G[v] and of every candidate met this round
-    uint4* xq_s = reinterpret_cast<uint4*>(wbase + LISTS_WAVES * (128 + set_words)) + wave * (g.ldq >> 4);
+    uint4* xq_s = reinterpret_cast<uint4*>(wbase + LISTS_WAVES * (128 + set_words)) + wave * ((g.ldq >> 4) + 2);
     const u32 set_mask = (u32)set_words - 1u;
     const int set_shift = 33 - __ffs(set_words);                    // top log2(set_words) bits of the hash
 
@@ -596,8 +596,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         dist = g.gdist[v * k + lane];
     }
     if (SCREEN) {
+        const int nch = g.ldq >> 4;
         const uint4* src = reinterpret_cast<const uint4*>(g.Xq + v * (int64_t)g.ldq);
-        for (int i = lane; i < (g.ldq >> 4); i += 64) xq_s[i] = src[i];
+        const uint4* srcm = reinterpret_cast<const uint4*>(g.Xqm + v * 8);
+        for (int i = lane; i < nch + 2; i += 64) xq_s[i] = i < nch ? src[i] : srcm[i - nch];
     }
     for (int i = lane; i < set_words; i += 64) seen[i] = TG_SET_FREE;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -682,16 +684,26 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_kernel(TgGraph g, int
         }
     }
 }
+// the screening variant is latency bound: five waves per SIMD (96 registers) instead of four
+__global__ __launch_bounds__(64 * LISTS_WAVES) __attribute__((amdgpu_waves_per_eu(5)))
+void phase2_screen_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
+{
+    phase2_body<true>(g, m, set_words, updates, stat_bins);
+}
+__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_plain_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
+{
+    phase2_body<false>(g, m, set_words, updates, stat_bins);
+}
 void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
 {
     // the id set holds the k listed ids and at most m k candidates; half as many words again, as a power of two
     int set_words = 64;
     while (set_words * 2 < 3 * (g.k + m * g.k)) set_words *= 2;
     const size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)set_words) * sizeof(u32) +
-                       (size_t)LISTS_WAVES * (g.Xq ? g.ldq : 0);
+                       (size_t)LISTS_WAVES * (g.Xq ? g.ldq + 32 : 0);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    if (g.Xq) hipLaunchKernelGGL(phase2_kernel<true>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
-    else hipLaunchKernelGGL(phase2_kernel<false>, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
+    if (g.Xq) hipLaunchKernelGGL(phase2_screen_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
+    else hipLaunchKernelGGL(phase2_plain_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
 }
 
 // ---------------------------------------------------------------------------------------
