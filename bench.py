@@ -134,7 +134,7 @@ def main():
         "recall_at_k": recall,
         "recall_ok": bool(recall >= 0.95),
         "join_mfma_pct": 100.0 * achieved / MFMA_FP32_PEAK_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "phase-1 local join (join_wave_kernel<3>, <4> and join_kernel of one round)",
+        "roofline": {"bound": "mfma", "kernel": "phase-1 local join (bin_kernel, join_wave_kernel<3>, <4> and join_kernel of one round)",
                      "achieved": achieved,
                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK_TFLOPS,
                      "avg_launch_ms": avg_launch_ms, "launches": launches, "gather_GBps": gather_gbs,
