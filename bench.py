@@ -58,8 +58,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=20000)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU; run with --gpus 1 (the method shards by node range, "
-              "see DESIGN.md, but no multi-GPU path is built)", file=sys.stderr)
+        print("bench.py: this build measures one GPU; run with --gpus 1 (the method would shard by node range, "
+              "but no multi-GPU path is built)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
