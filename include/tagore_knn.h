@@ -60,7 +60,9 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *   screen   1: a phase-2 round first bounds every candidate's distance from below on an
  *            8-bit copy of the vectors (n x (d + 47) bytes of workspace) and measures in fp32
  *            only those that may still enter the list; the bound is rigorous, so the graph is
- *            the same as with 0, which measures every candidate (section 4.1 as written)
+ *            the same as with 0, which measures every candidate (section 4.1 as written).
+ *            When more than half of a round's candidates pass the bound (real-valued data in
+ *            high dimension) the following rounds measure every candidate directly
  */
 typedef struct tg_knn_params {
     int32_t k;

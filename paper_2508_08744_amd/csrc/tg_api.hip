@@ -95,6 +95,7 @@ struct tg_knn_handle {
     float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     float* xqm;          // its row constants
+    u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -129,6 +130,7 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->xqm = p.screen ? c.take<float>((size_t)n * 8) : nullptr;
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
+    h->d_screen_on = c.take<u32>(64);
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);
     h->sm.off = c.take<u64>(n + 1);
@@ -299,6 +301,7 @@ extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
         tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
         h->edges_numbered = false;
     }
+    if (h->xq) tg_launch_fill_u32(h->d_screen_on, 1, 1u, h->stream);
     if (!h->phase2 && h->xq) {
         ensure_norms(h);
         int sp = begin_span(h, SPAN_NORMS, 0);
@@ -316,7 +319,8 @@ extern "C" int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates)
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
     int sp = begin_span(h, SPAN_JOIN, r);
-    tg_launch_phase2(h->g, h->p.m, h->d_updates + (size_t)r * TG_STAT_BINS, h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
+    tg_launch_phase2(h->g, h->p.m, h->d_updates + (size_t)r * TG_STAT_BINS, h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->d_screen_on,
+                     h->stream);
     end_span(h, sp);
     u32* t = h->g.gid; h->g.gid = h->g.gid_next; h->g.gid_next = t;   // the written lists are current now
     h->round++;

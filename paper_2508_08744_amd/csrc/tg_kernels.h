@@ -59,8 +59,8 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, unsigned long long* updates,
                       bool number_edges, hipStream_t s);
 void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
-void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates,
-                      unsigned long long* stat_bins, hipStream_t s);
+void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates, unsigned long long* stat_bins,
+                      uint32_t* screen_on /* device flag, used when g.Xq is set */, hipStream_t s);
 void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s);
 void tg_launch_export(const TgGraph& g, int32_t* ids, float* dist, uint8_t* fresh, hipStream_t s);
 void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s);

@@ -574,12 +574,10 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 // screening are put into the list one by one (many: sorted and merged).
 // ---------------------------------------------------------------------------------------
 template <bool SCREEN>
-__device__ __forceinline__ void phase2_body(const TgGraph& g, int m, int set_words, u64* updates, u64* stat_bins)
+__device__ __forceinline__ void phase2_node(const TgGraph& g, int64_t v, int m, int set_words, u64* updates, u64* stat_bins)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
-    if (v >= g.n) return;
     const int k = g.k;
     float* xs = smem + (size_t)wave * g.ld;
     u32* wbase = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld);
@@ -679,22 +677,62 @@ __device__ __forceinline__ void phase2_body(const TgGraph& g, int m, int set_wor
     if (lane == 0) {
         if (ins) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
         if (stat_bins && evaluated) {
-            atomicAdd(stat_bins + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)evaluated);                 // pairs
-            if (measured) atomicAdd(stat_bins + TG_STAT_BINS + (blockIdx.x & (TG_STAT_BINS - 1)), (u64)measured);  // fp32 vectors
+            atomicAdd(stat_bins + (v & (TG_STAT_BINS - 1)), (u64)evaluated);                          // pairs
+            if (measured) atomicAdd(stat_bins + TG_STAT_BINS + (v & (TG_STAT_BINS - 1)), (u64)measured);  // fp32 vectors
         }
+    }
+}
+// Workgroups walk the nodes with the stride of the grid.  Both variants are launched when a
+// screening copy exists; the flag says whose turn it is, and the other one ends at once.
+template <bool SCREEN>
+__device__ __forceinline__ void phase2_body(const TgGraph& g, int m, int set_words, u64* updates, u64* stat_bins,
+                                            const u32* __restrict__ screen_on)
+{
+    if (screen_on && (*screen_on != 0u) != SCREEN) return;
+    const int wave = threadIdx.x >> 6;
+    for (int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave; v < g.n; v += (int64_t)gridDim.x * LISTS_WAVES) {
+        phase2_node<SCREEN>(g, v, m, set_words, updates, stat_bins);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 // the screening variant is latency bound: five waves per SIMD (96 registers) instead of four
 __global__ __launch_bounds__(64 * LISTS_WAVES) __attribute__((amdgpu_waves_per_eu(5)))
-void phase2_screen_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
+void phase2_screen_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins, const u32* screen_on)
 {
-    phase2_body<true>(g, m, set_words, updates, stat_bins);
+    phase2_body<true>(g, m, set_words, updates, stat_bins, screen_on);
 }
-__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_plain_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void phase2_plain_kernel(TgGraph g, int m, int set_words, u64* updates, u64* stat_bins,
+                                                                        const u32* screen_on)
 {
-    phase2_body<false>(g, m, set_words, updates, stat_bins);
+    phase2_body<false>(g, m, set_words, updates, stat_bins, screen_on);
 }
-void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hipStream_t s)
+// Screening pays when the 8-bit codes are nearly lossless (byte-valued features); on real-valued
+// data in high dimension most candidates pass the bound and its reads are wasted.  After a
+// screened round: if more than half of the candidates went on to the fp32 evaluation, the
+// following rounds measure every candidate directly.
+__global__ __launch_bounds__(256) void screen_decide_kernel(const u64* __restrict__ stat_bins, u32* screen_on)
+{
+    __shared__ u64 red[2][4];
+    u64 pairs = 0, measured = 0;
+    for (int i = threadIdx.x; i < TG_STAT_BINS; i += 256) {
+        pairs += stat_bins[i];
+        measured += stat_bins[TG_STAT_BINS + i];
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        pairs += tg_shfl_xor64(pairs, o);
+        measured += tg_shfl_xor64(measured, o);
+    }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = pairs; red[1][threadIdx.x >> 6] = measured; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        pairs = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        measured = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+        if (*screen_on != 0u && 2 * measured > pairs) *screen_on = 0u;
+    }
+}
+#define PHASE2_GRID 16384
+void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, u32* screen_on, hipStream_t s)
 {
     // the id set holds the k listed ids and at most m k candidates; half as many words again, as a power of two
     int set_words = 64;
@@ -702,8 +740,17 @@ void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, hip
     const size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * (128 + (size_t)set_words) * sizeof(u32) +
                        (size_t)LISTS_WAVES * (g.Xq ? g.ldq + 32 : 0);
     int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    if (g.Xq) hipLaunchKernelGGL(phase2_screen_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
-    else hipLaunchKernelGGL(phase2_plain_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins);
+    if (blocks > PHASE2_GRID) blocks = PHASE2_GRID;
+    if (g.Xq) {
+        hipLaunchKernelGGL(phase2_screen_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins,
+                           (const u32*)screen_on);
+        hipLaunchKernelGGL(phase2_plain_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins,
+                           (const u32*)screen_on);
+        hipLaunchKernelGGL(screen_decide_kernel, dim3(1), dim3(256), 0, s, (const u64*)stat_bins, screen_on);
+    } else {
+        hipLaunchKernelGGL(phase2_plain_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, m, set_words, updates, stat_bins,
+                           (const u32*)nullptr);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

@@ -200,6 +200,24 @@ def test_screening_never_changes_the_graph(metric, d):
     assert out[0][2]["updates"] == out[1][2]["updates"]
 
 
+def test_screening_switches_itself_off_where_it_does_not_pay():
+    """Byte-valued data: few candidates reach the fp32 evaluation in every phase-2 round.  Real-valued
+    data in high dimension: most pass the 8-bit bound in the first screened round, and from the second
+    round on every candidate is measured directly (fp32 vectors == candidates)."""
+    Xi = inputs.make("C2", n=20000, d=128, comps=20)
+    Xr = inputs.make("C4", n=20000, comps=20)
+    for X, metric, pays in ((Xi, "l2", True), (Xr, "cosine", False)):
+        prm = knn.default_params(16, 8, metric=metric, seed=3)
+        _, _, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        r1 = st["rounds_phase1"]
+        pairs, vecs = st["join_pairs"][r1:], st["join_vectors"][r1:]
+        if pays:
+            assert all(v < 0.25 * p for v, p in zip(vecs, pairs)), (pairs, vecs)
+        else:
+            assert vecs[0] > 0.5 * pairs[0] and vecs[0] < pairs[0]
+            assert vecs[1:] == pairs[1:], (pairs, vecs)
+
+
 @pytest.mark.parametrize("iters", [1, 6, 9])
 def test_whole_build_identical_to_oracle(iters):
     X = inputs.make("C2", n=2000, d=48, comps=4)
