@@ -15,6 +15,7 @@
 
 #define JOIN_THREADS 256
 #define JOIN_HDR_BYTES 2560   // salt[128], kd[128], kid[128], ids[128], aux[128]
+#define JOIN_CELL_BYTES (TG_BLOCK_COLS * 8 * 8)   // one cell per member and opponent group (workgroup kernel)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -88,8 +89,7 @@ __device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
 // and the candidate of group q goes to word (q + rotation) % 8 of it, where it stays if it is
 // the smaller (dist, id): one 64-bit atomic minimum, no order dependence.  All candidates one
 // block has for t share a line, so they can travel in one memory transaction.
-__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, u32 odist, u32 c,
-                                      u32 v, int q)
+__device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const u32* s_salt, int tpos, u64 key, u32 v, int q)
 {
     const u32 t = (u32)s_ids[tpos];
     u32 h = (s_salt[tpos] + v) * 0x9E3779B1u;
@@ -98,7 +98,7 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
     h ^= h >> 13;
     const u32 line = h >> (36 - __ffs(cd.C));        // C / 8 lines
     const u32 slot = line * 8u + ((u32)(q + (int)(h & 7u)) & 7u);
-    atomicMin(cd.slots + (int64_t)t * cd.C + slot, ((u64)odist << 32) | (u64)((c << 2) | 3u));
+    atomicMin(cd.slots + (int64_t)t * cd.C + slot, key);
 }
 
 // MODE 0: emit candidates for the stored blocks.  MODE 1: write the distance tile of caller-given blocks.
@@ -114,13 +114,17 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     u32* s_kid = reinterpret_cast<u32*>(s_kd + TG_BLOCK_COLS);          //            and its id
     int* s_ids = reinterpret_cast<int*>(s_kid + TG_BLOCK_COLS);
     float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);     // squared norm (or 1/|x| for cosine)
-    float* tile = reinterpret_cast<float*>(smem_raw + JOIN_HDR_BYTES);
+    u64* s_cell = reinterpret_cast<u64*>(smem_raw + JOIN_HDR_BYTES);   // candidates of the block in hand
+    float* tile = reinterpret_cast<float*>(smem_raw + JOIN_HDR_BYTES + JOIN_CELL_BYTES);
     constexpr int LDT = DK + 4;          // LDS row stride in floats (16-byte pad against bank conflicts)
     constexpr int F4 = DK / 4;           // float4 per row and slab
     constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
+    if (MODE == 0) {
+        for (int c = tid; c < TG_BLOCK_COLS * 8; c += JOIN_THREADS) s_cell[c] = TG_EMPTY_KEY;
+    }
     for (int64_t w = blockIdx.x; w < count; w += gridDim.x) {
     const int64_t v = wl ? (int64_t)(u32)wl[w] : w;
     int nN, nT;
@@ -293,7 +297,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 const float md = c16 == 0 ? rbd[0] : c16 == 1 ? rbd[1] : c16 == 2 ? rbd[2] : rbd[3];
                 const u32 mi = c16 == 0 ? rbi[0] : c16 == 1 ? rbi[1] : c16 == 2 ? rbi[2] : rbi[3];
                 const int a = 16 * i + 4 * g4 + c16;
-                if (c16 < 4 && mi != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, a, tg_ord(md), mi, (u32)v, wc + 2 * cg);
+                if (c16 < 4 && mi != TG_NO_ID) atomicMin(s_cell + a * 8 + (wc + 2 * cg), ((u64)tg_ord(md) << 32) | (u64)((mi << 2) | 3u));
             }
         }
     }
@@ -309,7 +313,18 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                 pairmin(d0, i0, __shfl_xor(d0, 16), (u32)__shfl_xor((int)i0, 16));
                 pairmin(d0, i0, __shfl_xor(d0, 32), (u32)__shfl_xor((int)i0, 32));
                 const int b = 16 * j + c16;
-                if (g4 == 0 && i0 != TG_NO_ID) emit_candidate(cd, s_ids, s_salt, b, tg_ord(d0), i0, (u32)v, wr + 2 * rg);
+                if (g4 == 0 && i0 != TG_NO_ID) atomicMin(s_cell + b * 8 + (wr + 2 * rg), ((u64)tg_ord(d0) << 32) | (u64)((i0 << 2) | 3u));
+            }
+        }
+        // Hand-over: the eight cells of a member sit in eight neighbouring lanes and their slots
+        // share a 64-byte line, so a member's candidates travel as one transaction.  The cells
+        // are left empty for the next block.
+        __syncthreads();
+        for (int c = tid; c < ((nT + 3) & ~3) * 8; c += JOIN_THREADS) {
+            const u64 key = s_cell[c];
+            if (key != TG_EMPTY_KEY) {
+                s_cell[c] = TG_EMPTY_KEY;
+                emit_candidate(cd, s_ids, s_salt, c >> 3, key, (u32)v, c & 7);
             }
         }
     }
@@ -662,7 +677,7 @@ __global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wa
     }
 }
 
-static size_t join_lds_bytes(int DK, int rows) { return JOIN_HDR_BYTES + (size_t)rows * (DK + 4) * sizeof(float); }
+static size_t join_lds_bytes(int DK, int rows) { return JOIN_HDR_BYTES + JOIN_CELL_BYTES + (size_t)rows * (DK + 4) * sizeof(float); }
 
 // LDS beyond 64 KB per workgroup has to be asked for once per kernel
 template <class K>
