@@ -142,15 +142,27 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     if (nN == 0 || nT < 2 || ((nT + 15) >> 4) <= skip_le) continue;
     __syncthreads();                       // the previous block's epilogue has left the LDS header
 
-    // gather of one slab: global -> registers now, registers -> LDS once the tile is free
+    // gather of one slab: global -> registers now, registers -> LDS once the tile is free.
+    // A thread fetches the same column part of the same PER rows in every slab, so the row
+    // addresses are formed once per block and the loads are unconditional (rows and columns
+    // past the end read a valid address and are zeroed).
     float4 pre[PER];
+    const int cpart = (tid % F4) * 4;
+    const float* rp[PER];
+    bool rv[PER];
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+        const int row = (tid + JOIN_THREADS * it) / F4;
+        rv[it] = row < nT;
+        rp[it] = g.X + (int64_t)bids[rv[it] ? row : 0] * g.ld + cpart;
+    }
     auto issue = [&](int ks) {
+        const bool cv = ks + cpart < g.ld;
+        const int kso = cv ? ks : -cpart;
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
-            const int e = tid + JOIN_THREADS * it;
-            const int row = e / F4, col = ks + (e % F4) * 4;
-            pre[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < nT && col < g.ld) pre[it] = *reinterpret_cast<const float4*>(g.X + (int64_t)bids[row] * g.ld + col);
+            const float4 val = *reinterpret_cast<const float4*>(rp[it] + kso);
+            pre[it] = (rv[it] & cv) ? val : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
     auto commit = [&]() {
