@@ -110,6 +110,8 @@ STEPWISE = [
     (1500, 132, 32, dict(C=128, ng_row=4, ng_col=4)),
     (900, 7, 48, dict(C=64, ng_row=2, ng_col=8, R=32)),
     (400, 16, 64, dict(C=128, ng_row=4, ng_col=2, m=3)),
+    (1000, 256, 32, dict(C=256)),          # long rows: the workgroup join with 128-column slabs
+    (1400, 128, 32, dict(C=256)),          # the bench shape of rows and slots
 ]
 
 
