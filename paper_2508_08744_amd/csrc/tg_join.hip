@@ -719,7 +719,7 @@ static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c
     else if (ngr == 2 && ngc == 8) launch_join_t<64, 2, 8>(g, sm, c, hs_slot, stat_bins, s);
     else if (ngr == 4 && ngc == 2) launch_join_t<64, 4, 2>(g, sm, c, hs_slot, stat_bins, s);
     else if (ngr == 4 && ngc == 4) launch_join_t<64, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else if (g.ld >= 256) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, s);   // long rows: half as many slabs and barriers
+    else if (g.ld > 64) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, s);   // half as many slabs and barriers
     else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
 
