@@ -122,7 +122,41 @@ size_t tg_scan_tmp_elems(int64_t n) { return (size_t)((n + SCAN_BLOCK - 1) / SCA
 //                     OLD = (old_fwd not in NEW) ++ (old_rev in neither).
 // fwd entries sit one per lane (lanes < k), rn / ro are the kept reverse arrivals, ascending
 // by (priority, source), one per lane (lanes < cn / co).
-__device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int64_t v, u32 rn, int cn, u32 ro, int co)
+// A small id -> tag map in LDS for the cross checks between the forward and the reverse samples
+// (open addressing, 256 words for at most 64 ids; ids inside one list are distinct).
+#define ASM_WORDS 256
+#define ASM_FREE 0xFFFFFFFFu
+__device__ inline int asm_insert(u32* keys, u32 id, bool active)
+{
+    int slot = -1;
+    bool pending = active;
+    u32 h = (id * 0x9E3779B1u) >> 24;
+    while (__ballot(pending)) {
+        if (pending) {
+            const u32 old = atomicCAS(keys + h, ASM_FREE, id);
+            if (old == ASM_FREE) { slot = (int)h; pending = false; }
+            else h = (h + 1) & (ASM_WORDS - 1);
+        }
+    }
+    return slot;
+}
+__device__ inline int asm_find(const u32* keys, u32 id, bool active)
+{
+    int slot = -1;
+    bool pending = active;
+    u32 h = (id * 0x9E3779B1u) >> 24;
+    while (__ballot(pending)) {
+        if (pending) {
+            const u32 t = keys[h];
+            if (t == id) { slot = (int)h; pending = false; }
+            else if (t == ASM_FREE) pending = false;
+            else h = (h + 1) & (ASM_WORDS - 1);
+        }
+    }
+    return slot;
+}
+__device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int64_t v, u32 rn, int cn, u32 ro, int co,
+                                      u32* keys, u32* tags)
 {
     const int lane = tg_lane();
     const int k = g.k, S = sm.S;
@@ -134,16 +168,26 @@ __device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int6
     const bool is_nf = fr && __popcll(mf & lt) < S;     // sampled new forward entry
     const bool is_of = ol && __popcll(mo & lt) < S;     // sampled old forward entry
     const u32 fid = w & TG_ID_MASK;
-    if (lane >= cn) rn = 0xFFFFFFFFu;
-    if (lane >= co) ro = 0xFFFFFFFFu;
-    const u64 m_nf = __ballot(is_nf), m_of = __ballot(is_of);
-    bool rn_dup = false, ro_dup = false, of_drop = false;
-    for (int q = 0; q < k; ++q) {
-        const u32 f = (u32)__builtin_amdgcn_readlane((int)fid, q);
-        if ((m_nf >> q) & 1ull) { rn_dup |= (rn == f); ro_dup |= (ro == f); }
-        else if ((m_of >> q) & 1ull) ro_dup |= (ro == f);
-    }
-    for (int q = 0; q < cn; ++q) of_drop |= (fid == (u32)__builtin_amdgcn_readlane((int)rn, q));
+    const u64 m_nf = __ballot(is_nf);
+    // forward samples into the map: tag 1 = new, 2 = old (4 is added when a reverse-new arrival repeats it)
+    for (int i = lane; i < ASM_WORDS; i += 64) keys[i] = ASM_FREE;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int fslot = asm_insert(keys, fid, is_nf || is_of);
+    if (fslot >= 0) tags[fslot] = is_nf ? 1u : 2u;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int sn = asm_find(keys, rn, lane < cn);
+    const int so = asm_find(keys, ro, lane < co);
+    const u32 tn = sn >= 0 ? tags[sn] : 0u;
+    const bool rn_dup = tn == 1u;                       // already there as a new forward sample
+    const bool ro_dup = so >= 0;                        // already there as a forward sample of either class
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (tn == 2u) tags[sn] = 6u;                        // the old forward sample is NEW through the reverse side
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const bool of_drop = is_of && (tags[fslot >= 0 ? fslot : 0] & 4u);
     const bool keep_rn = lane < cn && !rn_dup;
     const bool keep_of = is_of && !of_drop;
     const bool keep_ro = lane < co && !ro_dup;
@@ -163,6 +207,7 @@ __device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int6
 __global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev)
 {
     __shared__ u64 part[4][2][64];
+    __shared__ u32 asm_keys[4][ASM_WORDS], asm_tags[4][ASM_WORDS];
     const int lane = tg_lane(), wave = threadIdx.x >> 6;
     const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     if (u >= g.n) return;
@@ -203,7 +248,7 @@ __global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm,
         tot_new += cn;
         tot_old += co;
     }
-    assemble_block(g, sm, u, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R));
+    assemble_block(g, sm, u, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R), asm_keys[wave], asm_tags[wave]);
 }
 
 // blocks as stored -> the boundary's fixed n x 128 layout (padding -1) and (|NEW|, |OLD|)
