@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=20000)
+    ap.add_argument("--cpu-sample", type=int, default=50000)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; run with --gpus 1 (the method would shard by node range, "
