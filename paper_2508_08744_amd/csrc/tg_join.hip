@@ -546,9 +546,10 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                 for (int e = 0; e < 4; ++e) {
                     const int a = 16 * i + 4 * q4 + e;
                     const int aa = a < nN ? a : 0;
-                    aux_a[e] = s_aux[aa];
-                    id_a[e] = (u32)s_ids[aa];
                     pen_a[e] = a < nN ? 0.f : INF;
+                    // L2: the penalty rides on the norm (norm + 0 is the norm, bit for bit)
+                    aux_a[e] = METRIC == 0 ? s_aux[aa] + pen_a[e] : s_aux[aa];
+                    id_a[e] = (u32)s_ids[aa];
                     if (MODE == 0) okd_max = max(okd_max, s_okd[aa]);
                 }
                 // the lane that will speak for row 16 i + 4 q4 + (r16 & 3) keeps that row's threshold
@@ -569,13 +570,14 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                     // column side: lane (r16, .) is column b = 16 j + r16
                     const int b = 16 * j + r16;
                     const int bb = b < nT ? b : 0;
-                    const float aux_b = s_aux[bb];
-                    const u32 id_b = (u32)s_ids[bb];
                     const float pen_b = b < nT ? 0.f : INF;
+                    const float aux_b = METRIC == 0 ? s_aux[bb] + pen_b : s_aux[bb];
+                    const u32 id_b = (u32)s_ids[bb];
                     u32 o[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b) + (pen_a[e] + pen_b);
+                        float dist = gram_to_dist<METRIC>(acc[e], aux_a[e], aux_b);
+                        if (METRIC != 0) dist += pen_a[e] + pen_b;
                         // only the diagonal tile has pairs on or below the diagonal to drop
                         if (i == j) dist += (r16 > 4 * q4 + e) ? 0.f : INF;
                         if (MODE == 1) {
@@ -603,15 +605,13 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         const u32 mi = e_mine == 0 ? ri[0] : e_mine == 1 ? ri[1] : e_mine == 2 ? ri[2] : ri[3];
                         if (r16 < 4 && ((mo < okd_mine) | ((mo == okd_mine) & (mi < kid_mine))))
                             atomicMin(cells + a_mine * GMAX + j, ((u64)mo << 32) | (u64)((mi << 2) | 3u));
-                        // Column node b: closest row node of the tile, over the lane's four rows and
-                        // then over the four row quarters.
+                        // Column node b: closest row node of the tile over the lane's four rows.
                         u64 cb = ((u64)o[0] << 32) | id_a[0];
 #pragma unroll
                         for (int e = 1; e < 4; ++e) cb = tg_min64(cb, ((u64)o[e] << 32) | id_a[e]);
-                        cb = tg_min64(cb, tg_shfl_xor64(cb, 16));
-                        cb = tg_min64(cb, tg_shfl_xor64(cb, 32));
+                        // (the four row quarters meet in the cell: it takes the minimum)
                         const u32 co = (u32)(cb >> 32), ci = (u32)cb;
-                        if (q4 == 0 && ((co < okd_b) | ((co == okd_b) & (ci < s_kid[bb]))))
+                        if ((co < okd_b) | ((co == okd_b) & (ci < s_kid[bb])))
                             atomicMin(cells + b * GMAX + i, ((u64)co << 32) | (u64)((ci << 2) | 3u));
                     }
                 }
