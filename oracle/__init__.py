@@ -2,7 +2,8 @@
 
 Thin ctypes loader for ``tg_oracle.c``: exact brute-force k-NN (O-BF) and the
 two-phase NN-Descent of Algorithm 1 (O-NND), both single-threaded and in
-double precision.  Nothing in the product path may import this package; it is
+double precision; and for ``tg_prune_oracle.c``: the rank-based pruning of a
+k-NN graph by detourable routes.  Nothing in the product path may import this package; it is
 for ``tests/``, the smoke check and the benchmark's CPU-baseline leg.
 """
 from __future__ import annotations
@@ -15,6 +16,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tg_oracle.c")
+_SRC2 = os.path.join(_HERE, "tg_prune_oracle.c")
 _LIB = os.path.join(_HERE, "libtg_oracle.so")
 
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
@@ -22,9 +24,9 @@ METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, no HIP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2)):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -56,6 +58,8 @@ def lib():
         L.onnd_init.argtypes = [vp]
         L.onnd_phase1_sample.argtypes = [vp]
         L.onnd_block.argtypes = [vp, i64, vp, vp]
+        L.oprune_rank.restype = i32
+        L.oprune_rank.argtypes = [vp, i64, i32, i32, vp, vp]
         L.oracle_merge_list.restype = i64
         L.oracle_merge_list.argtypes = [i32, i64, vp, vp, vp, vp, vp, i64]
         L.onnd_phase1_round.restype = i64
@@ -128,6 +132,18 @@ def merge_list(self_id, ids, dist, fresh, cand_ids, cand_dist):
     ins = lib().oracle_merge_list(len(ids), self_id, ids.ctypes.data, dist.ctypes.data, fresh.ctypes.data,
                                   cid.ctypes.data, cd.ctypes.data, len(cid))
     return ids, dist, fresh, ins
+
+
+def prune_rank(ids, d_out: int):
+    """Rank-based pruning (sections 3.2 and 5.2): returns (out_ids n x d_out, counts n x k)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n, k = ids.shape
+    out = np.empty((n, d_out), dtype=np.int32)
+    cnt = np.empty((n, k), dtype=np.int32)
+    rc = lib().oprune_rank(ids.ctypes.data, n, k, d_out, out.ctypes.data, cnt.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return out, cnt
 
 
 class NNDescent:
