@@ -168,6 +168,20 @@ int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric
                  const int64_t* query_rows, int64_t nq, int32_t* out_ids, float* out_dist,
                  void* stream);
 
+/*
+ * Rank-based pruning of a k-NN graph by detourable routes (section 3.2, the CAGRA row of the
+ * table of pruning strategies; section 5.2).  knn_ids: device n x k int32, every row ordered
+ * closest first (the output of tg_knn_build); the position of a neighbour in its row stands for
+ * its distance.  For node A and its neighbour F at position p, D is a detour of the edge (A, F)
+ * when D's positions in A's row and in F's row are both below p.  out_ids: device n x d_out, the
+ * d_out neighbours of each row with the smallest (detour count, position), in that order;
+ * out_counts: device n x k int32 detour counts by position, or NULL.  1 <= d_out <= k <= 64.
+ * Ids outside [0, n) are padding: they have no detours, are no detours, and are kept or dropped
+ * by their position alone.  The inputs are not modified; nothing is allocated.
+ */
+int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32_t d_out, int32_t* out_ids,
+                  int32_t* out_counts, void* stream);
+
 /* Message of the calling thread's last error (static storage, never NULL). */
 const char* tg_last_error(void);
 

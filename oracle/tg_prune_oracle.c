@@ -25,7 +25,7 @@
 #include <stdlib.h>
 
 /* counts: n x k (may be NULL), out_ids: n x d_out.  Ids outside [0, n) have no row
- * and therefore bring no detours.  Returns 0, or -1 on bad arguments. */
+ * and are no nodes: they bring no detours and are no detours.  Returns 0, or -1 on bad arguments. */
 int oprune_rank(const int32_t *ids, int64_t n, int k, int d_out, int32_t *out_ids, int32_t *counts)
 {
     if (!ids || !out_ids || n < 1 || k < 1 || d_out < 1 || d_out > k) return -1;
@@ -38,9 +38,11 @@ int oprune_rank(const int32_t *ids, int64_t n, int k, int d_out, int32_t *out_id
             int32_t f = NA[p];
             if (f < 0 || f >= n) continue;
             const int32_t *NF = ids + (int64_t)f * k;
-            for (int r = 0; r < p; ++r)        /* D = NF[r]: dis(D, F) = r + 1 < p + 1 */
+            for (int r = 0; r < p; ++r) {      /* D = NF[r]: dis(D, F) = r + 1 < p + 1 */
+                if (NF[r] < 0 || NF[r] >= n) continue;       /* padding is no node */
                 for (int i = 0; i < p; ++i)    /* dis(A, D) = i + 1 < p + 1 */
                     if (NA[i] == NF[r]) { cnt[p]++; break; }
+            }
         }
         /* keep the d_out smallest (count, position), in that order */
         for (int p = 0; p < k; ++p) taken[p] = 0;

@@ -547,3 +547,14 @@ extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int
     if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "exact k-NN failed: %s", hipGetErrorString(e));
     return rc;
 }
+
+extern "C" int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32_t d_out, int32_t* out_ids, int32_t* out_counts,
+                             void* stream)
+{
+    if (!knn_ids || !out_ids) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (n < 1 || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "n = %lld outside 1..2^30-1", (long long)n);
+    if (k < 1 || k > 64) return fail(TG_ERR_INVALID_ARG, "k = %d outside 1..64", k);
+    if (d_out < 1 || d_out > k) return fail(TG_ERR_INVALID_ARG, "d_out = %d outside 1..k", d_out);
+    tg_launch_prune_rank(knn_ids, n, k, d_out, out_ids, out_counts, reinterpret_cast<hipStream_t>(stream));
+    return launch_status("rank-based pruning");
+}

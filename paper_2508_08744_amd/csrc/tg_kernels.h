@@ -70,3 +70,5 @@ void tg_launch_exact_knn(const float* X, int ld, const float* nrm, const float* 
                          int metric, const int64_t* rows, int64_t nq, int32_t* out_ids, float* out_dist,
                          unsigned long long* partial /* nq x slices x k */, int nslices, hipStream_t s);
 size_t tg_scan_tmp_elems(int64_t n);
+void tg_launch_prune_rank(const int32_t* ids, int64_t n, int k, int d_out, int32_t* out_ids, int32_t* counts /* or null */,
+                          hipStream_t s);
