@@ -144,8 +144,31 @@ def main():
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
         "updates_per_round": last["updates"],
     }
+    # the next step after the hot path: rank-based pruning of the graph just built (outside `value`).
+    # Algorithmic bytes per node: its row, the entries in front of every neighbour's own position, the output.
+    d_out = k // 2
+    pr_ms = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pruned = knn.prune_rank(ids, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        pr_ms.append(e0.elapsed_time(e1))
+    pr_ms = sorted(pr_ms)[len(pr_ms) // 2]
+    pr_bytes = n * (4.0 * k + 2.0 * k * (k - 1) + 4.0 * d_out)
+    out["prune_rank"] = {"k": k, "d_out": d_out, "ms": pr_ms, "points_per_s": n / (pr_ms * 1e-3),
+                         "roofline": {"bound": "hbm", "achieved": pr_bytes / (pr_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                      "unit": "GB/s", "frac": pr_bytes / (pr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, prm, min(args.cpu_sample, n))
+        n_do = min(n, 50000)
+        t0 = time.perf_counter()
+        want, _ = oracle.prune_rank(ids.cpu().numpy(), d_out, n_do=n_do)
+        dt = time.perf_counter() - t0
+        out["prune_rank"]["cpu_baseline"] = {"value": n_do / dt, "unit": "points/s", "cores": 1, "kind": "oracle",
+                                             "sample": "rows of the first %d nodes of the graph just built, %.1f s" % (n_do, dt),
+                                             "identical": bool((pruned[:n_do].cpu().numpy() == want).all())}
     print(json.dumps(out))
 
 

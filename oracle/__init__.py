@@ -59,7 +59,7 @@ def lib():
         L.onnd_phase1_sample.argtypes = [vp]
         L.onnd_block.argtypes = [vp, i64, vp, vp]
         L.oprune_rank.restype = i32
-        L.oprune_rank.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.oracle_merge_list.restype = i64
         L.oracle_merge_list.argtypes = [i32, i64, vp, vp, vp, vp, vp, i64]
         L.onnd_phase1_round.restype = i64
@@ -134,13 +134,15 @@ def merge_list(self_id, ids, dist, fresh, cand_ids, cand_dist):
     return ids, dist, fresh, ins
 
 
-def prune_rank(ids, d_out: int):
-    """Rank-based pruning (sections 3.2 and 5.2): returns (out_ids n x d_out, counts n x k)."""
+def prune_rank(ids, d_out: int, n_do=None):
+    """Rank-based pruning (sections 3.2 and 5.2) of the rows of the first n_do nodes (default: all):
+    returns (out_ids n_do x d_out, counts n_do x k)."""
     ids = np.ascontiguousarray(ids, dtype=np.int32)
     n, k = ids.shape
-    out = np.empty((n, d_out), dtype=np.int32)
-    cnt = np.empty((n, k), dtype=np.int32)
-    rc = lib().oprune_rank(ids.ctypes.data, n, k, d_out, out.ctypes.data, cnt.ctypes.data)
+    n_do = n if n_do is None else int(n_do)
+    out = np.empty((n_do, d_out), dtype=np.int32)
+    cnt = np.empty((n_do, k), dtype=np.int32)
+    rc = lib().oprune_rank(ids.ctypes.data, n, n_do, k, d_out, out.ctypes.data, cnt.ctypes.data)
     if rc != 0:
         raise ValueError("bad arguments")
     return out, cnt

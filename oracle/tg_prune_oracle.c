@@ -24,14 +24,15 @@
 #include <stdint.h>
 #include <stdlib.h>
 
-/* counts: n x k (may be NULL), out_ids: n x d_out.  Ids outside [0, n) have no row
+/* Prunes the rows of nodes 0 .. n_do-1 (n_do <= n; the rest of the graph is only read).
+ * counts: n_do x k (may be NULL), out_ids: n_do x d_out.  Ids outside [0, n) have no row
  * and are no nodes: they bring no detours and are no detours.  Returns 0, or -1 on bad arguments. */
-int oprune_rank(const int32_t *ids, int64_t n, int k, int d_out, int32_t *out_ids, int32_t *counts)
+int oprune_rank(const int32_t *ids, int64_t n, int64_t n_do, int k, int d_out, int32_t *out_ids, int32_t *counts)
 {
-    if (!ids || !out_ids || n < 1 || k < 1 || d_out < 1 || d_out > k) return -1;
+    if (!ids || !out_ids || n < 1 || n_do < 0 || n_do > n || k < 1 || d_out < 1 || d_out > k) return -1;
     int32_t *cnt = (int32_t *)malloc((size_t)k * sizeof(int32_t));
     uint8_t *taken = (uint8_t *)malloc((size_t)k);
-    for (int64_t a = 0; a < n; ++a) {
+    for (int64_t a = 0; a < n_do; ++a) {
         const int32_t *NA = ids + a * k;
         for (int p = 0; p < k; ++p) {          /* p is the position minus one */
             cnt[p] = 0;

@@ -8,10 +8,8 @@
 // One wave per node A.  A's row goes into an id -> position map in LDS; the rows of the
 // neighbours F are read 64 / k' at a time (k' = k rounded up to a power of two), one entry D
 // per lane and only the entries in front of F's own position in A's row, and each lane looks
-// its D up in the map.  A ballot per row gives the count.  The paper balances warps that scan
-// rows of different useful length by pairing candidates; here a lane that has nothing to scan
-// simply idles inside a wave that is busy with the other rows, and the kernel is bound by the
-// gather of the rows (4 k^2 / 2 bytes per node), not by the scan.
+// its D up in the map.  A ballot per row gives the count.  Rows of different useful length are
+// balanced as in the paper, by pairing positions q and k - 1 - q inside one group of lanes.
 #include "tg_device.h"
 #include "tg_kernels.h"
 
@@ -52,24 +50,51 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const int32_t* __restri
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        for (int j0 = 0; j0 < k; j0 += per) {
-            const int j = j0 + my_row;               // position (from 0) of this lane's F in A's row
-            const int32_t F = __shfl(a, j < k ? j : 0);
-            const bool scan = my_row < per && j < k && r < j && F >= 0 && F < n;
-            const int32_t D = scan ? ids[(int64_t)F * k + r] : -1;
-            bool pending = scan && D >= 0 && D < n, hit = false;
-            u32 h = ((u32)D * 0x9E3779B1u) >> 24;
-            while (__ballot(pending)) {
-                if (pending) {
-                    const u32 t = mk[h];
-                    if (t == (u32)D) { hit = mp[h] < (u32)j; pending = false; }
-                    else if (t == PRUNE_FREE) pending = false;
-                    else h = (h + 1) & (PRUNE_MAP_WORDS - 1);
+        // Rows are taken in pairs (positions q and k - 1 - q): the first needs its q entries in
+        // front, the second k - 1 - q, together k - 1 lanes of a group of k' (the balanced
+        // pairing of section 5.2).  64 / k' pairs per pass; the loads of eight passes are in
+        // flight before the first look-up.
+        const int npairs = (k + 1) >> 1;
+        for (int p0 = 0; p0 < npairs; p0 += 8 * per) {
+            int32_t D[8];
+            int jj[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int q = p0 + t * per + my_row;
+                const int jlo = q, jhi = k - 1 - q;
+                const bool lo = r < jlo;
+                const int j = lo ? jlo : jhi;
+                const int rr = lo ? r : r - jlo;
+                const bool on = my_row < per && q < npairs && (lo || (jhi != jlo && rr < jhi));
+                const int32_t F = __shfl(a, on ? j : 0);
+                const bool scan = on && F >= 0 && F < n;
+                D[t] = scan ? ids[(int64_t)F * k + rr] : -1;
+                jj[t] = j;
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int q = p0 + t * per + my_row;
+                if (p0 + t * per >= npairs) break;           // uniform
+                bool pending = D[t] >= 0 && D[t] < n, hit = false;
+                u32 h = ((u32)D[t] * 0x9E3779B1u) >> 24;
+                while (__ballot(pending)) {
+                    if (pending) {
+                        const u32 w = mk[h];
+                        if (w == (u32)D[t]) { hit = mp[h] < (u32)jj[t]; pending = false; }
+                        else if (w == PRUNE_FREE) pending = false;
+                        else h = (h + 1) & (PRUNE_MAP_WORDS - 1);
+                    }
+                }
+                const u64 hits = __ballot(hit);
+                if (r == 0 && my_row < per && q < npairs) {
+                    const int jlo = q, jhi = k - 1 - q;
+                    const int base = my_row * kp;
+                    const u64 mlo = jlo ? (((1ull << jlo) - 1ull) << base) : 0ull;
+                    const u64 mhi = (jhi >= 64 ? ~0ull : ((1ull << jhi) - 1ull)) << (base + jlo);
+                    mc[jlo] = (u32)__popcll(hits & mlo);
+                    if (jhi != jlo) mc[jhi] = (u32)__popcll(hits & mhi);
                 }
             }
-            const u64 hits = __ballot(hit);
-            const u64 rowmask = (kp == 64 ? ~0ull : ((1ull << kp) - 1ull)) << (my_row * kp);
-            if (r == 0 && my_row < per && j < k) mc[j] = (u32)__popcll(hits & rowmask);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();

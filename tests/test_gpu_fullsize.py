@@ -44,3 +44,12 @@ def test_c2_full_size():
     rec = oracle.recall(ids[torch.from_numpy(rows2).cuda()].cpu().numpy(), ti.cpu().numpy())
     assert rec >= 0.95, rec
     assert st["rounds_phase1"] == prm.it1 and st["rounds_phase2"] == prm.it2
+    # --- the next step on the full-size graph, in the launch configuration the benchmark times: rank-based
+    # pruning of all rows; the rows of the first 20 000 nodes (which reach into the whole graph) against the oracle
+    pruned, cnt = knn.prune_rank(ids, k // 2, want_counts=True)
+    want, want_cnt = oracle.prune_rank(ids.cpu().numpy(), k // 2, n_do=20000)
+    assert (pruned[:20000].cpu().numpy() == want).all() and (cnt[:20000].cpu().numpy() == want_cnt).all()
+    # properties that hold for every row: kept ids come from the row, none twice; counts bounded by the position
+    both = torch.cat([pruned, ids], dim=1).sort(dim=1).values
+    assert int((both[:, 1:] == both[:, :-1]).sum()) == n * (k // 2)
+    assert bool((cnt <= torch.arange(k, device="cuda")[None, :]).all()) and bool((cnt[:, 0] == 0).all())
