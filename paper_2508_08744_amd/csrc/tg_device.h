@@ -135,4 +135,47 @@ __device__ inline u64 tg_wave_merge_low(u64 a, u64 b)
     return x;
 }
 
+// The same network on 32-bit keys: compare-exchange is one v_min / v_max with a DPP operand.
+template <int CTRL>
+__device__ inline u32 tg_dpp32(u32 x)
+{
+    return (u32)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xF, 0xF, true);
+}
+template <int XOR>
+__device__ inline u32 tg_partner32(u32 x)
+{
+    if (XOR == 1) return tg_dpp32<0xB1>(x);
+    if (XOR == 2) return tg_dpp32<0x4E>(x);
+    if (XOR == 3) return tg_dpp32<0x1B>(x);
+    if (XOR == 4) return tg_dpp32<0x1B>(tg_dpp32<0x141>(x));
+    if (XOR == 7) return tg_dpp32<0x141>(x);
+    if (XOR == 8) return tg_dpp32<0x128>(x);
+    if (XOR == 15) return tg_dpp32<0x140>(x);
+    return (u32)__shfl_xor((int)x, XOR);
+}
+__device__ inline u32 tg_cmpx32(u32 key, u32 other, bool keep_min) { return keep_min ? min(key, other) : max(key, other); }
+template <int SIZE>
+__device__ inline u32 tg_sort_level32(u32 key, int lane)
+{
+    key = tg_cmpx32(key, tg_partner32<SIZE - 1>(key), (lane & (SIZE >> 1)) == 0);
+    if (SIZE >= 64) key = tg_cmpx32(key, tg_partner32<16>(key), (lane & 16) == 0);
+    if (SIZE >= 32) key = tg_cmpx32(key, tg_partner32<8>(key), (lane & 8) == 0);
+    if (SIZE >= 16) key = tg_cmpx32(key, tg_partner32<4>(key), (lane & 4) == 0);
+    if (SIZE >= 8) key = tg_cmpx32(key, tg_partner32<2>(key), (lane & 2) == 0);
+    if (SIZE >= 4) key = tg_cmpx32(key, tg_partner32<1>(key), (lane & 1) == 0);
+    return key;
+}
+// Ascending bitonic sort of one 32-bit key per lane across the wave.
+__device__ inline u32 tg_wave_sort32(u32 key)
+{
+    const int lane = tg_lane();
+    key = tg_sort_level32<2>(key, lane);
+    key = tg_sort_level32<4>(key, lane);
+    key = tg_sort_level32<8>(key, lane);
+    key = tg_sort_level32<16>(key, lane);
+    key = tg_sort_level32<32>(key, lane);
+    key = tg_sort_level32<64>(key, lane);
+    return key;
+}
+
 __device__ inline u64 tg_lanemask_lt() { return (1ull << tg_lane()) - 1ull; }

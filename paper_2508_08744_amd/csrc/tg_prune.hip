@@ -13,7 +13,7 @@
 #include "tg_device.h"
 #include "tg_kernels.h"
 
-#define PRUNE_MAP_WORDS 256     // more than twice the 64 ids of a row
+#define PRUNE_MAP_WORDS 256     // 128 buckets of two ids for the at most 64 ids of a row
 #define PRUNE_FREE 0xFFFFFFFFu
 #define PRUNE_GRID 8192
 
@@ -36,10 +36,11 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const int32_t* __restri
         mc[lane] = 0u;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        // A's row into the map; an id listed twice keeps its first position
+        // A's row into the map (buckets of two words, read with one 8-byte load later); an id
+        // listed twice keeps its first position
         {
             bool pending = a_ok;
-            u32 h = ((u32)a * 0x9E3779B1u) >> 24;
+            u32 h = (((u32)a * 0x9E3779B1u) >> 25) << 1;
             while (__ballot(pending)) {
                 if (pending) {
                     const u32 old = atomicCAS(mk + h, PRUNE_FREE, (u32)a);
@@ -75,8 +76,18 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const int32_t* __restri
             for (int t = 0; t < 8; ++t) {
                 const int q = p0 + t * per + my_row;
                 if (p0 + t * per >= npairs) break;           // uniform
-                bool pending = D[t] >= 0 && D[t] < n, hit = false;
-                u32 h = ((u32)D[t] * 0x9E3779B1u) >> 24;
+                // look D up: its home bucket first (almost always decisive), then word by word
+                const bool live = D[t] >= 0 && D[t] < n;
+                u32 h = (((u32)D[t] * 0x9E3779B1u) >> 25) << 1;
+                const uint2 b2 = *reinterpret_cast<const uint2*>(mk + h);
+                bool hit = false;
+                bool pending = false;
+                if (live) {
+                    if (b2.x == (u32)D[t]) hit = mp[h] < (u32)jj[t];
+                    else if (b2.y == (u32)D[t]) hit = mp[h + 1] < (u32)jj[t];
+                    else pending = b2.x != PRUNE_FREE && b2.y != PRUNE_FREE;
+                }
+                h = (h + 2) & (PRUNE_MAP_WORDS - 1);
                 while (__ballot(pending)) {
                     if (pending) {
                         const u32 w = mk[h];
@@ -101,9 +112,9 @@ __global__ __launch_bounds__(256) void prune_rank_kernel(const int32_t* __restri
         const u32 c = lane < k ? mc[lane] : 0u;
         if (counts && lane < k) counts[A * k + lane] = (int32_t)c;
         // smallest (count, position) first
-        u64 key = lane < k ? (((u64)c << 8) | (u64)lane) : TG_EMPTY_KEY;
-        key = tg_wave_sort(key);
-        const int32_t keep = __shfl(a, (int)(key & 63ull));
+        u32 key = lane < k ? ((c << 8) | (u32)lane) : 0xFFFFFFFFu;
+        key = tg_wave_sort32(key);
+        const int32_t keep = __shfl(a, (int)(key & 63u));
         if (lane < d_out) out_ids[A * d_out + lane] = keep;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
