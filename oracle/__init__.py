@@ -3,7 +3,8 @@
 Thin ctypes loader for ``tg_oracle.c``: exact brute-force k-NN (O-BF) and the
 two-phase NN-Descent of Algorithm 1 (O-NND), both single-threaded and in
 double precision; and for ``tg_prune_oracle.c``: the rank-based pruning of a
-k-NN graph by detourable routes.  Nothing in the product path may import this package; it is
+k-NN graph by detourable routes; and for ``tg_filter_oracle.c``: the distance-based
+(NSG / Vamana) pruning over 1-hop or 2-hop candidates.  Nothing in the product path may import this package; it is
 for ``tests/``, the smoke check and the benchmark's CPU-baseline leg.
 """
 from __future__ import annotations
@@ -17,6 +18,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tg_oracle.c")
 _SRC2 = os.path.join(_HERE, "tg_prune_oracle.c")
+_SRC3 = os.path.join(_HERE, "tg_filter_oracle.c")
 _LIB = os.path.join(_HERE, "libtg_oracle.so")
 
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
@@ -24,9 +26,9 @@ METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, no HIP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2)):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in (_SRC, _SRC2, _SRC3)):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, "-lm"])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, _SRC3, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -60,6 +62,8 @@ def lib():
         L.onnd_block.argtypes = [vp, i64, vp, vp]
         L.oprune_rank.restype = i32
         L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.ofilter_dist.restype = i32
+        L.ofilter_dist.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.oracle_merge_list.restype = i64
         L.oracle_merge_list.argtypes = [i32, i64, vp, vp, vp, vp, vp, i64]
         L.onnd_phase1_round.restype = i64
@@ -146,6 +150,25 @@ def prune_rank(ids, d_out: int, n_do=None):
     if rc != 0:
         raise ValueError("bad arguments")
     return out, cnt
+
+
+def filter_dist(X, ids, hops: int, cand_size: int, alpha: float, d_out: int, n_do=None):
+    """Distance-based pruning (section 3.2: NSG for alpha = 1, Vamana for alpha > 1) over the 1-hop or
+    2-hop candidates of the graph ``ids`` (section 5.1), squared L2.  Returns (out_ids n_do x d_out
+    padded with -1, degrees, margins): see tg_filter_oracle.c for the margin."""
+    X = _f32(X)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n, k = ids.shape
+    assert X.shape[0] == n
+    n_do = n if n_do is None else int(n_do)
+    out = np.empty((n_do, d_out), dtype=np.int32)
+    deg = np.empty(n_do, dtype=np.int32)
+    margin = np.empty(n_do, dtype=np.float64)
+    rc = lib().ofilter_dist(X.ctypes.data, n, X.shape[1], ids.ctypes.data, k, n_do, hops, cand_size,
+                            float(alpha), d_out, out.ctypes.data, deg.ctypes.data, margin.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return out, deg, margin
 
 
 class NNDescent:

@@ -1,0 +1,140 @@
+/*
+ * CPU oracle for the distance-based pruning of a k-NN graph in the Collect-Filter-Store
+ * procedure (paper section 5.1, the algorithm "CFS procedure of pruning"; the NSG and
+ * Vamana rows of the table of pruning strategies and their description in section 3.2).
+ *
+ * THIS IS TEST INFRASTRUCTURE: a plain, slow, single-threaded definition written out,
+ * used only by the test-suite.  It shares no code with the HIP library.
+ *
+ * For every node p:
+ *   Collect  hops = 1: the candidates are p's neighbours in the k-NN graph;
+ *            hops = 2: those and the neighbours of each of them.
+ *            p itself, ids without a row and repeats are no candidates.  The candidates
+ *            are ordered by (dis(p, c), id) and the first cand_size of them go on.
+ *   Filter   the serial rule of section 3.2: the candidates are taken closest first; p' is
+ *            inserted into R iff for every p* already in R
+ *                dis(p, p') < alpha * dis(p*, p')            (alpha = 1: NSG; alpha > 1: Vamana)
+ *            until R holds d_out nodes.  dis is the Euclidean distance; this library stores
+ *            its square, so the test is  sq(p, p') < alpha^2 * sq(p*, p').
+ *   Store    R in insertion order, padded with -1.
+ *
+ * Precision: squared distances are summed in double from the float inputs and then rounded
+ * to float; the comparison above is taken in float (alpha^2 and the product rounded to
+ * float), the precision the GPU decides in.  On integer-valued data below 2^24 every one of
+ * these values is exact.
+ *
+ * Pinning (tests/test_oracle_filter.py): closed forms on a line and on a circle, the strict
+ * inequality on an isosceles triangle, alpha -> infinity reduces to "the d_out nearest
+ * candidates", duplicates, 2-hop collection against a set union in Python, invariants.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+static const float *g_X;
+static int g_d;
+
+static double sq64(int64_t a, int64_t b)
+{
+    const float *x = g_X + a * g_d, *y = g_X + b * g_d;
+    double s = 0.0;
+    for (int j = 0; j < g_d; ++j) { double t = (double)x[j] - (double)y[j]; s += t * t; }
+    return s;
+}
+
+static double norm64(int64_t a)
+{
+    const float *x = g_X + a * g_d;
+    double s = 0.0;
+    for (int j = 0; j < g_d; ++j) s += (double)x[j] * (double)x[j];
+    return s;
+}
+
+typedef struct { float dist; int32_t id; } cand_t;
+
+static int cand_less(const void *pa, const void *pb)
+{
+    const cand_t *a = (const cand_t *)pa, *b = (const cand_t *)pb;
+    if (a->dist != b->dist) return a->dist < b->dist ? -1 : 1;
+    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+/* Prunes the rows of nodes 0 .. n_do-1 (n_do <= n; the rest of the graph is only read).
+ * out_ids: n_do x d_out; out_deg: n_do (may be NULL); out_margin: n_do (may be NULL): the
+ * smallest distance of any decision taken for the row from flipping, |lhs - rhs| divided by
+ * the sum of the squared norms of the nodes involved (0 when equal keys were ordered by id).
+ * A row whose margin is far above float rounding has one possible result in any arithmetic.
+ * Returns 0, or -1 on bad arguments. */
+int ofilter_dist(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t n_do,
+                 int hops, int cand_size, float alpha, int d_out,
+                 int32_t *out_ids, int32_t *out_deg, double *out_margin)
+{
+    if (!X || !ids || !out_ids || n < 1 || d < 1 || k < 1 || n_do < 0 || n_do > n) return -1;
+    if ((hops != 1 && hops != 2) || cand_size < 1 || d_out < 1 || !(alpha >= 1.0f)) return -1;
+    g_X = X; g_d = d;
+    const float a2 = alpha * alpha;
+    int64_t cap = (int64_t)k + (hops == 2 ? (int64_t)k * k : 0);
+    cand_t *cand = (cand_t *)malloc((size_t)cap * sizeof(cand_t));
+    int64_t *stamp = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+    int32_t *R = (int32_t *)malloc((size_t)d_out * sizeof(int32_t));
+    for (int64_t i = 0; i < n; ++i) stamp[i] = -1;
+    for (int64_t p = 0; p < n_do; ++p) {
+        /* Collect */
+        int64_t m = 0;
+        const int32_t *Np = ids + p * k;
+        for (int i = 0; i < k; ++i) {
+            int32_t u = Np[i];
+            if (u < 0 || u >= n || u == p || stamp[u] == p) continue;
+            stamp[u] = p; cand[m++].id = u;
+        }
+        if (hops == 2) {
+            int64_t m1 = m;
+            for (int64_t i = 0; i < m1; ++i) {
+                const int32_t *Nu = ids + (int64_t)cand[i].id * k;
+                for (int j = 0; j < k; ++j) {
+                    int32_t w = Nu[j];
+                    if (w < 0 || w >= n || w == p || stamp[w] == p) continue;
+                    stamp[w] = p; cand[m++].id = w;
+                }
+            }
+        }
+        for (int64_t i = 0; i < m; ++i) cand[i].dist = (float)sq64(p, cand[i].id);
+        qsort(cand, (size_t)m, sizeof(cand_t), cand_less);
+        double margin = INFINITY;
+        double np_ = norm64(p);
+        int64_t mc = m < cand_size ? m : cand_size;
+        if (out_margin) {
+            int64_t last = mc < m ? mc : mc - 1;       /* includes the cut between kept and dropped candidates */
+            for (int64_t i = 0; i < last; ++i) {
+                double sc = np_ + norm64(cand[i].id) + norm64(cand[i + 1].id);
+                double g = fabs((double)cand[i + 1].dist - (double)cand[i].dist) / (sc > 0 ? sc : 1.0);
+                if (g < margin) margin = g;
+            }
+        }
+        /* Filter */
+        int deg = 0;
+        for (int64_t i = 0; i < mc && deg < d_out; ++i) {
+            int32_t c = cand[i].id;
+            float lhs = cand[i].dist;
+            int keep = 1;
+            double m_keep = INFINITY, m_drop = 0.0;
+            for (int r = 0; r < deg; ++r) {
+                float drc = (float)sq64(R[r], c);
+                float rhs = a2 * drc;
+                double sc = np_ + norm64(c) + norm64(R[r]);
+                double g = fabs((double)lhs - (double)rhs) / (sc > 0 ? sc : 1.0);
+                if (lhs < rhs) { if (g < m_keep) m_keep = g; }
+                else { keep = 0; if (g > m_drop) m_drop = g; }
+            }
+            double mcand = keep ? m_keep : m_drop;      /* dropped: safe if one occluder is safe */
+            if (mcand < margin) margin = mcand;
+            if (keep) R[deg++] = c;
+        }
+        /* Store */
+        for (int t = 0; t < d_out; ++t) out_ids[p * d_out + t] = t < deg ? R[t] : -1;
+        if (out_deg) out_deg[p] = deg;
+        if (out_margin) out_margin[p] = margin;
+    }
+    free(cand); free(stamp); free(R);
+    return 0;
+}
