@@ -558,3 +558,20 @@ extern "C" int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32
     tg_launch_prune_rank(knn_ids, n, k, d_out, out_ids, out_counts, reinterpret_cast<hipStream_t>(stream));
     return launch_status("rank-based pruning");
 }
+
+extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops,
+                             int32_t cand_size, float alpha, int32_t d_out, int32_t* out_ids, int32_t* out_deg, void* stream)
+{
+    if (!X || !knn_ids || !out_ids) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (n < 1 || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "n = %lld outside 1..2^30-1", (long long)n);
+    if (d < 1 || d > 4096) return fail(TG_ERR_INVALID_ARG, "d = %d outside 1..4096", d);
+    if (k < 1 || k > 64) return fail(TG_ERR_INVALID_ARG, "k = %d outside 1..64", k);
+    if (hops != 1 && hops != 2) return fail(TG_ERR_INVALID_ARG, "hops = %d must be 1 or 2", hops);
+    if (cand_size < 1 || cand_size > 64) return fail(TG_ERR_INVALID_ARG, "cand_size = %d outside 1..64", cand_size);
+    if (d_out < 1 || d_out > 64) return fail(TG_ERR_INVALID_ARG, "d_out = %d outside 1..64", d_out);
+    if (!(alpha >= 1.0f) || !(alpha <= 1e6f)) return fail(TG_ERR_INVALID_ARG, "alpha must be in [1, 1e6]");
+    if (hops == 2 && k > 32) return fail(TG_ERR_UNSUPPORTED, "hops = 2 needs k <= 32 (k = %d)", k);
+    tg_launch_filter_dist(X, n, d, knn_ids, k, hops, cand_size, alpha, d_out, out_ids, out_deg,
+                          reinterpret_cast<hipStream_t>(stream));
+    return launch_status("distance-based pruning");
+}

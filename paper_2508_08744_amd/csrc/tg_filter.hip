@@ -1,0 +1,357 @@
+// Distance-based pruning of a k-NN graph in the Collect-Filter-Store procedure (section 5.1;
+// the NSG and Vamana rows of the table of pruning strategies, section 3.2).  For node p the
+// candidates are its neighbours (hops = 1) or those and their neighbours (hops = 2), ordered
+// by (dis(p, c), id) and cut to cand_size; they are taken closest first and p' is inserted
+// iff dis(p, p') < alpha dis(p*, p') for every p* inserted before, until d_out are in.
+// Distances are squared here, so the test uses alpha^2.
+//
+// One wave per node.  Section 5.2 evaluates a batch of candidates against the neighbour that
+// was inserted last, one batch per insertion.  Here the candidate rows (at most 64) are loaded
+// once into registers in matrix-core operand layout and ALL their pairwise products are
+// formed at once (a Gram matrix on v_mfma_f32_16x16x4_f32, upper triangle of 16 x 16 tiles);
+// what remains of the serial rule is bit arithmetic: every candidate gets the 64-bit set of
+// candidates it would occlude, and the wave walks the candidates in order with a scalar loop
+// that ORs the sets of the inserted ones.  The rows are the only large HBM traffic
+// (4 d bytes per candidate); the products are cheap next to it.
+//
+// Lane (r, q) = (lane % 16, lane / 16) holds, for row group t and column step s, columns
+// 16 s + 4 q .. + 3 of the chunk of 128 columns of candidate 16 t + r: one load instruction
+// reads 64 contiguous bytes of each of 16 rows.  dis(p, c) is summed in difference form from
+// the same registers.
+#include "tg_device.h"
+#include "tg_kernels.h"
+
+#define FILTER_KS 8                 // float4 steps per chunk of 128 columns
+#define FILTER_SET_WORDS 2048       // id set of the 2-hop collection: at most 1 + 32 + 32 * 32 ids
+#define FILTER_QUEUE_WORDS 1088
+#define FILTER_GRID 16384
+#define FILTER_FREE 0xFFFFFFFFu
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct FilterArgs {
+    const float* X;
+    int64_t n;
+    int32_t d;
+    const int32_t* ids;
+    int32_t k, kp;          // kp: k rounded up to a power of two
+    int32_t hops, cand_size;
+    float a2;
+    int32_t d_out;
+    int32_t* out_ids;
+    int32_t* out_deg;
+};
+
+__device__ inline float4 filter_load4(const float* row, int col, int d, bool full, bool vec)
+{
+    if (full) return *reinterpret_cast<const float4*>(row + col);
+    if (vec) return col < d ? *reinterpret_cast<const float4*>(row + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 v;
+    v.x = col + 0 < d ? row[col + 0] : 0.f;
+    v.y = col + 1 < d ? row[col + 1] : 0.f;
+    v.z = col + 2 < d ? row[col + 2] : 0.f;
+    v.w = col + 3 < d ? row[col + 3] : 0.f;
+    return v;
+}
+
+// Loads the chunk [c0, c0 + 128) of the rows cid[0 .. cnt) (16 NG >= cnt; rows past cnt repeat
+// row 0) and adds this lane's share of the squared differences to node p's row into dp[t].
+template <int NG, bool FULL, bool VEC>
+__device__ inline void filter_load_chunk(const FilterArgs& A, const float* xp, const int* cid, int cnt, int c0,
+                                         float4 (&X)[NG][FILTER_KS], float (&dp)[NG])
+{
+    const int lane = tg_lane(), r16 = lane & 15, q4 = lane >> 4;
+    const float* rp[NG];
+#pragma unroll
+    for (int t = 0; t < NG; ++t) {
+        const int row = 16 * t + r16;
+        rp[t] = A.X + (int64_t)cid[row < cnt ? row : 0] * A.d;
+    }
+#pragma unroll
+    for (int t = 0; t < NG; ++t)
+#pragma unroll
+        for (int s = 0; s < FILTER_KS; ++s) X[t][s] = filter_load4(rp[t], c0 + 16 * s + 4 * q4, A.d, FULL, VEC);
+#pragma unroll
+    for (int s = 0; s < FILTER_KS; ++s) {
+        const float4 a = filter_load4(xp, c0 + 16 * s + 4 * q4, A.d, FULL, VEC);
+#pragma unroll
+        for (int t = 0; t < NG; ++t) {
+            const float t0 = a.x - X[t][s].x, t1 = a.y - X[t][s].y, t2 = a.z - X[t][s].z, t3 = a.w - X[t][s].w;
+            dp[t] += t0 * t0 + t1 * t1 + t2 * t2 + t3 * t3;
+        }
+    }
+}
+
+// the four quarter sums of a row meet: afterwards every lane (r, q) holds the whole sum of row 16 t + r
+template <int NG>
+__device__ inline void filter_reduce_quarters(float (&dp)[NG])
+{
+#pragma unroll
+    for (int t = 0; t < NG; ++t) {
+        dp[t] += __shfl_xor(dp[t], 16);
+        dp[t] += __shfl_xor(dp[t], 32);
+    }
+}
+
+template <int NG>
+__device__ inline float filter_own(const float (&dp)[NG], int q4)
+{
+    // lane 16 q + r speaks for row 16 q + r (bit selects: an indexed read would go through scratch)
+    if (NG == 1) return dp[0];
+    if (NG == 2) return (q4 & 1) ? dp[1] : dp[0];
+    const float lo = (q4 & 1) ? dp[1] : dp[0];
+    const float hi = (q4 & 1) ? dp[NG - 1] : dp[2];
+    return (q4 & 2) ? hi : lo;
+}
+
+__device__ inline bool filter_set_insert(u32* tab, u32 id, bool active)
+{
+    bool present = false, pending = active;
+    u32 h = (id * 0x9E3779B1u) >> 21;                 // FILTER_SET_WORDS = 2^11
+    while (__ballot(pending)) {
+        if (pending) {
+            const u32 old = atomicCAS(tab + h, FILTER_FREE, id);
+            if (old == FILTER_FREE) pending = false;
+            else if (old == id) { present = true; pending = false; }
+            else h = (h + 1) & (FILTER_SET_WORDS - 1);
+        }
+    }
+    return present;
+}
+
+__device__ inline void filter_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int NG, bool FULL, bool VEC, bool TWO_HOPS>
+__global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
+{
+    extern __shared__ u32 dyn[];         // hops = 2: per wave an id set and a queue of collected ids
+    __shared__ int s_cid[4][64];
+    __shared__ __align__(16) float s_dpc[4][64];
+    __shared__ __align__(16) float s_nrm[4][64];
+    __shared__ u32 s_occ[4][128];
+    __shared__ int s_ord[4][64];
+    const int wave = threadIdx.x >> 6, lane = tg_lane();
+    const int r16 = lane & 15, q4 = lane >> 4;
+    int* cid = s_cid[wave];
+    float* dpc = s_dpc[wave];
+    float* nrm = s_nrm[wave];
+    u32* occ = s_occ[wave];
+    int* ord = s_ord[wave];
+    const int k = A.k;
+    const int nchunks = (A.d + 127) >> 7;
+
+    for (int64_t p = (int64_t)blockIdx.x * 4 + wave; p < A.n; p += (int64_t)gridDim.x * 4) {
+        const float* xp = A.X + p * A.d;
+        int m = 0;
+        // ---- Collect ----
+        const int32_t u = lane < k ? A.ids[p * k + lane] : -1;
+        bool u_ok = u >= 0 && u < A.n && u != p;
+        if (!TWO_HOPS) {
+            for (int j = 0; j < k; ++j) {                       // a repeated id counts once
+                const int32_t uj = __builtin_amdgcn_readlane(u, j);
+                u_ok &= !(j < lane && uj == u);
+            }
+            const u64 mask = __ballot(u_ok);
+            if (u_ok) cid[__popcll(mask & tg_lanemask_lt())] = u;
+            m = __popcll(mask);
+            filter_wave_sync();
+        } else {
+            u32* set = dyn + wave * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS);
+            int* queue = reinterpret_cast<int*>(set + FILTER_SET_WORDS);
+            for (int i = lane; i < FILTER_SET_WORDS; i += 64) set[i] = FILTER_FREE;
+            filter_wave_sync();
+            int Q = 0;
+            {
+                const bool fresh = u_ok && !filter_set_insert(set, (u32)u, u_ok);
+                const u64 mask = __ballot(fresh);
+                if (fresh) queue[__popcll(mask & tg_lanemask_lt())] = u;
+                Q = __popcll(mask);
+            }
+            const int per = 64 / A.kp;
+            const int my_row = lane / A.kp, r = lane - my_row * A.kp;
+            for (int j0 = 0; j0 < k; j0 += per) {
+                const int j = j0 + my_row;
+                const bool on = my_row < per && j < k && r < k;
+                const int32_t uj = __shfl(u, on ? j : 0);
+                const bool uj_ok = __shfl((int)u_ok, on ? j : 0) != 0;
+                const int32_t w = (on && uj_ok) ? A.ids[(int64_t)uj * k + r] : -1;
+                const bool w_ok = w >= 0 && w < A.n && w != p;
+                const bool fresh = w_ok && !filter_set_insert(set, (u32)w, w_ok);
+                const u64 mask = __ballot(fresh);
+                if (fresh) queue[Q + __popcll(mask & tg_lanemask_lt())] = w;
+                Q += __popcll(mask);
+            }
+            filter_wave_sync();
+            // distance to p of everything collected, 64 at a time; the 64 closest stay, in order
+            u64 best = TG_EMPTY_KEY;
+            for (int b0 = 0; b0 < Q; b0 += 64) {
+                const int cnt = min(64, Q - b0);
+                float dp[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < nchunks; ++c) {
+                    float4 X[4][FILTER_KS];
+                    filter_load_chunk<4, FULL, VEC>(A, xp, queue + b0, cnt, c << 7, X, dp);
+                }
+                filter_reduce_quarters<4>(dp);
+                const float own = filter_own<4>(dp, q4);
+                u64 key = lane < cnt ? tg_key(own, (u32)queue[b0 + lane], 0u) : TG_EMPTY_KEY;
+                key = tg_wave_sort(key);
+                best = b0 == 0 ? key : tg_wave_merge_low(best, key);
+            }
+            m = min(min(Q, 64), A.cand_size);
+            if (lane < m) cid[lane] = (int)tg_key_id(best);
+            filter_wave_sync();
+        }
+        if (m > 16 * NG) m = 16 * NG;          // never true: the launcher sizes NG for the largest candidate set
+        if (m == 0) {
+            if (lane < A.d_out) A.out_ids[p * A.d_out + lane] = -1;
+            if (A.out_deg && lane == 0) A.out_deg[p] = 0;
+            filter_wave_sync();
+            continue;
+        }
+
+        // ---- Filter: rows into registers, dis(p, c) and the Gram matrix of the candidates ----
+        floatx4 acc[NG][NG];
+#pragma unroll
+        for (int i = 0; i < NG; ++i)
+#pragma unroll
+            for (int j = 0; j < NG; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float dp[NG];
+#pragma unroll
+        for (int t = 0; t < NG; ++t) dp[t] = 0.f;
+        const int groups = (m + 15) >> 4;
+        for (int c = 0; c < nchunks; ++c) {
+            float4 X[NG][FILTER_KS];
+            filter_load_chunk<NG, FULL, VEC>(A, xp, cid, m, c << 7, X, dp);
+#pragma unroll
+            for (int i = 0; i < NG; ++i) {
+                if (i >= groups) break;                           // uniform
+#pragma unroll
+                for (int j = i; j < NG; ++j) {
+                    if (j >= groups) break;
+#pragma unroll
+                    for (int s = 0; s < FILTER_KS; ++s) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].x, X[j][s].x, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].y, X[j][s].y, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].z, X[j][s].z, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].w, X[j][s].w, acc[i][j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        filter_reduce_quarters<NG>(dp);
+        // accumulator register e of lane (r, q) in tile (i, j) is the product of rows 16 i + 4 q + e
+        // and 16 j + r; the diagonal of tile (t, t) gives the squared norms
+#pragma unroll
+        for (int t = 0; t < NG; ++t) {
+            const floatx4 a = acc[t][t];
+            const float lo = (r16 & 1) ? a.y : a.x, hi = (r16 & 1) ? a.w : a.z;
+            if (q4 == (r16 >> 2)) nrm[16 * t + r16] = (r16 & 2) ? hi : lo;
+            if (q4 == 0) dpc[16 * t + r16] = dp[t];
+        }
+        occ[lane] = 0u;
+        occ[lane + 64] = 0u;
+        filter_wave_sync();
+        // occ[R] = the candidates C that R would occlude: not dis(p, C) < alpha^2 dis(R, C)
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            if (i >= groups) break;
+            const float4 nR = *reinterpret_cast<const float4*>(nrm + 16 * i + 4 * q4);
+            const float4 dR = *reinterpret_cast<const float4*>(dpc + 16 * i + 4 * q4);
+#pragma unroll
+            for (int j = i; j < NG; ++j) {
+                if (j >= groups) break;
+                const float nC = nrm[16 * j + r16];
+                const float dC = dp[j];
+                const floatx4 g = acc[i][j];
+                const float rhs0 = A.a2 * ((nR.x + nC) - 2.0f * g.x);
+                const float rhs1 = A.a2 * ((nR.y + nC) - 2.0f * g.y);
+                const float rhs2 = A.a2 * ((nR.z + nC) - 2.0f * g.z);
+                const float rhs3 = A.a2 * ((nR.w + nC) - 2.0f * g.w);
+                const u64 b0 = __ballot(!(dC < rhs0));
+                const u64 b1 = __ballot(!(dC < rhs1));
+                const u64 b2 = __ballot(!(dC < rhs2));
+                const u64 b3 = __ballot(!(dC < rhs3));
+                if (r16 == 0) {
+                    const int R = 16 * i + 4 * q4, sh = 16 * q4, word = j >> 1, up = 16 * (j & 1);
+                    atomicOr(occ + 2 * (R + 0) + word, (u32)((b0 >> sh) & 0xFFFFull) << up);
+                    atomicOr(occ + 2 * (R + 1) + word, (u32)((b1 >> sh) & 0xFFFFull) << up);
+                    atomicOr(occ + 2 * (R + 2) + word, (u32)((b2 >> sh) & 0xFFFFull) << up);
+                    atomicOr(occ + 2 * (R + 3) + word, (u32)((b3 >> sh) & 0xFFFFull) << up);
+                }
+                if (j > i) {
+                    // the mirrored pairs: C occludes R
+                    const u32 nib = (u32)!(dR.x < rhs0) | ((u32)!(dR.y < rhs1) << 1) | ((u32)!(dR.z < rhs2) << 2) |
+                                    ((u32)!(dR.w < rhs3) << 3);
+                    atomicOr(occ + 2 * (16 * j + r16) + (i >> 1), nib << (16 * (i & 1) + 4 * q4));
+                }
+            }
+        }
+        // rank of every candidate under (dis(p, c), id)
+        const float own = filter_own<NG>(dp, q4);
+        const int my_id = lane < m ? cid[lane] : 0;
+        const u64 key = lane < m ? tg_key(own, (u32)my_id, 0u) : TG_EMPTY_KEY;
+        int rank = 0;
+        for (int j = 0; j < m; ++j) {
+            const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
+            const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
+            rank += ((((u64)hi << 32) | lo) < key) ? 1 : 0;
+        }
+        if (lane < m) ord[rank] = lane;
+        filter_wave_sync();
+        const int my_ord = lane < m ? ord[lane] : 0;
+        const u32 occ_lo = occ[2 * lane], occ_hi = occ[2 * lane + 1];
+        // ---- the serial rule on bit sets ----
+        const int mc = min(m, A.cand_size);
+        u64 occluded = 0ull;
+        int deg = 0;
+        int32_t mine = -1;
+        for (int t = 0; t < mc && deg < A.d_out; ++t) {
+            const int c = __builtin_amdgcn_readlane(my_ord, t);
+            if ((occluded >> c) & 1ull) continue;
+            const u32 lo = (u32)__builtin_amdgcn_readlane((int)occ_lo, c);
+            const u32 hi = (u32)__builtin_amdgcn_readlane((int)occ_hi, c);
+            occluded |= ((u64)hi << 32) | lo;
+            const int32_t idc = __builtin_amdgcn_readlane(my_id, c);
+            if (lane == deg) mine = idc;
+            ++deg;
+        }
+        // ---- Store ----
+        if (lane < A.d_out) A.out_ids[p * A.d_out + lane] = lane < deg ? mine : -1;
+        if (A.out_deg && lane == 0) A.out_deg[p] = deg;
+        filter_wave_sync();
+    }
+}
+
+template <int NG, bool TWO_HOPS>
+static void launch_filter(const FilterArgs& A, bool full, bool vec, dim3 grid, size_t shm, hipStream_t s)
+{
+    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, true, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, false, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    else hipLaunchKernelGGL((filter_dist_kernel<NG, false, false, TWO_HOPS>), grid, dim3(256), shm, s, A);
+}
+
+void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, float alpha,
+                           int d_out, int32_t* out_ids, int32_t* out_deg, hipStream_t s)
+{
+    FilterArgs A;
+    A.X = X; A.n = n; A.d = d; A.ids = ids; A.k = k;
+    A.kp = 1;
+    while (A.kp < k) A.kp <<= 1;
+    A.hops = hops; A.cand_size = cand_size;
+    A.a2 = alpha * alpha;
+    A.d_out = d_out; A.out_ids = out_ids; A.out_deg = out_deg;
+    const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const bool full = vec && (d % 128 == 0);
+    const int most = hops == 1 ? k : (cand_size < 64 ? cand_size : 64);      // candidates that reach the filter
+    int64_t wgs = (n + 3) / 4;
+    if (wgs > FILTER_GRID) wgs = FILTER_GRID;
+    const size_t shm = hops == 2 ? (size_t)4 * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS) * sizeof(u32) : 0;
+    // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
+    if (hops == 2) launch_filter<4, true>(A, full, vec, dim3((unsigned)wgs), shm, s);
+    else if (most <= 32) launch_filter<2, false>(A, full, vec, dim3((unsigned)wgs), shm, s);
+    else launch_filter<4, false>(A, full, vec, dim3((unsigned)wgs), shm, s);
+}

@@ -72,3 +72,5 @@ void tg_launch_exact_knn(const float* X, int ld, const float* nrm, const float* 
 size_t tg_scan_tmp_elems(int64_t n);
 void tg_launch_prune_rank(const int32_t* ids, int64_t n, int k, int d_out, int32_t* out_ids, int32_t* counts /* or null */,
                           hipStream_t s);
+void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, float alpha,
+                           int d_out, int32_t* out_ids, int32_t* out_deg /* or null */, hipStream_t s);

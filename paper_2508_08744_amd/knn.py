@@ -44,7 +44,7 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_last_error"]
+           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_last_error"]
 
 _lib = None
 
@@ -77,6 +77,7 @@ def lib():
         L.tg_knn_join_distances.argtypes = [vp, vp, vp, i64, vp]
         L.tg_exact_knn.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         L.tg_prune_rank.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        L.tg_prune_dist.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.tg_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -244,6 +245,21 @@ def prune_rank(ids, d_out, want_counts=False):
     _check(lib().tg_prune_rank(ids.data_ptr(), n, k, d_out, out.data_ptr(), cnt.data_ptr() if want_counts else None,
                                _stream_ptr()))
     return (out, cnt) if want_counts else out
+
+
+def prune_dist(X, ids, d_out, alpha=1.0, hops=1, cand_size=64, want_degrees=False):
+    """tg_prune_dist: NSG (alpha = 1) / Vamana (alpha > 1) pruning over the 1-hop or 2-hop candidates."""
+    X = _dev_f32(X)
+    if not (ids.is_cuda and ids.dtype == torch.int32 and ids.dim() == 2 and ids.is_contiguous()):
+        raise ValueError("ids must be a contiguous int32 CUDA tensor of shape (n, k)")
+    n, k = ids.shape
+    if X.shape[0] != n:
+        raise ValueError("X and ids disagree on n")
+    out = torch.empty((n, d_out), dtype=torch.int32, device=ids.device)
+    deg = torch.empty(n, dtype=torch.int32, device=ids.device) if want_degrees else None
+    _check(lib().tg_prune_dist(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, float(alpha), d_out,
+                               out.data_ptr(), deg.data_ptr() if want_degrees else None, _stream_ptr()))
+    return (out, deg) if want_degrees else out
 
 
 def exact_knn(X, k, metric="l2", rows=None):
