@@ -10,18 +10,17 @@
 // once into registers in matrix-core operand layout and ALL their pairwise products are
 // formed at once (a Gram matrix on v_mfma_f32_16x16x4_f32, upper triangle of 16 x 16 tiles);
 // what remains of the serial rule is bit arithmetic: every candidate gets the 64-bit set of
-// candidates it would occlude, and the wave walks the candidates in order with a scalar loop
-// that ORs the sets of the inserted ones.  The rows are the only large HBM traffic
+// the candidates in front of it that would occlude it, and the set of inserted candidates is the
+// fixed point of "inserted iff no inserted candidate occludes me", found in a few passes.  The rows are the only large HBM traffic
 // (4 d bytes per candidate); the products are cheap next to it.
 //
 // Lane (r, q) = (lane % 16, lane / 16) holds, for row group t and column step s, columns
-// 16 s + 4 q .. + 3 of the chunk of 128 columns of candidate 16 t + r: one load instruction
+// 16 s + 4 q .. + 3 of the current chunk of columns of candidate 16 t + r: one load instruction
 // reads 64 contiguous bytes of each of 16 rows.  dis(p, c) is summed in difference form from
 // the same registers.
 #include "tg_device.h"
 #include "tg_kernels.h"
 
-#define FILTER_KS 8                 // float4 steps per chunk of 128 columns
 #define FILTER_SET_WORDS 2048       // id set of the 2-hop collection: at most 1 + 32 + 32 * 32 ids
 #define FILTER_QUEUE_WORDS 1088
 #define FILTER_GRID 16384
@@ -54,11 +53,11 @@ __device__ inline float4 filter_load4(const float* row, int col, int d, bool ful
     return v;
 }
 
-// Loads the chunk [c0, c0 + 128) of the rows cid[0 .. cnt) (16 NG >= cnt; rows past cnt repeat
+// Loads the chunk [c0, c0 + 16 KS) of the rows cid[0 .. cnt) (16 NG >= cnt; rows past cnt repeat
 // row 0) and adds this lane's share of the squared differences to node p's row into dp[t].
-template <int NG, bool FULL, bool VEC>
+template <int NG, int KS, bool FULL, bool VEC>
 __device__ inline void filter_load_chunk(const FilterArgs& A, const float* xp, const int* cid, int cnt, int c0,
-                                         float4 (&X)[NG][FILTER_KS], float (&dp)[NG])
+                                         float4 (&X)[NG][KS], float (&dp)[NG])
 {
     const int lane = tg_lane(), r16 = lane & 15, q4 = lane >> 4;
     const float* rp[NG];
@@ -70,9 +69,9 @@ __device__ inline void filter_load_chunk(const FilterArgs& A, const float* xp, c
 #pragma unroll
     for (int t = 0; t < NG; ++t)
 #pragma unroll
-        for (int s = 0; s < FILTER_KS; ++s) X[t][s] = filter_load4(rp[t], c0 + 16 * s + 4 * q4, A.d, FULL, VEC);
+        for (int s = 0; s < KS; ++s) X[t][s] = filter_load4(rp[t], c0 + 16 * s + 4 * q4, A.d, FULL, VEC);
 #pragma unroll
-    for (int s = 0; s < FILTER_KS; ++s) {
+    for (int s = 0; s < KS; ++s) {
         const float4 a = filter_load4(xp, c0 + 16 * s + 4 * q4, A.d, FULL, VEC);
 #pragma unroll
         for (int t = 0; t < NG; ++t) {
@@ -125,7 +124,7 @@ __device__ inline void filter_wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NG, bool FULL, bool VEC, bool TWO_HOPS>
+template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS>
 __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 {
     extern __shared__ u32 dyn[];         // hops = 2: per wave an id set and a queue of collected ids
@@ -133,16 +132,14 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
     __shared__ __align__(16) float s_dpc[4][64];
     __shared__ __align__(16) float s_nrm[4][64];
     __shared__ u32 s_occ[4][128];
-    __shared__ int s_ord[4][64];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     int* cid = s_cid[wave];
     float* dpc = s_dpc[wave];
     float* nrm = s_nrm[wave];
     u32* occ = s_occ[wave];
-    int* ord = s_ord[wave];
     const int k = A.k;
-    const int nchunks = (A.d + 127) >> 7;
+    const int nchunks = (A.d + 16 * KS - 1) / (16 * KS);
 
     for (int64_t p = (int64_t)blockIdx.x * 4 + wave; p < A.n; p += (int64_t)gridDim.x * 4) {
         const float* xp = A.X + p * A.d;
@@ -151,13 +148,11 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         const int32_t u = lane < k ? A.ids[p * k + lane] : -1;
         bool u_ok = u >= 0 && u < A.n && u != p;
         if (!TWO_HOPS) {
-            for (int j = 0; j < k; ++j) {                       // a repeated id counts once
-                const int32_t uj = __builtin_amdgcn_readlane(u, j);
-                u_ok &= !(j < lane && uj == u);
-            }
-            const u64 mask = __ballot(u_ok);
-            if (u_ok) cid[__popcll(mask & tg_lanemask_lt())] = u;
-            m = __popcll(mask);
+            // candidate l is entry l of the row; an entry that is no candidate (padding, p itself;
+            // repeats are found below, where the keys are compared) keeps its place as a dead one
+            // and reads p's own row
+            m = k;
+            cid[lane] = u_ok ? u : (int)p;
             filter_wave_sync();
         } else {
             u32* set = dyn + wave * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS);
@@ -192,8 +187,8 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 const int cnt = min(64, Q - b0);
                 float dp[4] = {0.f, 0.f, 0.f, 0.f};
                 for (int c = 0; c < nchunks; ++c) {
-                    float4 X[4][FILTER_KS];
-                    filter_load_chunk<4, FULL, VEC>(A, xp, queue + b0, cnt, c << 7, X, dp);
+                    float4 X[4][KS];
+                    filter_load_chunk<4, KS, FULL, VEC>(A, xp, queue + b0, cnt, c * 16 * KS, X, dp);
                 }
                 filter_reduce_quarters<4>(dp);
                 const float own = filter_own<4>(dp, q4);
@@ -224,8 +219,8 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         for (int t = 0; t < NG; ++t) dp[t] = 0.f;
         const int groups = (m + 15) >> 4;
         for (int c = 0; c < nchunks; ++c) {
-            float4 X[NG][FILTER_KS];
-            filter_load_chunk<NG, FULL, VEC>(A, xp, cid, m, c << 7, X, dp);
+            float4 X[NG][KS];
+            filter_load_chunk<NG, KS, FULL, VEC>(A, xp, cid, m, c * 16 * KS, X, dp);
 #pragma unroll
             for (int i = 0; i < NG; ++i) {
                 if (i >= groups) break;                           // uniform
@@ -233,7 +228,7 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 for (int j = i; j < NG; ++j) {
                     if (j >= groups) break;
 #pragma unroll
-                    for (int s = 0; s < FILTER_KS; ++s) {
+                    for (int s = 0; s < KS; ++s) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].x, X[j][s].x, acc[i][j], 0, 0, 0);
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].y, X[j][s].y, acc[i][j], 0, 0, 0);
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s].z, X[j][s].z, acc[i][j], 0, 0, 0);
@@ -255,7 +250,9 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         occ[lane] = 0u;
         occ[lane + 64] = 0u;
         filter_wave_sync();
-        // occ[R] = the candidates C that R would occlude: not dis(p, C) < alpha^2 dis(R, C)
+        // occ[C] = the candidates R that would occlude C: not dis(p, C) < alpha^2 dis(R, C).  The lane
+        // holds its column's four rows as a nibble; the mirrored pairs (rows and columns exchanged)
+        // of a tile off the diagonal come out of ballots.
 #pragma unroll
         for (int i = 0; i < NG; ++i) {
             if (i >= groups) break;
@@ -271,67 +268,86 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 const float rhs1 = A.a2 * ((nR.y + nC) - 2.0f * g.y);
                 const float rhs2 = A.a2 * ((nR.z + nC) - 2.0f * g.z);
                 const float rhs3 = A.a2 * ((nR.w + nC) - 2.0f * g.w);
-                const u64 b0 = __ballot(!(dC < rhs0));
-                const u64 b1 = __ballot(!(dC < rhs1));
-                const u64 b2 = __ballot(!(dC < rhs2));
-                const u64 b3 = __ballot(!(dC < rhs3));
-                if (r16 == 0) {
-                    const int R = 16 * i + 4 * q4, sh = 16 * q4, word = j >> 1, up = 16 * (j & 1);
-                    atomicOr(occ + 2 * (R + 0) + word, (u32)((b0 >> sh) & 0xFFFFull) << up);
-                    atomicOr(occ + 2 * (R + 1) + word, (u32)((b1 >> sh) & 0xFFFFull) << up);
-                    atomicOr(occ + 2 * (R + 2) + word, (u32)((b2 >> sh) & 0xFFFFull) << up);
-                    atomicOr(occ + 2 * (R + 3) + word, (u32)((b3 >> sh) & 0xFFFFull) << up);
-                }
+                const u32 nib = (u32)!(dC < rhs0) | ((u32)!(dC < rhs1) << 1) | ((u32)!(dC < rhs2) << 2) | ((u32)!(dC < rhs3) << 3);
+                atomicOr(occ + 2 * (16 * j + r16) + (i >> 1), nib << (16 * (i & 1) + 4 * q4));
                 if (j > i) {
-                    // the mirrored pairs: C occludes R
-                    const u32 nib = (u32)!(dR.x < rhs0) | ((u32)!(dR.y < rhs1) << 1) | ((u32)!(dR.z < rhs2) << 2) |
-                                    ((u32)!(dR.w < rhs3) << 3);
-                    atomicOr(occ + 2 * (16 * j + r16) + (i >> 1), nib << (16 * (i & 1) + 4 * q4));
+                    const u64 b0 = __ballot(!(dR.x < rhs0));
+                    const u64 b1 = __ballot(!(dR.y < rhs1));
+                    const u64 b2 = __ballot(!(dR.z < rhs2));
+                    const u64 b3 = __ballot(!(dR.w < rhs3));
+                    if (r16 == 0) {
+                        const int R = 16 * i + 4 * q4, sh = 16 * q4, word = j >> 1, up = 16 * (j & 1);
+                        atomicOr(occ + 2 * (R + 0) + word, (u32)((b0 >> sh) & 0xFFFFull) << up);
+                        atomicOr(occ + 2 * (R + 1) + word, (u32)((b1 >> sh) & 0xFFFFull) << up);
+                        atomicOr(occ + 2 * (R + 2) + word, (u32)((b2 >> sh) & 0xFFFFull) << up);
+                        atomicOr(occ + 2 * (R + 3) + word, (u32)((b3 >> sh) & 0xFFFFull) << up);
+                    }
                 }
             }
         }
-        // rank of every candidate under (dis(p, c), id)
+        // before = the candidates in front of this lane's under (dis(p, c), id); an id that the row
+        // lists again has the same key: the earlier entry goes first and the later one is dead
         const float own = filter_own<NG>(dp, q4);
         const int my_id = lane < m ? cid[lane] : 0;
-        const u64 key = lane < m ? tg_key(own, (u32)my_id, 0u) : TG_EMPTY_KEY;
-        int rank = 0;
-        for (int j = 0; j < m; ++j) {
-            const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
-            const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
-            rank += ((((u64)hi << 32) | lo) < key) ? 1 : 0;
+        bool dead = TWO_HOPS ? lane >= m : !u_ok;
+        const u64 key = dead ? TG_EMPTY_KEY : tg_key(own, (u32)my_id, 0u);
+        u32 lt_lo = 0u, lt_hi = 0u, eq_lo = 0u, eq_hi = 0u;
+        {
+            const int m_lo = min(m, 32);
+#pragma unroll 4
+            for (int j = 0; j < m_lo; ++j) {
+                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
+                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
+                const u64 kj = ((u64)hi << 32) | lo;
+                lt_lo |= kj < key ? (1u << j) : 0u;
+                if (!TWO_HOPS) eq_lo |= kj == key ? (1u << j) : 0u;
+            }
+#pragma unroll 4
+            for (int j = 32; j < m; ++j) {
+                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
+                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
+                const u64 kj = ((u64)hi << 32) | lo;
+                lt_hi |= kj < key ? (1u << (j - 32)) : 0u;
+                if (!TWO_HOPS) eq_hi |= kj == key ? (1u << (j - 32)) : 0u;
+            }
         }
-        if (lane < m) ord[rank] = lane;
+        const u64 twins = (((u64)eq_hi << 32) | eq_lo) & tg_lanemask_lt();
+        if (!TWO_HOPS) dead |= twins != 0ull;
+        const u64 live = ~__ballot(dead);
+        const u64 before = ((((u64)lt_hi << 32) | lt_lo) | twins) & live;
         filter_wave_sync();
-        const int my_ord = lane < m ? ord[lane] : 0;
-        const u32 occ_lo = occ[2 * lane], occ_hi = occ[2 * lane + 1];
-        // ---- the serial rule on bit sets ----
-        const int mc = min(m, A.cand_size);
-        u64 occluded = 0ull;
-        int deg = 0;
-        int32_t mine = -1;
-        for (int t = 0; t < mc && deg < A.d_out; ++t) {
-            const int c = __builtin_amdgcn_readlane(my_ord, t);
-            if ((occluded >> c) & 1ull) continue;
-            const u32 lo = (u32)__builtin_amdgcn_readlane((int)occ_lo, c);
-            const u32 hi = (u32)__builtin_amdgcn_readlane((int)occ_hi, c);
-            occluded |= ((u64)hi << 32) | lo;
-            const int32_t idc = __builtin_amdgcn_readlane(my_id, c);
-            if (lane == deg) mine = idc;
-            ++deg;
+        const u64 occ_by = (((u64)occ[2 * lane + 1] << 32) | occ[2 * lane]) & before;
+        // ---- the serial rule as a fixed point ----
+        // c is inserted iff no inserted candidate in front of it occludes it.  Starting from "all
+        // inserted", every pass settles at least the next candidate in order, so the set stops
+        // changing after at most m passes, and what it then holds obeys the rule.
+        const bool in_cut = !dead && __popcll(before) < A.cand_size;       // the cut to cand_size counts candidates only
+        u64 K = __ballot(in_cut);
+        for (int pass = 0; pass < 65; ++pass) {
+            const u64 Kn = __ballot(in_cut && (occ_by & K) == 0ull);
+            if (Kn == K) break;
+            K = Kn;
         }
-        // ---- Store ----
-        if (lane < A.d_out) A.out_ids[p * A.d_out + lane] = lane < deg ? mine : -1;
+        // ---- Store: insertion order is the order of the candidates; the first d_out are in ----
+        const bool kept = (K >> lane) & 1ull;
+        const int pos = __popcll(K & before);
+        const int deg = min(__popcll(K), A.d_out);
+        if (kept && pos < A.d_out) A.out_ids[p * A.d_out + pos] = my_id;
+        if (lane >= deg && lane < A.d_out) A.out_ids[p * A.d_out + lane] = -1;
         if (A.out_deg && lane == 0) A.out_deg[p] = deg;
         filter_wave_sync();
     }
 }
 
 template <int NG, bool TWO_HOPS>
-static void launch_filter(const FilterArgs& A, bool full, bool vec, dim3 grid, size_t shm, hipStream_t s)
+static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, size_t shm, hipStream_t s)
 {
-    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, true, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
-    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, false, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
-    else hipLaunchKernelGGL((filter_dist_kernel<NG, false, false, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    // four row groups take their columns in chunks of 64, two in chunks of 128: the same number of registers
+    constexpr int KS = NG > 2 ? 4 : 8;
+    const bool full = vec && (A.d % (16 * KS) == 0);         // no column guards needed
+    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, true, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    else hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, false, TWO_HOPS>), grid, dim3(256), shm, s, A);
 }
 
 void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, float alpha,
@@ -345,13 +361,12 @@ void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids,
     A.a2 = alpha * alpha;
     A.d_out = d_out; A.out_ids = out_ids; A.out_deg = out_deg;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    const bool full = vec && (d % 128 == 0);
     const int most = hops == 1 ? k : (cand_size < 64 ? cand_size : 64);      // candidates that reach the filter
     int64_t wgs = (n + 3) / 4;
     if (wgs > FILTER_GRID) wgs = FILTER_GRID;
     const size_t shm = hops == 2 ? (size_t)4 * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS) * sizeof(u32) : 0;
     // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
-    if (hops == 2) launch_filter<4, true>(A, full, vec, dim3((unsigned)wgs), shm, s);
-    else if (most <= 32) launch_filter<2, false>(A, full, vec, dim3((unsigned)wgs), shm, s);
-    else launch_filter<4, false>(A, full, vec, dim3((unsigned)wgs), shm, s);
+    if (hops == 2) launch_filter<4, true>(A, vec, dim3((unsigned)wgs), shm, s);
+    else if (most <= 32) launch_filter<2, false>(A, vec, dim3((unsigned)wgs), shm, s);
+    else launch_filter<4, false>(A, vec, dim3((unsigned)wgs), shm, s);
 }
