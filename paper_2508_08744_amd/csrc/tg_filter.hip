@@ -342,8 +342,9 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 template <int NG, bool TWO_HOPS>
 static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, size_t shm, hipStream_t s)
 {
-    // four row groups take their columns in chunks of 64, two in chunks of 128: the same number of registers
-    constexpr int KS = NG > 2 ? 4 : 8;
+    // two row groups take their columns in chunks of 64, four in chunks of 32: few registers, so that
+    // four (three) waves per SIMD cover each other's loads
+    constexpr int KS = NG > 2 ? 2 : 4;
     const bool full = vec && (A.d % (16 * KS) == 0);         // no column guards needed
     if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, true, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
     else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
