@@ -53,3 +53,21 @@ def test_c2_full_size():
     both = torch.cat([pruned, ids], dim=1).sort(dim=1).values
     assert int((both[:, 1:] == both[:, :-1]).sum()) == n * (k // 2)
     assert bool((cnt <= torch.arange(k, device="cuda")[None, :]).all()) and bool((cnt[:, 0] == 0).all())
+    # --- distance-based pruning of the same graph, as the benchmark runs it (Vamana's rule over the neighbours,
+    # NSG's over two hops); byte-valued features: the rows of the first nodes must equal the oracle's bit for bit
+    ids_h = ids.cpu().numpy()
+    for hops, alpha, n_do in ((1, 1.2, 20000), (2, 1.0, 3000)):
+        out, deg = knn.prune_dist(Xg, ids, k, alpha=alpha, hops=hops, want_degrees=True)
+        want, want_deg, _ = oracle.filter_dist(X, ids_h, hops, 64, alpha, k, n_do=n_do)
+        assert (out[:n_do].cpu().numpy() == want).all() and (deg[:n_do].cpu().numpy() == want_deg).all()
+        # every row: degree within bounds, the nearest neighbour first, padding only behind the kept ids
+        assert int(deg.min()) >= 1 and int(deg.max()) <= k
+        if hops == 1:       # (two hops of an approximate graph can reach something nearer than the row's first)
+            assert bool((out[:, 0] == ids[:, 0]).all())
+        pad = out < 0
+        assert bool((pad.sum(dim=1) == k - deg).all()) and bool((pad[:, 1:] >= pad[:, :-1]).all())
+        if hops == 1:
+            # kept ids come from the row, none twice (padding made distinct so that it pairs with nothing)
+            distinct = torch.where(pad, -2 - torch.arange(k, device="cuda", dtype=torch.int32)[None, :], out)
+            merged = torch.cat([distinct, ids], dim=1).sort(dim=1).values
+            assert int((merged[:, 1:] == merged[:, :-1]).sum()) == int(deg.sum())
