@@ -72,6 +72,15 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert lib.tg_knn_create(ctypes.byref(h), fake, 1000, 16, ctypes.byref(p), ctypes.c_void_p(8), need, None) == -1
     assert lib.tg_exact_knn(fake, 100, 4, 200, 0, None, 10, fake, None, None) == -1
     assert lib.tg_knn_init(None) == -1 and lib.tg_knn_destroy(None) == 0
+    # pruning entry points: (n, d, k, hops, cand_size, alpha, d_out) -> status, before anything is launched
+    for a, want in [((100, 8, 16, 1, 64, 1.0, 0), -1), ((100, 8, 16, 1, 64, 1.0, 65), -1), ((100, 8, 16, 3, 64, 1.0, 8), -1),
+                    ((100, 8, 16, 1, 0, 1.0, 8), -1), ((100, 8, 16, 1, 65, 1.0, 8), -1), ((100, 8, 16, 1, 64, 0.99, 8), -1),
+                    ((100, 8, 16, 1, 64, float("nan"), 8), -1), ((0, 8, 16, 1, 64, 1.0, 8), -1), ((100, 0, 16, 1, 64, 1.0, 8), -1),
+                    ((100, 8, 65, 1, 64, 1.0, 8), -1), ((100, 8, 40, 2, 64, 1.0, 8), -2)]:
+        n, d, k, hops, cs, alpha, d_out = a
+        assert lib.tg_prune_dist(fake, n, d, fake, k, hops, cs, alpha, d_out, fake, None, None) == want, a
+    assert lib.tg_prune_dist(None, 100, 8, fake, 16, 1, 64, 1.0, 8, fake, None, None) == -1
+    assert lib.tg_prune_rank(fake, 100, 16, 17, fake, None, None) == -1
 
 
 def test_workspace_fits_the_largest_configuration():
