@@ -4,7 +4,8 @@ Thin ctypes loader for ``tg_oracle.c``: exact brute-force k-NN (O-BF) and the
 two-phase NN-Descent of Algorithm 1 (O-NND), both single-threaded and in
 double precision; and for ``tg_prune_oracle.c``: the rank-based pruning of a
 k-NN graph by detourable routes; and for ``tg_filter_oracle.c``: the distance-based
-(NSG / Vamana) pruning over 1-hop or 2-hop candidates.  Nothing in the product path may import this package; it is
+(NSG / Vamana) pruning over 1-hop or 2-hop candidates; and for ``tg_merge_oracle.c``: the merge of
+a local index into the global one.  Nothing in the product path may import this package; it is
 for ``tests/``, the smoke check and the benchmark's CPU-baseline leg.
 """
 from __future__ import annotations
@@ -19,6 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tg_oracle.c")
 _SRC2 = os.path.join(_HERE, "tg_prune_oracle.c")
 _SRC3 = os.path.join(_HERE, "tg_filter_oracle.c")
+_SRC4 = os.path.join(_HERE, "tg_merge_oracle.c")
 _LIB = os.path.join(_HERE, "libtg_oracle.so")
 
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
@@ -26,9 +28,9 @@ METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, no HIP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in (_SRC, _SRC2, _SRC3)):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in (_SRC, _SRC2, _SRC3, _SRC4)):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, _SRC3, "-lm"])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, _SRC3, _SRC4, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -64,6 +66,8 @@ def lib():
         L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.ofilter_dist.restype = i32
         L.ofilter_dist.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, ctypes.c_float, i32, vp, vp, vp]
+        L.omerge_local.restype = i32
+        L.omerge_local.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, vp]
         L.oracle_merge_list.restype = i64
         L.oracle_merge_list.argtypes = [i32, i64, vp, vp, vp, vp, vp, i64]
         L.onnd_phase1_round.restype = i64
@@ -169,6 +173,21 @@ def filter_dist(X, ids, hops: int, cand_size: int, alpha: float, d_out: int, n_d
     if rc != 0:
         raise ValueError("bad arguments")
     return out, deg, margin
+
+
+def merge_local(g_ids, g_dist, l_ids, l_dist, l2g):
+    """Merges a local index (local numbering, ``l2g`` gives the global ids) into the global lists
+    (section 6.1), in place: every touched row becomes the k closest of the union."""
+    assert g_ids.dtype == np.int32 and g_dist.dtype == np.float32 and g_ids.flags.c_contiguous and g_dist.flags.c_contiguous
+    l_ids = np.ascontiguousarray(l_ids, dtype=np.int32)
+    l_dist = np.ascontiguousarray(l_dist, dtype=np.float32)
+    l2g = np.ascontiguousarray(l2g, dtype=np.int32)
+    n, k = g_ids.shape
+    nl, kl = l_ids.shape
+    rc = lib().omerge_local(g_ids.ctypes.data, g_dist.ctypes.data, n, k, l_ids.ctypes.data, l_dist.ctypes.data, nl, kl,
+                            l2g.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
 
 
 class NNDescent:
