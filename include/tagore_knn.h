@@ -204,6 +204,26 @@ int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, 
                   int32_t hops, int32_t cand_size, float alpha, int32_t d_out,
                   int32_t* out_ids, int32_t* out_deg, void* stream);
 
+/*
+ * Merge of a local index into the global neighbour lists (section 6.1: a node belongs to several
+ * clusters, every cluster gets a local index, and the node's list becomes merge(list so far, its list
+ * in the local index)).  g_ids, g_dist: device n x k, updated in place; an unused entry has id -1 and
+ * distance +infinity (tg_lists_clear writes a whole array of them).  l_ids, l_dist: device
+ * n_local x k_local, the local index in local numbering (the output of tg_knn_build on the
+ * cluster's rows); local_to_global: device n_local int32, the global id of every local node, every
+ * global id at most once.  For local node i with v = local_to_global[i] the row of v becomes the k
+ * entries with the smallest (distance, id) of its old entries and the translated local ones; an id
+ * counts once (an old entry wins over a local one, else the first in the row), v itself and ids
+ * without a node are no entries, a shorter row ends in -1 / +infinity.  Rows of nodes outside the
+ * cluster are not touched; a local node whose global id is outside [0, n) is skipped.
+ * 1 <= k, k_local <= 64.  Nothing is allocated.
+ */
+int tg_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, const int32_t* l_ids,
+                   const float* l_dist, int64_t n_local, int32_t k_local,
+                   const int32_t* local_to_global, void* stream);
+/* Makes every entry of n x k lists unused (id -1, distance +infinity). */
+int tg_lists_clear(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, void* stream);
+
 /* Message of the calling thread's last error (static storage, never NULL). */
 const char* tg_last_error(void);
 

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtagore_knn.so")
-SOURCES = ["tg_api.hip", "tg_lists.hip", "tg_sample.hip", "tg_join.hip", "tg_exact.hip", "tg_prune.hip", "tg_filter.hip"]
+SOURCES = ["tg_api.hip", "tg_lists.hip", "tg_sample.hip", "tg_join.hip", "tg_exact.hip", "tg_prune.hip", "tg_filter.hip", "tg_merge.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -74,3 +74,5 @@ void tg_launch_prune_rank(const int32_t* ids, int64_t n, int k, int d_out, int32
                           hipStream_t s);
 void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, float alpha,
                            int d_out, int32_t* out_ids, int32_t* out_deg /* or null */, hipStream_t s);
+void tg_launch_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int k, const int32_t* l_ids, const float* l_dist,
+                           int64_t n_local, int k_local, const int32_t* l2g, hipStream_t s);

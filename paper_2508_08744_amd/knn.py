@@ -44,7 +44,8 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_last_error"]
+           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_merge_local", "tg_lists_clear",
+           "tg_last_error"]
 
 _lib = None
 
@@ -77,6 +78,8 @@ def lib():
         L.tg_knn_join_distances.argtypes = [vp, vp, vp, i64, vp]
         L.tg_exact_knn.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         L.tg_prune_rank.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        L.tg_merge_local.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, vp, vp]
+        L.tg_lists_clear.argtypes = [vp, vp, i64, i32, vp]
         L.tg_prune_dist.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.tg_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -260,6 +263,28 @@ def prune_dist(X, ids, d_out, alpha=1.0, hops=1, cand_size=64, want_degrees=Fals
     _check(lib().tg_prune_dist(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, float(alpha), d_out,
                                out.data_ptr(), deg.data_ptr() if want_degrees else None, _stream_ptr()))
     return (out, deg) if want_degrees else out
+
+
+def lists_clear(n, k, device="cuda"):
+    """New n x k lists with every entry unused (tg_lists_clear): ids -1, distances +inf."""
+    ids = torch.empty((n, k), dtype=torch.int32, device=device)
+    dist = torch.empty((n, k), dtype=torch.float32, device=device)
+    _check(lib().tg_lists_clear(ids.data_ptr(), dist.data_ptr(), n, k, _stream_ptr()))
+    return ids, dist
+
+
+def merge_local(g_ids, g_dist, l_ids, l_dist, local_to_global):
+    """tg_merge_local: merges a local index (local numbering) into the global lists, in place."""
+    for t_, dt in ((g_ids, torch.int32), (g_dist, torch.float32), (l_ids, torch.int32), (l_dist, torch.float32),
+                   (local_to_global, torch.int32)):
+        if not (t_.is_cuda and t_.dtype == dt and t_.is_contiguous()):
+            raise ValueError("arguments must be contiguous CUDA tensors (ids int32, distances float32)")
+    n, k = g_ids.shape
+    nl, kl = l_ids.shape
+    if g_dist.shape != g_ids.shape or l_dist.shape != l_ids.shape or local_to_global.numel() != nl:
+        raise ValueError("shapes disagree")
+    _check(lib().tg_merge_local(g_ids.data_ptr(), g_dist.data_ptr(), n, k, l_ids.data_ptr(), l_dist.data_ptr(), nl, kl,
+                                local_to_global.data_ptr(), _stream_ptr()))
 
 
 def exact_knn(X, k, metric="l2", rows=None):
