@@ -186,8 +186,61 @@ def main():
                 "points_per_s": n / (ms_pd * 1e-3),
                 "roofline": {"bound": "hbm", "achieved": by / (ms_pd * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": by / (ms_pd * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+    # sharded construction (the clusters of the paper's large-scale framework): every point goes to its 2 closest
+    # of 8 centres (a few Lloyd steps on a sample: input preparation, untimed), every cluster is built on its own
+    # with the same parameters and merged into the global lists.  Merge bytes per local node: its global row read
+    # and written, its local row, the translated ids.
+    shard_last = None
+    if n >= 100000:
+        nc, copies = 8, 2
+        gen = torch.Generator(device="cpu").manual_seed(2)
+        centres = Xg[torch.randperm(n, generator=gen)[:nc].to(dev)].clone()
+        samp = Xg[::16]
+        for _ in range(5):
+            a = torch.cdist(samp, centres).argmin(dim=1)
+            for c in range(nc):
+                if bool((a == c).any()):
+                    centres[c] = samp[a == c].mean(dim=0)
+        near = torch.cdist(Xg, centres).topk(copies, dim=1, largest=False).indices
+        members = [torch.nonzero((near == c).any(dim=1)).flatten().to(torch.int32) for c in range(nc)]
+        Xs = [Xg[mm.long()].contiguous() for mm in members]
+        wss = [torch.empty(knn.workspace_bytes(x.shape[0], d, prm), dtype=torch.uint8, device=dev) for x in Xs]
+        for rep in range(2):
+            g_ids, g_dist = knn.lists_clear(n, k)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * nc + 1)]
+            ev[0].record()
+            for c in range(nc):
+                l_ids, l_dist, _ = knn.knn_build_ex(Xs[c], prm, wss[c], want_stats=False)
+                ev[2 * c + 1].record()
+                if c == nc - 1:
+                    before = (g_ids.clone(), g_dist.clone())
+                    ev[2 * c + 1].record()
+                knn.merge_local(g_ids, g_dist, l_ids, l_dist, members[c])
+                ev[2 * c + 2].record()
+            torch.cuda.synchronize()
+        ms_b = sum(ev[2 * c].elapsed_time(ev[2 * c + 1]) for c in range(nc))
+        ms_m = sum(ev[2 * c + 1].elapsed_time(ev[2 * c + 2]) for c in range(nc))
+        shard_last = (before, l_ids, l_dist, members[nc - 1], g_ids, g_dist)
+        nl = sum(int(mm.numel()) for mm in members)
+        mby = nl * (8.0 * k + 8.0 * k + 8.0 * k + 4.0 * k)
+        out["sharded_build"] = {
+            "clusters": nc, "copies_per_point": copies, "cluster_sizes": [int(mm.numel()) for mm in members],
+            "ms_builds": ms_b, "ms_merges": ms_m, "points_per_s": n / ((ms_b + ms_m) * 1e-3),
+            "recall_at_k": oracle.recall(g_ids[rows_g].cpu().numpy(), truth.cpu().numpy()),
+            "merge_roofline": {"bound": "hbm", "achieved": mby / (ms_m * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": mby / (ms_m * 1e-3) / 1e9 / HBM_PEAK_GBS}}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, prm, min(args.cpu_sample, n))
+        if shard_last is not None:
+            (b_ids, b_dist), l_ids, l_dist, mm, a_ids, a_dist = shard_last
+            w_ids, w_dist = b_ids.cpu().numpy(), b_dist.cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.merge_local(w_ids, w_dist, l_ids.cpu().numpy(), l_dist.cpu().numpy(), mm.cpu().numpy())
+            dt = time.perf_counter() - t0
+            out["sharded_build"]["cpu_baseline"] = {
+                "value": int(mm.numel()) / dt, "unit": "merged lists/s", "cores": 1, "kind": "oracle",
+                "sample": "the merge of the last cluster (%d nodes) into the lists of the other seven, %.1f s" % (int(mm.numel()), dt),
+                "identical": bool((a_ids.cpu().numpy() == w_ids).all() and (a_dist.cpu().numpy() == w_dist).all())}
         ids_h = ids.cpu().numpy()
         for hops, alpha, pd_out in pd_cases:
             n_do = min(n, 20000 if hops == 1 else 3000)
