@@ -488,14 +488,18 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     // all filled slots of v, closed up in LDS (the slots are handed back empty)
     const u64 lt = tg_lanemask_lt();
     int nq = 0;
-    for (int c0 = 0; c0 < cd.C; c0 += 64) {
-        u64* slot = cd.slots + v * (int64_t)cd.C + c0 + lane;
-        const u64 ck = (c0 + lane < cd.C) ? *slot : TG_EMPTY_KEY;
-        const bool filled = ck != TG_EMPTY_KEY;
+    u64* slot0 = cd.slots + v * (int64_t)cd.C + lane;
+    u64 cks[UPDATE_MAX_C / 64];
+#pragma unroll
+    for (int j = 0; j < UPDATE_MAX_C / 64; ++j)          // every load is on its way before the first is looked at
+        cks[j] = (64 * j + lane < cd.C) ? slot0[64 * j] : TG_EMPTY_KEY;
+#pragma unroll
+    for (int j = 0; j < UPDATE_MAX_C / 64; ++j) {
+        const bool filled = cks[j] != TG_EMPTY_KEY;
         const u64 m = __ballot(filled);
         if (filled) {
-            *slot = TG_EMPTY_KEY;
-            queue[wave][nq + __popcll(m & lt)] = ck;
+            slot0[64 * j] = TG_EMPTY_KEY;
+            queue[wave][nq + __popcll(m & lt)] = cks[j];
         }
         nq += __popcll(m);
     }
