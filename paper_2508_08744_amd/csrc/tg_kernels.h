@@ -8,6 +8,16 @@
 #define TG_BLOCK_ROWS 64
 #define TG_STAT_BINS 1024   // spread of the per-round statistics counters
 
+// One launch carries fewer than 2^32 work-items.  Kernels that give every node a wave (or a group
+// of lanes) of its own are therefore launched once per chunk of TG_LAUNCH_NODES nodes and told
+// where their chunk begins; the chunk size is a multiple of every such group size.
+#define TG_LAUNCH_NODES (1ll << 24)
+template <class F>
+static inline void tg_for_node_chunks(int64_t n, F launch)
+{
+    for (int64_t v0 = 0; v0 < n; v0 += TG_LAUNCH_NODES) launch(v0, n - v0 < TG_LAUNCH_NODES ? n - v0 : TG_LAUNCH_NODES);
+}
+
 struct TgGraph {
     int64_t n;
     int32_t d;        // logical dimension

@@ -62,9 +62,9 @@ void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hip
 // squared norms: 16 lanes per row, float4 loads
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X, int64_t n, int ld,
-                                                    float* __restrict__ nrm, float* __restrict__ rnorm)
+                                                    float* __restrict__ nrm, float* __restrict__ rnorm, int64_t v0)
 {
-    int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    int64_t row = v0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     int sub = threadIdx.x & 15;
     float acc = 0.0f;
     if (row < n) {
@@ -85,9 +85,10 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
 }
 void tg_launch_norms(const TgGraph& g, hipStream_t s)
 {
-    int64_t blocks = (g.n + 15) / 16;
-    hipLaunchKernelGGL(norms_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g.X, g.n, g.ld, g.nrm,
-                       g.metric == 2 ? g.rnorm : (float*)nullptr);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(norms_kernel, dim3((unsigned)((cnt + 15) / 16)), dim3(256), 0, s, g.X, g.n, g.ld, g.nrm,
+                           g.metric == 2 ? g.rnorm : (float*)nullptr, v0);
+    });
 }
 
 // ---------------------------------------------------------------------------------------
@@ -97,9 +98,9 @@ void tg_launch_norms(const TgGraph& g, hipStream_t s)
 // 1/|x| (cosine) and a spare.  With them <xq, yq> follows from the integer dot product of
 // the codes, and |x - y| >= |xq - yq| - err_x - err_y bounds the true distance from below.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq, float* __restrict__ Xqm)
+__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq, float* __restrict__ Xqm, int64_t v0)
 {
-    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t row = v0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int sub = threadIdx.x & 15;
     const bool live = row < g.n;
     const float* x = g.X + (live ? row : 0) * (int64_t)g.ld;
@@ -158,8 +159,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __res
 }
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s)
 {
-    int64_t blocks = (g.n + 15) / 16;
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g, Xq, Xqm);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((cnt + 15) / 16)), dim3(256), 0, s, g, Xq, Xqm, v0);
+    });
 }
 
 // ---------------------------------------------------------------------------------------
@@ -391,11 +393,11 @@ __device__ inline void number_sampled_edges(int64_t v, int k, int S, u32 id, boo
 // Algorithm 1 lines 1-2.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
 // hash and keeps the first k that differ from v and from all earlier draws.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int S, u32* deg)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int S, u32* deg, int64_t v0)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    const int64_t v = v0 + (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
     float* xs = smem + (size_t)wave * g.ld;
     u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
@@ -436,9 +438,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
 void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges, hipStream_t s)
 {
     size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
-    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(init_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, hs_init,
-                       number_edges ? number_edges->S : 0, number_edges ? number_edges->deg : (u32*)nullptr);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(init_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), shm, s, g,
+                           hs_init, number_edges ? number_edges->S : 0, number_edges ? number_edges->deg : (u32*)nullptr, v0);
+    });
 }
 
 // ---------------------------------------------------------------------------------------
@@ -471,12 +474,12 @@ __device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, boo
 // ---------------------------------------------------------------------------------------
 #define UPDATE_MAX_C 256
 #define UPDATE_SET_WORDS 512     // more than 64 + UPDATE_MAX_C ids
-__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg, int64_t v0)
 {
     __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
     __shared__ u32 seen_s[LISTS_WAVES][UPDATE_SET_WORDS];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    const int64_t v = v0 + (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
     const int k = g.k;
     u32 w = 0;
@@ -549,9 +552,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool number_edges, hipStream_t s)
 {
     if (c.C > UPDATE_MAX_C) return;    // the boundary refuses such C; the queue in LDS holds no more
-    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(update_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
-                       number_edges ? sm.deg : (u32*)nullptr);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(update_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), 0, s, g, sm.S,
+                           c, updates, number_edges ? sm.deg : (u32*)nullptr, v0);
+    });
 }
 
 // phase switch: every entry unvisited
@@ -761,11 +765,11 @@ void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, u32
 // Output: optionally recompute every kept distance directly from the vectors (the join
 // ranks with the norm-plus-Gram form, which loses digits to cancellation) and re-sort.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, int recompute, int32_t* out_ids, float* out_dist)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, int recompute, int32_t* out_ids, float* out_dist, int64_t v0)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
-    const int64_t v = (int64_t)blockIdx.x * LISTS_WAVES + wave;
+    const int64_t v = v0 + (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
     const int k = g.k;
     float* xs = smem + (size_t)wave * g.ld;
@@ -793,8 +797,10 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, i
 void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s)
 {
     size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
-    int64_t blocks = (g.n + LISTS_WAVES - 1) / LISTS_WAVES;
-    hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)blocks), dim3(64 * LISTS_WAVES), shm, s, g, recompute, out_ids, out_dist);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), shm, s, g,
+                           recompute, out_ids, out_dist, v0);
+    });
 }
 
 // ---------------------------------------------------------------------------------------

@@ -11,13 +11,13 @@
 
 // ---- walk over the sampled edges: each group of KP lanes (KP = power of two >= k) owns one list
 template <class F>
-__device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, F f)
+__device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, int64_t v0, F f)
 {
     const int lane = tg_lane();
     const int per_wave = 64 / kp;
     const int64_t wave_id = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int sub = lane & (kp - 1), grp = lane / kp;
-    const int64_t v = wave_id * per_wave + grp;
+    const int64_t v = v0 + wave_id * per_wave + grp;
     const bool live = v < g.n && sub < g.k;
     u32 w = live ? g.gid[v * g.k + sub] : 0u;
     const bool fresh = live && (w >> 31);
@@ -34,18 +34,18 @@ __device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, F 
 // arrivals) and remembers it in epos, so that the scatter below needs no second atomic.  The
 // kernels that write the lists (initial lists, list update) number the edges of the lists they
 // have just written in the same way; this kernel serves the cases where that has not happened.
-__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg, u32* epos)
+__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg, u32* epos, int64_t v0)
 {
     const int sub = tg_lane() & (kp - 1);
-    for_each_sampled_edge(g, S, kp, [&](u32 v, u32 u, u32) { epos[(int64_t)v * g.k + sub] = atomicAdd(deg + u, 1u); });
+    for_each_sampled_edge(g, S, kp, v0, [&](u32 v, u32 u, u32) { epos[(int64_t)v * g.k + sub] = atomicAdd(deg + u, 1u); });
 }
 
 // edge v -> u with arrival number a goes to csr[off[u] + a]
 __global__ __launch_bounds__(256) void rev_fill_kernel(TgGraph g, int S, int kp, const u32* __restrict__ epos,
-                                                       const u64* __restrict__ off, u32* __restrict__ csr)
+                                                       const u64* __restrict__ off, u32* __restrict__ csr, int64_t v0)
 {
     const int sub = tg_lane() & (kp - 1);
-    for_each_sampled_edge(g, S, kp, [&](u32 v, u32 u, u32 cls) {
+    for_each_sampled_edge(g, S, kp, v0, [&](u32 v, u32 u, u32 cls) {
         csr[off[u] + epos[(int64_t)v * g.k + sub]] = v | (cls << 31);
     });
 }
@@ -204,12 +204,12 @@ __device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int6
     if (lane == 0) sm.bsz[v] = (u32)nN | ((u32)nT << 8);
 }
 
-__global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev)
+__global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev, int64_t v0)
 {
     __shared__ u64 part[4][2][64];
     __shared__ u32 asm_keys[4][ASM_WORDS], asm_tags[4][ASM_WORDS];
     const int lane = tg_lane(), wave = threadIdx.x >> 6;
-    const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t u = v0 + (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     if (u >= g.n) return;
     const u64 beg = sm.off[u], end = sm.off[u + 1];
     const u64 lt = tg_lanemask_lt();
@@ -279,13 +279,20 @@ void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bo
     int kp = 1;
     while (kp < g.k) kp <<= 1;
     const int per_wave = 64 / kp;
-    const int64_t waves = (g.n + per_wave - 1) / per_wave;
-    const unsigned edge_blocks = (unsigned)((waves + 3) / 4);
+    auto edge_blocks = [&](int64_t cnt) { return dim3((unsigned)(((cnt + per_wave - 1) / per_wave + 3) / 4)); };
     const int64_t nsb = (g.n + SCAN_BLOCK - 1) / SCAN_BLOCK;
-    if (!counted) hipLaunchKernelGGL(rev_count_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, sm.deg, g.gid_next);
+    if (!counted)
+        tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+            hipLaunchKernelGGL(rev_count_kernel, edge_blocks(cnt), dim3(256), 0, s, g, sm.S, kp, sm.deg, g.gid_next, v0);
+        });
     hipLaunchKernelGGL(scan_partial_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp);
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sm.scan_tmp, nsb, sm.off + g.n);
     hipLaunchKernelGGL(scan_final_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp, sm.off);
-    hipLaunchKernelGGL(rev_fill_kernel, dim3(edge_blocks), dim3(256), 0, s, g, sm.S, kp, (const u32*)g.gid_next, (const u64*)sm.off, sm.csr);
-    hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)((g.n + 3) / 4)), dim3(256), 0, s, g, sm, hs_rev);
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(rev_fill_kernel, edge_blocks(cnt), dim3(256), 0, s, g, sm.S, kp, (const u32*)g.gid_next, (const u64*)sm.off,
+                           sm.csr, v0);
+    });
+    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
+        hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, s, g, sm, hs_rev, v0);
+    });
 }

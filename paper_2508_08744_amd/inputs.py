@@ -76,3 +76,26 @@ def sample_rows(n: int, q: int, seed: int = 7) -> np.ndarray:
     if q >= n:
         return np.arange(n, dtype=np.int64)
     return np.sort(rng.choice(n, size=q, replace=False)).astype(np.int64)
+
+
+def make_on_device(config: str, device, n: int | None = None, seed: int | None = None, chunk: int = 1 << 21):
+    """The C4 / C5 recipe (unit-norm Gaussian mixture) drawn on the device with torch's generator, in
+    chunks, for sizes the host should not have to hold (1e8 x 96 fp32 is 38.4 GB).  Same distribution
+    as ``make``, other random numbers: no oracle input comes from here."""
+    import torch
+    if config not in ("C4", "C5"):
+        raise KeyError(config)
+    cfg = CONFIGS[config]
+    idx = int(config[1:])
+    n = cfg["n"] if n is None else n
+    d, ncomp = cfg["d"], cfg["comps"]
+    gen = torch.Generator(device=device).manual_seed(DATA_SEED_BASE + idx if seed is None else seed)
+    centers = torch.randn((ncomp, d), generator=gen, device=device, dtype=torch.float32)
+    X = torch.empty((n, d), device=device, dtype=torch.float32)
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        comp = torch.randint(0, ncomp, (e - s,), generator=gen, device=device)
+        x = centers[comp] + 0.3 * torch.randn((e - s, d), generator=gen, device=device, dtype=torch.float32)
+        x /= x.norm(dim=1, keepdim=True)
+        X[s:e] = x
+    return X

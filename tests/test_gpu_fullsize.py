@@ -71,3 +71,29 @@ def test_c2_full_size():
             distinct = torch.where(pad, -2 - torch.arange(k, device="cuda", dtype=torch.int32)[None, :], out)
             merged = torch.cat([distinct, ids], dim=1).sort(dim=1).values
             assert int((merged[:, 1:] == merged[:, :-1]).sum()) == int(deg.sum())
+
+
+def test_more_nodes_than_one_launch_can_carry():
+    # a launch holds fewer than 2^32 work-items, a wave per node reaches that at 2^26 nodes: the kernels that work
+    # that way are launched in chunks.  Small rows keep this at a few GB; every row of the result is checked on the
+    # device, the last rows (past 2^26) also entry by entry.
+    n, d, k = (1 << 26) + 5000, 4, 4
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    Xg = torch.randint(0, 64, (n, d), generator=gen, device="cuda").to(torch.float32)
+    prm = knn.default_params(k, 2, seed=1, it1=1, it2=1, C=16)
+    prm.R = 4
+    ids, dist, st = knn.knn_build_ex(Xg, prm)
+    assert st["rounds_phase1"] == 1 and st["rounds_phase2"] == 1
+    assert int(ids.min()) >= 0 and int(ids.max()) < n
+    ar = torch.arange(n, device="cuda", dtype=torch.int32)[:, None]
+    assert not bool((ids == ar).any())
+    srt = torch.sort(ids, dim=1).values
+    assert not bool((srt[:, 1:] == srt[:, :-1]).any())
+    assert bool((dist[:, 1:] >= dist[:, :-1]).all())
+    del srt, ar
+    for lo in (0, (1 << 24) - 2000, (1 << 26) - 2000, n - 4000):           # around the chunk borders and at the very end
+        rows = slice(lo, lo + 4000)
+        ref = ((Xg[rows][:, None, :] - Xg[ids[rows].long()]) ** 2).sum(dim=2)
+        assert bool((ref == dist[rows]).all())
+    # better than the random start: the mean distance of the lists dropped over the two rounds, everywhere
+    assert float(dist[-5000:].mean()) < 0.8 * float(((Xg[-5000:] - Xg[:5000]) ** 2).sum(dim=1).mean())
