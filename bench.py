@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--it1", type=int, default=None, help="phase-1 rounds (default: the headline setting)")
     ap.add_argument("--it2", type=int, default=None, help="phase-2 rounds (default: the headline setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="only the build: no pruning and sharding legs (for profiles)")
     ap.add_argument("--cpu-sample", type=int, default=50000)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -123,7 +124,7 @@ def main():
     # HBM bytes per join launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/ (calibrated
     # against a plain copy); only quoted for the workload those runs were made on
     traffic = None
-    extras = not big              # the pruning and sharding legs below are sized for the headline workload
+    extras = not big and not args.no_extras      # the pruning and sharding legs below are sized for the headline workload
     tfile = os.path.join(ROOT, "profiles", "join_C2_1Mx128_k32_hbm_traffic.txt")
     if args.config == "C2" and n == cfg["n"] and os.path.exists(tfile):
         for line in open(tfile):
