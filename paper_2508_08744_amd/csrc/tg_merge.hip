@@ -29,11 +29,30 @@ __device__ inline u32 merge_map_insert(u32* keys, u32* owner, u32 id, u32 entry,
     return h;
 }
 
+// the keys that are not empty move to the front, order kept (tmp: 64 words of 8 bytes private to the wave)
+__device__ inline u64 merge_close_up(u64 key, u64* tmp, int lane)
+{
+    const bool has = key != TG_EMPTY_KEY;
+    const u64 mask = __ballot(has);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (has) tmp[__popcll(mask & tg_lanemask_lt())] = key;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return lane < __popcll(mask) ? tmp[lane] : TG_EMPTY_KEY;
+}
+// true when the keys ascend across the wave (uniform)
+__device__ inline bool merge_ascending(u64 key, int lane)
+{
+    const u64 prev = tg_shfl64(key, lane > 0 ? lane - 1 : 0);
+    return __ballot(lane > 0 && prev > key) == 0ull;
+}
+
 __global__ __launch_bounds__(256) void merge_local_kernel(int32_t* __restrict__ g_ids, float* __restrict__ g_dist, int64_t n, int k,
                                                           const int32_t* __restrict__ l_ids, const float* __restrict__ l_dist,
                                                           int64_t n_local, int k_local, const int32_t* __restrict__ l2g)
 {
-    __shared__ u32 s_keys[4][MERGE_MAP_WORDS];
+    __shared__ __align__(16) u32 s_keys[4][MERGE_MAP_WORDS];
     __shared__ u32 s_owner[4][MERGE_MAP_WORDS];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     u32* keys = s_keys[wave];
@@ -60,8 +79,13 @@ __global__ __launch_bounds__(256) void merge_local_kernel(int32_t* __restrict__ 
         const bool b_in = b_ok && owner[hb] == 64u + (u32)lane;
         u64 ka = a_in ? tg_key(a_dist, (u32)a_id, 0u) : TG_EMPTY_KEY;
         u64 kb = b_in ? tg_key(b_dist, (u32)b_id, 0u) : TG_EMPTY_KEY;
-        ka = tg_wave_sort(ka);
-        kb = tg_wave_sort(kb);
+        // Rows that tg_knn_build wrote are ascending already; an entry that fell out above leaves a
+        // gap.  Closing the gaps (through the map's words, free again by now) keeps the order, and a
+        // row whose neighbours in lanes are then in order needs no sorting network.
+        ka = merge_close_up(ka, reinterpret_cast<u64*>(keys), lane);
+        kb = merge_close_up(kb, reinterpret_cast<u64*>(keys) + 64, lane);
+        if (!merge_ascending(ka, lane)) ka = tg_wave_sort(ka);
+        if (!merge_ascending(kb, lane)) kb = tg_wave_sort(kb);
         const u64 m = tg_wave_merge_low(ka, kb);
         if (lane < k) {
             const bool none = m == TG_EMPTY_KEY;
