@@ -132,12 +132,15 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
     __shared__ __align__(16) float s_dpc[4][64];
     __shared__ __align__(16) float s_nrm[4][64];
     __shared__ u32 s_occ[4][128];
+    __shared__ __align__(16) u64 s_key[4][64];       // the candidates' (distance, id) keys, read by every lane
+    __shared__ u32 s_twin[4][256];                   // 1-hop: id -> first lane that lists it (128 ids, 128 lanes)
     const int wave = threadIdx.x >> 6, lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     int* cid = s_cid[wave];
     float* dpc = s_dpc[wave];
     float* nrm = s_nrm[wave];
     u32* occ = s_occ[wave];
+    u64* skey = s_key[wave];
     const int k = A.k;
     const int nchunks = (A.d + 16 * KS - 1) / (16 * KS);
 
@@ -148,10 +151,25 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         const int32_t u = lane < k ? A.ids[p * k + lane] : -1;
         bool u_ok = u >= 0 && u < A.n && u != p;
         if (!TWO_HOPS) {
-            // candidate l is entry l of the row; an entry that is no candidate (padding, p itself;
-            // repeats are found below, where the keys are compared) keeps its place as a dead one
-            // and reads p's own row
+            // candidate l is entry l of the row; an entry that is no candidate (padding, p itself, an
+            // id that an earlier entry lists already) keeps its place as a dead one and reads p's own row
             m = k;
+            u32* tw = s_twin[wave];
+            for (int i = lane; i < 256; i += 64) tw[i] = FILTER_FREE;
+            filter_wave_sync();
+            {
+                bool pending = u_ok;
+                u32 h = ((u32)u * 0x9E3779B1u) >> 25;
+                while (__ballot(pending)) {
+                    if (pending) {
+                        const u32 old = atomicCAS(tw + h, FILTER_FREE, (u32)u);
+                        if (old == FILTER_FREE || old == (u32)u) { atomicMin(tw + 128 + h, (u32)lane); pending = false; }
+                        else h = (h + 1) & 127u;
+                    }
+                }
+                filter_wave_sync();
+                u_ok = u_ok && tw[128 + h] == (u32)lane;
+            }
             cid[lane] = u_ok ? u : (int)p;
             filter_wave_sync();
         } else {
@@ -285,36 +303,29 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 }
             }
         }
-        // before = the candidates in front of this lane's under (dis(p, c), id); an id that the row
-        // lists again has the same key: the earlier entry goes first and the later one is dead
+        // before = the candidates in front of this lane's under (dis(p, c), id); dead entries have the
+        // largest key and are in front of nothing
         const float own = filter_own<NG>(dp, q4);
         const int my_id = lane < m ? cid[lane] : 0;
-        bool dead = TWO_HOPS ? lane >= m : !u_ok;
+        const bool dead = TWO_HOPS ? lane >= m : !u_ok;
         const u64 key = dead ? TG_EMPTY_KEY : tg_key(own, (u32)my_id, 0u);
-        u32 lt_lo = 0u, lt_hi = 0u, eq_lo = 0u, eq_hi = 0u;
-        {
-            const int m_lo = min(m, 32);
-#pragma unroll 4
-            for (int j = 0; j < m_lo; ++j) {
-                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
-                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
-                const u64 kj = ((u64)hi << 32) | lo;
-                lt_lo |= kj < key ? (1u << j) : 0u;
-                if (!TWO_HOPS) eq_lo |= kj == key ? (1u << j) : 0u;
-            }
-#pragma unroll 4
-            for (int j = 32; j < m; ++j) {
-                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)key, j);
-                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(key >> 32), j);
-                const u64 kj = ((u64)hi << 32) | lo;
-                lt_hi |= kj < key ? (1u << (j - 32)) : 0u;
-                if (!TWO_HOPS) eq_hi |= kj == key ? (1u << (j - 32)) : 0u;
-            }
+        skey[lane] = key;
+        filter_wave_sync();
+        // one bit per other candidate, shifted in from below: after J steps candidate j sits at bit J - 1 - j
+        u32 lt_lo = 0u, lt_hi = 0u;
+        const int J = (m + 7) & ~7, J_lo = min(J, 32);
+        for (int j0 = 0; j0 < J_lo; j0 += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lt_lo = lt_lo + lt_lo + (skey[j0 + j] < key ? 1u : 0u);
         }
-        const u64 twins = (((u64)eq_hi << 32) | eq_lo) & tg_lanemask_lt();
-        if (!TWO_HOPS) dead |= twins != 0ull;
+        for (int j0 = 32; j0 < J; j0 += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lt_hi = lt_hi + lt_hi + (skey[j0 + j] < key ? 1u : 0u);
+        }
+        lt_lo = __brev(lt_lo) >> (32 - J_lo);
+        lt_hi = J > 32 ? __brev(lt_hi) >> (64 - J) : 0u;
         const u64 live = ~__ballot(dead);
-        const u64 before = ((((u64)lt_hi << 32) | lt_lo) | twins) & live;
+        const u64 before = (((u64)lt_hi << 32) | lt_lo) & live;
         filter_wave_sync();
         const u64 occ_by = (((u64)occ[2 * lane + 1] << 32) | occ[2 * lane]) & before;
         // ---- the serial rule as a fixed point ----
