@@ -216,7 +216,8 @@ int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, 
  * counts once (an old entry wins over a local one, else the first in the row), v itself and ids
  * without a node are no entries, a shorter row ends in -1 / +infinity.  Rows of nodes outside the
  * cluster are not touched; a local node whose global id is outside [0, n) is skipped.
- * 1 <= k, k_local <= 64.  Nothing is allocated.
+ * 1 <= k, k_local <= 64; n_local = 0 is allowed (nothing happens, the local pointers may be NULL).
+ * Nothing is allocated.
  */
 int tg_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, const int32_t* l_ids,
                    const float* l_dist, int64_t n_local, int32_t k_local,

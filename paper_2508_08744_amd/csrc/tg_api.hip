@@ -579,10 +579,12 @@ extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t
 extern "C" int tg_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, const int32_t* l_ids, const float* l_dist,
                               int64_t n_local, int32_t k_local, const int32_t* local_to_global, void* stream)
 {
-    if (!g_ids || !g_dist || !l_ids || !l_dist || !local_to_global) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (!g_ids || !g_dist) return fail(TG_ERR_INVALID_ARG, "NULL argument");
     if (n < 1 || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "n = %lld outside 1..2^30-1", (long long)n);
     if (n_local < 0 || n_local > n) return fail(TG_ERR_INVALID_ARG, "n_local = %lld outside 0..n", (long long)n_local);
     if (k < 1 || k > 64 || k_local < 1 || k_local > 64) return fail(TG_ERR_INVALID_ARG, "k = %d, k_local = %d outside 1..64", k, k_local);
+    if (n_local == 0) return TG_OK;              // an empty local index: nothing to merge, its pointers are not looked at
+    if (!l_ids || !l_dist || !local_to_global) return fail(TG_ERR_INVALID_ARG, "NULL argument");
     tg_launch_merge_local(g_ids, g_dist, n, k, l_ids, l_dist, n_local, k_local, local_to_global,
                           reinterpret_cast<hipStream_t>(stream));
     return launch_status("merge of a local index");

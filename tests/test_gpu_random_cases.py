@@ -1,0 +1,77 @@
+"""Many small random cases of the steps that work on finished lists (both prunings and the merge), each
+compared with the oracle bit for bit: shapes that no hand-picked case covers (tiny n, k above n, odd d,
+cand_size and d_out at their limits, rows full of padding)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_08744_amd import knn
+
+pytestmark = pytest.mark.gpu
+
+
+def _graph(rng, n, k):
+    """Rows of random ids with padding, ids without a node, repeats and self ids mixed in."""
+    ids = rng.integers(0, n, size=(n, k)).astype(np.int32)
+    noise = rng.random((n, k))
+    ids[noise < 0.08] = -1
+    ids[(noise >= 0.08) & (noise < 0.11)] = n + rng.integers(0, 5)
+    return ids
+
+
+def test_distance_pruning_random_cases():
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        n = int(rng.integers(2, 300))
+        d = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 33, 64, 100, 128, 129, 200]))
+        hops = int(rng.integers(1, 3))
+        k = int(rng.integers(1, 33 if hops == 2 else 65))
+        cand_size = int(rng.integers(1, 65))
+        d_out = int(rng.integers(1, 65))
+        alpha = float(rng.choice([1.0, 1.0, 1.1, 1.5, 3.0]))
+        X = rng.integers(0, 40, size=(n, d)).astype(np.float32)           # exact in fp32, many ties and twins
+        ids = _graph(rng, n, k)
+        want, want_deg, _ = oracle.filter_dist(X, ids, hops, cand_size, alpha, d_out)
+        out, deg = knn.prune_dist(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), d_out, alpha=alpha, hops=hops,
+                                  cand_size=cand_size, want_degrees=True)
+        where = dict(case=case, n=n, d=d, k=k, hops=hops, cand_size=cand_size, d_out=d_out, alpha=alpha)
+        assert (out.cpu().numpy() == want).all(), where
+        assert (deg.cpu().numpy() == want_deg).all(), where
+
+
+def test_rank_pruning_random_cases():
+    rng = np.random.default_rng(2025)
+    for case in range(60):
+        n = int(rng.integers(1, 400))
+        k = int(rng.integers(1, 65))
+        d_out = int(rng.integers(1, k + 1))
+        ids = _graph(rng, n, k)
+        want, want_cnt = oracle.prune_rank(ids, d_out)
+        out, cnt = knn.prune_rank(torch.from_numpy(ids).cuda(), d_out, want_counts=True)
+        where = dict(case=case, n=n, k=k, d_out=d_out)
+        assert (cnt.cpu().numpy() == want_cnt).all(), where
+        assert (out.cpu().numpy() == want).all(), where
+
+
+def test_merge_random_cases():
+    rng = np.random.default_rng(2026)
+    for case in range(60):
+        n = int(rng.integers(1, 300))
+        k = int(rng.integers(1, 65))
+        kl = int(rng.integers(1, 65))
+        w_ids = np.full((n, k), -1, dtype=np.int32)
+        w_dist = np.full((n, k), np.inf, dtype=np.float32)
+        g_ids, g_dist = knn.lists_clear(n, k)
+        for step in range(int(rng.integers(1, 5))):
+            nl = int(rng.integers(0, n + 1))
+            l2g = rng.permutation(n)[:nl].astype(np.int32)
+            l_ids = rng.integers(-1, max(nl, 1) + 2, size=(nl, kl)).astype(np.int32)
+            l_dist = rng.integers(0, 30, size=(nl, kl)).astype(np.float32)
+            where = dict(case=case, step=step, n=n, k=k, kl=kl, nl=nl)
+            if nl:
+                oracle.merge_local(w_ids, w_dist, l_ids, l_dist, l2g)
+            knn.merge_local(g_ids, g_dist, torch.from_numpy(l_ids).cuda().reshape(nl, kl), torch.from_numpy(l_dist).cuda().reshape(nl, kl),
+                            torch.from_numpy(l2g).cuda())
+            assert (g_ids.cpu().numpy() == w_ids).all(), where
+            assert (g_dist.cpu().numpy() == w_dist).all(), where
