@@ -75,3 +75,30 @@ def test_merge_random_cases():
                             torch.from_numpy(l2g).cuda())
             assert (g_ids.cpu().numpy() == w_ids).all(), where
             assert (g_dist.cpu().numpy() == w_dist).all(), where
+
+
+def test_whole_build_random_cases():
+    """The hot path itself under random shapes and parameters: the finished graph (ids and distances) must equal
+    the oracle's on integer-valued data, whatever the dimension, list length, caps, slot count, retention groups
+    and round counts."""
+    rng = np.random.default_rng(2027)
+    for case in range(36):
+        n = int(rng.integers(70, 1600))
+        d = int(rng.choice([1, 2, 3, 5, 8, 16, 24, 31, 32, 48, 64, 65, 96, 100, 128, 130, 200, 256]))
+        k = int(rng.choice([1, 2, 5, 8, 10, 16, 17, 24, 32, 33, 40, 48, 64]))
+        k = min(k, n - 1)
+        kw = dict(C=int(rng.choice([16, 32, 64, 128, 256])), ng_row=int(rng.choice([2, 4])), ng_col=int(rng.choice([2, 4, 8])),
+                  m=int(rng.integers(1, 5)), S=int(rng.integers(1, 33)), R=int(rng.integers(0, 33)))
+        it1, it2 = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        shrink = 1 if d <= 128 else 4                                   # squared norms stay below 2^23
+        X = np.floor(rng.integers(0, 256, size=(n, d)) / shrink).astype(np.float32)
+        metric = str(rng.choice(["l2", "l2", "ip"]))                     # both are exact on these integers
+        prm = knn.default_params(k, 6, metric=metric, seed=int(rng.integers(1, 1000)), it1=it1, it2=it2, **kw)
+        ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row, ng_col=prm.ng_col,
+                             m=prm.m, seed=int(prm.seed))
+        o.run(it1, it2)
+        oi, od, _ = o.graph()
+        where = dict(case=case, n=n, d=d, k=k, metric=metric, it1=it1, it2=it2, seed=int(prm.seed), **kw)
+        assert (ids.cpu().numpy() == oi).all(), where
+        assert (dist.cpu().numpy().astype(np.float64) == od).all(), where
