@@ -159,6 +159,26 @@ def main():
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
         "updates_per_round": last["updates"],
     }
+    # the same build with the local join on the fp16 matrix instructions (join_f16 = 1, off by default and not part of
+    # `value`): byte-valued features are fp16 numbers, so the graph must come out bit for bit the same
+    if args.config == "C2":
+        prm16 = bench_params(k)
+        prm16.metric = prm.metric
+        prm16.it1, prm16.it2, prm16.join_f16 = prm.it1, prm.it2, 1
+        ws16 = torch.empty(knn.workspace_bytes(n, d, prm16), dtype=torch.uint8, device=dev)
+        knn.knn_build_ex(Xg, prm16, ws16, want_stats=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            ids16, dist16, st16 = knn.knn_build_ex(Xg, prm16, ws16, want_stats=True)
+        torch.cuda.synchronize()
+        ms16 = 1e3 * (time.perf_counter() - t0) / 3
+        r16 = st16["rounds_phase1"]
+        out["join_f16"] = {"ms_per_step": ms16, "points_per_s": n / (ms16 * 1e-3), "ms_join": sum(st16["ms_join"][:r16]),
+                           "join_launch_ms": sum(st16["ms_join"][:r16]) / max(r16, 1),
+                           "recall_at_k": oracle.recall(ids16[rows_g].cpu().numpy(), truth.cpu().numpy()),
+                           "identical_to_fp32_join": bool((ids16 == ids).all() and (dist16 == dist).all())}
+        del ws16, ids16, dist16
     # the next step after the hot path: rank-based pruning of the graph just built (outside `value`).
     # Algorithmic bytes per node: its row, the entries in front of every neighbour's own position, the output.
     if not extras:

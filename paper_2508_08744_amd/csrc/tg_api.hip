@@ -46,6 +46,7 @@ static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
     if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);
     if (!(p->delta >= 0.0f && p->delta < 1.0f)) return fail(TG_ERR_INVALID_ARG, "delta must be in [0, 1)");
     if (p->screen != 0 && p->screen != 1) return fail(TG_ERR_INVALID_ARG, "screen = %d must be 0 or 1", p->screen);
+    if (p->join_f16 != 0 && p->join_f16 != 1) return fail(TG_ERR_INVALID_ARG, "join_f16 = %d must be 0 or 1", p->join_f16);
     return TG_OK;
 }
 
@@ -67,6 +68,7 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->m = 2;
     p->finalize = 1;
     p->screen = 1;
+    p->join_f16 = 0;
     p->seed = 1;
     return TG_OK;
 }
@@ -96,6 +98,7 @@ struct tg_knn_handle {
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     float* xqm;          // its row constants
     u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
+    uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1 and rows of at most 128 values)
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -131,6 +134,9 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
     h->d_screen_on = c.take<u32>(64);
+    h->g.ldh = ld <= 64 ? 64 : ld <= 96 ? 96 : 128;      // what the register-resident join reads per row: 4, 6 or 8 steps of 16 columns
+    h->xh = (p.join_f16 && ld <= 128) ? c.take<uint16_t>((size_t)n * h->g.ldh) : nullptr;
+    h->g.Xh = h->xh;
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);
     h->sm.off = c.take<u64>(n + 1);
@@ -235,6 +241,7 @@ static void ensure_norms(tg_knn_handle* h)
     if (h->norms_done) return;
     int sp = begin_span(h, SPAN_NORMS, 0);
     tg_launch_norms(h->g, h->stream);
+    if (h->xh) tg_launch_narrow(h->g, h->xh, h->stream);
     end_span(h, sp);
     h->norms_done = true;
 }

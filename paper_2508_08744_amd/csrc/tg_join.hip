@@ -18,6 +18,7 @@
 #define JOIN_CELL_BYTES (TG_BLOCK_COLS * 8 * 8)   // one cell per member and opponent group (workgroup kernel)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------------------------------
 // cross-lane helpers: rotations inside a row of 16 lanes are DPP operand modifiers (no LDS)
@@ -367,7 +368,10 @@ struct WaveItem {
 // work record: anchor | |NEW| << 32 | (|NEW|+|OLD|) << 40
 __device__ inline u64 pack_rec(u32 v, int nN, int nT) { return (u64)v | ((u64)nN << 32) | ((u64)nT << 40); }
 
-template <int GMAX, int MODE, int METRIC, int KS, bool FULL>
+// NARROW: the rows come from the fp16 copy (g.Xh, rows of 32 KS values, zero padded): a register
+// then holds eight values, columns 32 s + 8 q .. + 7, and a tile step is one
+// v_mfma_f32_16x16x32_f16 (fp32 accumulation) in place of eight fp32 matrix instructions.
+template <int GMAX, int MODE, int METRIC, int KS, bool FULL, bool NARROW>
 __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot, u64* stat_bins,
                                                         const int32_t* xblk, const int32_t* xsizes, float* xout,
                                                         const u64* __restrict__ wl, const u32* __restrict__ wl_cnt,
@@ -419,6 +423,12 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
     };
     float4 X[GMAX][KS];
     auto load_group = [&](int t, u32 id) {      // t is a compile-time constant at every call site
+        if (NARROW) {
+            const uint16_t* xh = g.Xh + (int64_t)id * g.ldh;
+#pragma unroll
+            for (int s8 = 0; s8 < KS; ++s8) X[t][s8] = *reinterpret_cast<const float4*>(xh + 32 * s8 + 8 * q4);
+            return;
+        }
         const float* x = g.X + (int64_t)id * g.ld;
 #pragma unroll
         for (int s8 = 0; s8 < KS; ++s8) {
@@ -562,10 +572,15 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                     floatx4 acc = (floatx4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s8 = 0; s8 < KS; ++s8) {
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
+                        if (NARROW) {
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, X[i][s8]),
+                                                                          __builtin_bit_cast(halfx8, X[j][s8]), acc, 0, 0, 0);
+                        } else {
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].x, X[j][s8].x, acc, 0, 0, 0);
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].y, X[j][s8].y, acc, 0, 0, 0);
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].z, X[j][s8].z, acc, 0, 0, 0);
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[i][s8].w, X[j][s8].w, acc, 0, 0, 0);
+                        }
                     }
                     // column side: lane (r16, .) is column b = 16 j + r16
                     const int b = 16 * j + r16;
@@ -729,12 +744,16 @@ static void launch_wave_k(const TgGraph& g, const TgSample& sm, const TgCand& c,
 {
     const int64_t wgs = (g.n + 3) / 4;
     const unsigned grid = (unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID);
-    if (g.ld == 16 * KS)
-        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, true>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+    if (g.Xh)       // rows of the fp16 copy are whole steps of 32 values: KS / 2 of them
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS / 2, true, true>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+                           (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
+                           (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+    else if (g.ld == 16 * KS)
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, true, false>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
                            (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
                            (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
     else
-        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, false>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, false, false>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
                            (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
                            (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
 }
@@ -745,8 +764,12 @@ static void launch_wave_dump_k(const TgGraph& g, const int32_t* blk, const int32
     TgSample sm = {};
     TgCand c = {};
     const int64_t wgs = (nb + 3) / 4;
-    hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS, false>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)), dim3(256), 0,
-                       s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
+    if (g.Xh)
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS / 2, true, true>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)),
+                           dim3(256), 0, s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
+    else
+        hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS, false, false>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)),
+                           dim3(256), 0, s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
 }
 // rows of at most 64 / 96 / 128 floats take 4 / 6 / 8 column steps per lane quarter
 template <int GMAX, int METRIC>

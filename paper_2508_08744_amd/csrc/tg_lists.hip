@@ -5,6 +5,7 @@
 // Ownership rule that makes the update lock-free: exactly one wavefront reads and
 // rewrites a given list in a given kernel; other nodes reach a list only through its
 // candidate slots (atomic minimum) or through the previous round's snapshot.
+#include <hip/hip_fp16.h>
 #include "tg_device.h"
 #include "tg_kernels.h"
 
@@ -162,6 +163,31 @@ void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s
     tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
         hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((cnt + 15) / 16)), dim3(256), 0, s, g, Xq, Xqm, v0);
     });
+}
+
+// ---------------------------------------------------------------------------------------
+// fp16 copy of the rows for the local join: round to nearest even, eight values per thread,
+// zero beyond column d.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __restrict__ Xh)
+{
+    const int per_row = g.ldh >> 3;
+    const size_t total = (size_t)g.n * per_row;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const size_t row = i / per_row;
+        const int c0 = (int)(i - row * per_row) * 8;
+        const float* x = g.X + row * (size_t)g.ld;
+        u32 h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = c0 + e < g.d ? (u32)__half_as_ushort(__float2half_rn(x[c0 + e])) : 0u;
+        *reinterpret_cast<uint4*>(Xh + row * (size_t)g.ldh + c0) =
+            make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+}
+void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, hipStream_t s)
+{
+    hipLaunchKernelGGL(narrow_kernel, dim3(grid_for((size_t)g.n * (g.ldh >> 3), 256)), dim3(256), 0, s, g, Xh);
 }
 
 // ---------------------------------------------------------------------------------------

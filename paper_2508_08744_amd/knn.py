@@ -21,7 +21,8 @@ class Params(ctypes.Structure):
     _fields_ = [("k", ctypes.c_int32), ("metric", ctypes.c_int32), ("it1", ctypes.c_int32), ("it2", ctypes.c_int32),
                 ("S", ctypes.c_int32), ("R", ctypes.c_int32), ("C", ctypes.c_int32), ("ng_row", ctypes.c_int32),
                 ("ng_col", ctypes.c_int32), ("m", ctypes.c_int32), ("delta", ctypes.c_float),
-                ("finalize", ctypes.c_int32), ("screen", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+                ("finalize", ctypes.c_int32), ("screen", ctypes.c_int32), ("join_f16", ctypes.c_int32),
+                ("seed", ctypes.c_uint64)]
 
 
 class Stats(ctypes.Structure):

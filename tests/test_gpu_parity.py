@@ -402,3 +402,84 @@ def test_set_graph_round_trip_and_stream():
         assert b.phase2_round() == o.phase2_round()
         assert _same(b.graph(), o.graph())
         b.close()
+
+
+# ---- the local join on f16 matrix instructions (join_f16 = 1) ---------------------------------------------
+
+def _f16(X):
+    """Round to nearest even to f16, by torch's conversion (independent of the library's)."""
+    return torch.from_numpy(np.ascontiguousarray(X)).to(torch.float16).to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("d", [4, 32, 50, 64, 100, 128])
+def test_f16_join_distance_tile(d):
+    """The register-resident join core with join_f16 = 1: fp32 norms of the vectors as given, inner products of
+    the vectors rounded to f16 (a truncating conversion, or a wrong operand layout of the wider matrix
+    instruction, would be far outside the tolerance)."""
+    n = 600
+    rng = np.random.default_rng(100 + d)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    b = knn.Builder(torch.from_numpy(X).cuda(), knn.default_params(16, 4, join_f16=1))
+    shapes = [(32, 32), (1, 1), (17, 30), (64, 0), (5, 0), (16, 16), (2, 0), (1, 63), (40, 24), (33, 15)]
+    blk = np.zeros((len(shapes), 128), dtype=np.int32)
+    sizes = np.zeros((len(shapes), 2), dtype=np.int32)
+    for i, (a, o) in enumerate(shapes):
+        blk[i, :a + o] = rng.choice(n, size=a + o, replace=False)
+        sizes[i] = (a, o)
+    out = b.join_distances(torch.from_numpy(blk), torch.from_numpy(sizes)).cpu().numpy()
+    Xr = _f16(X)
+    nrm = (X.astype(np.float64) ** 2).sum(1)
+    tol = 4e-6 * nrm.max()
+    worst_vs_unrounded = 0.0
+    for i, (a, o) in enumerate(shapes):
+        idx = blk[i, :a + o]
+        ref = nrm[idx][:, None] + nrm[idx][None, :] - 2.0 * Xr[idx] @ Xr[idx].T
+        exact = nrm[idx][:, None] + nrm[idx][None, :] - 2.0 * X[idx].astype(np.float64) @ X[idx].astype(np.float64).T
+        used = np.zeros((a, a + o), dtype=bool)
+        for r in range(a):
+            used[r, r + 1:] = True
+        got = out[i][:a, :a + o]
+        assert np.abs(got[used] - ref[:a][used]).max() <= tol
+        if used.any():
+            worst_vs_unrounded = max(worst_vs_unrounded, np.abs(got[used] - exact[:a][used]).max())
+    assert worst_vs_unrounded > tol, "the rounded copy was not used"
+    b.close()
+
+
+@pytest.mark.parametrize("n,d,k,kw", [(3000, 64, 32, dict(C=64)), (1400, 128, 32, dict(C=256)), (1200, 30, 10, dict(C=32)),
+                                      (1500, 100, 24, dict(C=128)), (900, 256, 32, dict(C=64))])
+def test_f16_join_is_exact_on_representable_data(n, d, k, kw):
+    """Byte-valued features (and eighths of them) are f16 numbers: the rounded copy is exact, products and sums are
+    exact in fp32, so the graph must equal the oracle's bit for bit."""
+    Xi = inputs.make("C2", n=n, d=d, comps=max(2, n // 500))
+    for X in (Xi, np.floor(Xi / 8) / 8):
+        X = np.ascontiguousarray(X, dtype=np.float32)
+        assert (_f16(X) == X).all()
+        prm = knn.default_params(k, 8, seed=7, join_f16=1, **kw)
+        ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        o = _oracle_for(X, prm)
+        o.run(prm.it1, prm.it2)
+        oi, od, _ = o.graph()
+        assert (ids.cpu().numpy() == oi).all()
+        assert (dist.cpu().numpy().astype(np.float64) == od).all()
+
+
+@pytest.mark.parametrize("cfg,metric", [("C1", "l2"), ("C4", "cosine"), ("C4", "ip")])
+def test_f16_join_statistical_parity_on_real_valued_data(cfg, metric):
+    """Real-valued data: the join ranks on rounded vectors, so parity is what it is for the fp32 join: recall within
+    0.005 of the oracle's (mean of 3 seeds), reported distances exact to 1e-4 of fp64, lists well-formed."""
+    sizes = {"C1": dict(n=6000), "C4": dict(n=5000, comps=10)}[cfg]
+    X = inputs.make(cfg, **sizes)
+    k = 16
+    mcode = knn.METRICS[metric]
+    truth, _ = oracle.brute_force_knn(X, k, mcode)
+    gaps = []
+    for seed in (1, 2, 3):
+        prm = knn.default_params(k, 6, metric=metric, seed=seed, C=32, join_f16=1)
+        ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+        ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
+        _check_properties(X, ids, dist, mcode)
+        o = _oracle_for(X, knn.default_params(k, 6, metric=metric, seed=seed, C=32), mcode)
+        o.run(prm.it1, prm.it2)
+        gaps.append(oracle.recall(ids, truth) - oracle.recall(o.graph()[0], truth))
+    assert np.mean(gaps) >= -RECALL_TOL, gaps
