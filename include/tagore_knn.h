@@ -65,14 +65,12 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            high dimension) the following rounds measure every candidate directly
  *   join_f16 1: the local join of phase 1 forms its inner products on the fp16 matrix
  *            instructions from a copy of the vectors rounded to fp16 (round to nearest even;
- *            n x (64, 96 or 128) x 2 bytes of workspace), accumulating in fp32; norms,
+ *            n x (64, 96, 128, or d rounded up to 32) x 2 bytes of workspace), accumulating in fp32; norms,
  *            thresholds, phase 2 and the reported distances stay fp32.  Where every value is an
  *            fp16 number (byte-valued features, say) the copy is exact and the graph is the same
  *            as with 0; elsewhere the join ranks its candidates on rounded vectors (11 significant
  *            bits) and the final recomputation (finalize = 1) restores exact distances.  Values
- *            beyond +-65504 have no fp16 number: such data must not use it.  Applies to rows of
- *            at most 128 values (the register-resident join); longer rows are joined in fp32.
- *            Default 0
+ *            beyond +-65504 have no fp16 number: such data must not use it.  Default 0
  */
 typedef struct tg_knn_params {
     int32_t k;

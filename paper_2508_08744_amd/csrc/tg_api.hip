@@ -98,7 +98,7 @@ struct tg_knn_handle {
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     float* xqm;          // its row constants
     u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
-    uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1 and rows of at most 128 values)
+    uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1)
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -134,8 +134,9 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
     h->d_screen_on = c.take<u32>(64);
-    h->g.ldh = ld <= 64 ? 64 : ld <= 96 ? 96 : 128;      // what the register-resident join reads per row: 4, 6 or 8 steps of 16 columns
-    h->xh = (p.join_f16 && ld <= 128) ? c.take<uint16_t>((size_t)n * h->g.ldh) : nullptr;
+    // the register-resident join reads 64, 96 or 128 columns per row (4, 6 or 8 steps of 16); longer rows are whole steps of 32
+    h->g.ldh = ld <= 64 ? 64 : ld <= 96 ? 96 : ld <= 128 ? 128 : (d + 31) & ~31;
+    h->xh = p.join_f16 ? c.take<uint16_t>((size_t)n * h->g.ldh) : nullptr;
     h->g.Xh = h->xh;
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);

@@ -103,7 +103,9 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
 }
 
 // MODE 0: emit candidates for the stored blocks.  MODE 1: write the distance tile of caller-given blocks.
-template <int DK, int NGR, int NGC, int MODE>
+// NARROW: the rows come from the fp16 copy; a slab then holds 2 DK columns in the same bytes, and a
+// step of 32 columns is one v_mfma_f32_16x16x32_f16 per tile.
+template <int DK, int NGR, int NGC, int MODE, bool NARROW = false>
 __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
                                                             const int32_t* xsizes, float* xout, const u64* wl,
@@ -116,9 +118,13 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     int* s_ids = reinterpret_cast<int*>(s_kid + TG_BLOCK_COLS);
     float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);     // squared norm (or 1/|x| for cosine)
     u64* s_cell = reinterpret_cast<u64*>(smem_raw + JOIN_HDR_BYTES);   // candidates of the block in hand
-    float* tile = reinterpret_cast<float*>(smem_raw + JOIN_HDR_BYTES + JOIN_CELL_BYTES);
-    constexpr int LDT = DK + 4;          // LDS row stride in floats (16-byte pad against bank conflicts)
-    constexpr int F4 = DK / 4;           // float4 per row and slab
+    unsigned char* tile = smem_raw + JOIN_HDR_BYTES + JOIN_CELL_BYTES;
+    constexpr int LDTB = 4 * DK + 16;    // LDS row stride in bytes (16-byte pad against bank conflicts)
+    constexpr int F4 = DK / 4;           // 16-byte pieces per row and slab
+    constexpr int ES = NARROW ? 2 : 4;   // bytes per value
+    constexpr int CS = 4 * DK / ES;      // columns per slab
+    const int ldx = NARROW ? g.ldh : g.ld;                                   // columns per stored row
+    const unsigned char* xbase = NARROW ? reinterpret_cast<const unsigned char*>(g.Xh) : reinterpret_cast<const unsigned char*>(g.X);
     constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -148,21 +154,21 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     // addresses are formed once per block and the loads are unconditional (rows and columns
     // past the end read a valid address and are zeroed).
     float4 pre[PER];
-    const int cpart = (tid % F4) * 4;
-    const float* rp[PER];
+    const int cpart = (tid % F4) * (16 / ES);          // first column of this thread's 16-byte piece
+    const unsigned char* rp[PER];
     bool rv[PER];
 #pragma unroll
     for (int it = 0; it < PER; ++it) {
         const int row = (tid + JOIN_THREADS * it) / F4;
         rv[it] = row < nT;
-        rp[it] = g.X + (int64_t)bids[rv[it] ? row : 0] * g.ld + cpart;
+        rp[it] = xbase + ((int64_t)bids[rv[it] ? row : 0] * ldx + cpart) * ES;
     }
     auto issue = [&](int ks) {
-        const bool cv = ks + cpart < g.ld;
+        const bool cv = ks + cpart < ldx;
         const int kso = cv ? ks : -cpart;
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
-            const float4 val = *reinterpret_cast<const float4*>(rp[it] + kso);
+            const float4 val = *reinterpret_cast<const float4*>(rp[it] + (int64_t)kso * ES);
             pre[it] = (rv[it] & cv) ? val : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
         for (int it = 0; it < PER; ++it) {
             const int e = tid + JOIN_THREADS * it;
             const int row = e / F4;
-            if (row < nT) *reinterpret_cast<float4*>(tile + row * LDT + (e % F4) * 4) = pre[it];
+            if (row < nT) *reinterpret_cast<float4*>(tile + row * LDTB + (e % F4) * 16) = pre[it];
         }
     };
     issue(0);
@@ -212,11 +218,32 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
 #pragma unroll
         for (int tj = 0; tj < 4; ++tj) acc[ti][tj] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
-    for (int ks = 0; ks < g.ld; ks += DK) {
+    for (int ks = 0; ks < ldx; ks += CS) {
         __syncthreads();
         commit();
         __syncthreads();
-        if (ks + DK < g.ld) issue(ks + DK);      // next slab travels while this one is multiplied
+        if (ks + CS < ldx) issue(ks + CS);      // next slab travels while this one is multiplied
+        if (NARROW) {
+            // lane (r, q) reads the 8 consecutive columns 32 s + 8 q .. + 7 of its row: one matrix instruction per step
+            const int kend = min(CS, ldx - ks);         // rows of the fp16 copy are whole steps, zero padded
+            for (int kk = 0; kk < kend; kk += 32) {
+                float4 av[2], bv[4];
+#pragma unroll
+                for (int ti = 0; ti < 2; ++ti)
+                    if (wr + 2 * ti < MT) av[ti] = *reinterpret_cast<const float4*>(tile + ((wr + 2 * ti) * 16 + c16) * LDTB + (kk + 8 * g4) * 2);
+#pragma unroll
+                for (int tj = 0; tj < 4; ++tj)
+                    if (wc + 2 * tj < NT) bv[tj] = *reinterpret_cast<const float4*>(tile + ((wc + 2 * tj) * 16 + c16) * LDTB + (kk + 8 * g4) * 2);
+#pragma unroll
+                for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj < 4; ++tj)
+                        if (act[ti][tj])
+                            acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, av[ti]),
+                                                                                  __builtin_bit_cast(halfx8, bv[tj]), acc[ti][tj], 0, 0, 0);
+            }
+            continue;
+        }
         const int kend = min(DK, (g.ld - ks + 15) & ~15);
         // Lane (r, q) = (lane % 16, lane / 16) reads 4 consecutive columns 16*s + 4*q .. +3 of its
         // row; step t of the four MFMAs then contracts columns {16*s + 4*q + t : q = 0..3}.  The
@@ -225,10 +252,10 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
             float4 av[2], bv[4];
 #pragma unroll
             for (int ti = 0; ti < 2; ++ti)
-                if (wr + 2 * ti < MT) av[ti] = *reinterpret_cast<const float4*>(tile + ((wr + 2 * ti) * 16 + c16) * LDT + kk + 4 * g4);
+                if (wr + 2 * ti < MT) av[ti] = *reinterpret_cast<const float4*>(tile + ((wr + 2 * ti) * 16 + c16) * LDTB + (kk + 4 * g4) * 4);
 #pragma unroll
             for (int tj = 0; tj < 4; ++tj)
-                if (wc + 2 * tj < NT) bv[tj] = *reinterpret_cast<const float4*>(tile + ((wc + 2 * tj) * 16 + c16) * LDT + kk + 4 * g4);
+                if (wc + 2 * tj < NT) bv[tj] = *reinterpret_cast<const float4*>(tile + ((wc + 2 * tj) * 16 + c16) * LDTB + (kk + 4 * g4) * 4);
 #pragma unroll
             for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
@@ -718,13 +745,19 @@ static void allow_large_lds(K kernel, size_t bytes)
 template <int DK, int NGR, int NGC>
 static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, hipStream_t s)
 {
-    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
+    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0, false>, join_lds_bytes(DK, TG_BLOCK_COLS)),
+                        allow_large_lds(join_kernel<DK, NGR, NGC, 0, true>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
     (void)once;
     const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;   // a stored block never exceeds BC rows
     const unsigned grid = (unsigned)(g.n < JOIN_GRID ? g.n : JOIN_GRID);
-    hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
-                       hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
-                       (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
+    if (g.Xh)
+        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, true>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
+                           hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
+                           (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
+    else
+        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, false>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
+                           hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
+                           (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
 }
 static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
                            u64* stat_bins, hipStream_t s)
@@ -734,7 +767,7 @@ static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c
     else if (ngr == 2 && ngc == 8) launch_join_t<64, 2, 8>(g, sm, c, hs_slot, stat_bins, s);
     else if (ngr == 4 && ngc == 2) launch_join_t<64, 4, 2>(g, sm, c, hs_slot, stat_bins, s);
     else if (ngr == 4 && ngc == 4) launch_join_t<64, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else if (g.ld > 64) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, s);   // half as many slabs and barriers
+    else if (g.ld > 64 || (g.Xh && g.ldh > 128)) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, s);   // half as many slabs and barriers
     else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
 }
 
@@ -818,7 +851,8 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
 {
     TgSample sm = {};
     TgCand c = {};
-    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1>, join_lds_bytes(64, TG_BLOCK_COLS)), true);
+    static bool once = (allow_large_lds(join_kernel<64, 2, 2, 1, false>, join_lds_bytes(64, TG_BLOCK_COLS)),
+                        allow_large_lds(join_kernel<64, 2, 2, 1, true>, join_lds_bytes(64, TG_BLOCK_COLS)), true);
     (void)once;
     int skip_le = 0;
     if (wave_path(g, 4, 8)) {      // same routing by block size as the production join
@@ -827,7 +861,12 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
         else { launch_wave_dump<3, 2>(g, blk, sizes, nb, out, 0, s); launch_wave_dump<4, 2>(g, blk, sizes, nb, out, 4, s); }
         skip_le = 4;
     }
-    hipLaunchKernelGGL((join_kernel<64, 2, 2, 1>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
-                       join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
-                       (const u32*)nullptr, nb, skip_le);
+    if (g.Xh)
+        hipLaunchKernelGGL((join_kernel<64, 2, 2, 1, true>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
+                           join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
+                           (const u32*)nullptr, nb, skip_le);
+    else
+        hipLaunchKernelGGL((join_kernel<64, 2, 2, 1, false>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
+                           join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
+                           (const u32*)nullptr, nb, skip_le);
 }

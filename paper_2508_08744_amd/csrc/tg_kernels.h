@@ -35,7 +35,7 @@ struct TgGraph {
     const float* Xqm;   // n x 8: the row constants that go with the codes
     int32_t ldq;        // d rounded up to 16: a row of codes never straddles more lines than it must
     const uint16_t* Xh; // n x ldh: the rows rounded to fp16 for the local join, or null (join in fp32)
-    int32_t ldh;        // 64, 96 or 128 (the smallest that holds d): columns d..ldh-1 are zero
+    int32_t ldh;        // 64, 96 or 128 (the smallest that holds d), d rounded up to 32 beyond: columns d..ldh-1 are zero
 };
 
 struct TgSample {

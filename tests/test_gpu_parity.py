@@ -411,16 +411,17 @@ def _f16(X):
     return torch.from_numpy(np.ascontiguousarray(X)).to(torch.float16).to(torch.float64).numpy()
 
 
-@pytest.mark.parametrize("d", [4, 32, 50, 64, 100, 128])
+@pytest.mark.parametrize("d", [4, 32, 50, 64, 100, 128, 200, 960])
 def test_f16_join_distance_tile(d):
-    """The register-resident join core with join_f16 = 1: fp32 norms of the vectors as given, inner products of
-    the vectors rounded to f16 (a truncating conversion, or a wrong operand layout of the wider matrix
-    instruction, would be far outside the tolerance)."""
+    """Both join cores (register-resident for small blocks of short rows, LDS tiles otherwise) with join_f16 = 1:
+    fp32 norms of the vectors as given, inner products of the vectors rounded to f16 (a truncating conversion,
+    or a wrong operand layout of the wider matrix instruction, would be far outside the tolerance)."""
     n = 600
     rng = np.random.default_rng(100 + d)
     X = rng.standard_normal((n, d)).astype(np.float32)
     b = knn.Builder(torch.from_numpy(X).cuda(), knn.default_params(16, 4, join_f16=1))
-    shapes = [(32, 32), (1, 1), (17, 30), (64, 0), (5, 0), (16, 16), (2, 0), (1, 63), (40, 24), (33, 15)]
+    shapes = [(32, 32), (1, 1), (17, 30), (64, 0), (5, 0), (16, 16), (2, 0), (1, 63), (40, 24), (33, 15), (64, 64), (48, 49),
+              (33, 95), (1, 127)]
     blk = np.zeros((len(shapes), 128), dtype=np.int32)
     sizes = np.zeros((len(shapes), 2), dtype=np.int32)
     for i, (a, o) in enumerate(shapes):
@@ -447,11 +448,14 @@ def test_f16_join_distance_tile(d):
 
 
 @pytest.mark.parametrize("n,d,k,kw", [(3000, 64, 32, dict(C=64)), (1400, 128, 32, dict(C=256)), (1200, 30, 10, dict(C=32)),
-                                      (1500, 100, 24, dict(C=128)), (900, 256, 32, dict(C=64))])
+                                      (1500, 100, 24, dict(C=128)), (900, 256, 32, dict(C=64)), (800, 300, 48, dict(C=128)),
+                                      (1000, 64, 16, dict(C=32, ng_row=2, ng_col=4))])
 def test_f16_join_is_exact_on_representable_data(n, d, k, kw):
     """Byte-valued features (and eighths of them) are f16 numbers: the rounded copy is exact, products and sums are
     exact in fp32, so the graph must equal the oracle's bit for bit."""
     Xi = inputs.make("C2", n=n, d=d, comps=max(2, n // 500))
+    if d > 128:
+        Xi = np.floor(Xi / 4)                 # squared norms stay below 2^23
     for X in (Xi, np.floor(Xi / 8) / 8):
         X = np.ascontiguousarray(X, dtype=np.float32)
         assert (_f16(X) == X).all()
@@ -464,11 +468,11 @@ def test_f16_join_is_exact_on_representable_data(n, d, k, kw):
         assert (dist.cpu().numpy().astype(np.float64) == od).all()
 
 
-@pytest.mark.parametrize("cfg,metric", [("C1", "l2"), ("C4", "cosine"), ("C4", "ip")])
+@pytest.mark.parametrize("cfg,metric", [("C1", "l2"), ("C4", "cosine"), ("C4", "ip"), ("C3", "l2")])
 def test_f16_join_statistical_parity_on_real_valued_data(cfg, metric):
     """Real-valued data: the join ranks on rounded vectors, so parity is what it is for the fp32 join: recall within
     0.005 of the oracle's (mean of 3 seeds), reported distances exact to 1e-4 of fp64, lists well-formed."""
-    sizes = {"C1": dict(n=6000), "C4": dict(n=5000, comps=10)}[cfg]
+    sizes = {"C1": dict(n=6000), "C4": dict(n=5000, comps=10), "C3": dict(n=3000, d=200, comps=6)}[cfg]
     X = inputs.make(cfg, **sizes)
     k = 16
     mcode = knn.METRICS[metric]
