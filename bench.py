@@ -159,12 +159,13 @@ def main():
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
         "updates_per_round": last["updates"],
     }
-    # the same build with the local join on the fp16 matrix instructions (join_f16 = 1, off by default and not part of
-    # `value`): byte-valued features are fp16 numbers, so the graph must come out bit for bit the same
+    # the same build with the local join on the fp16 matrix instructions where that is exact (join_f16 = 2: the library
+    # checks on the device that every value is an fp16 number, as byte-valued features are; off by default and not part
+    # of `value`): the graph must come out bit for bit the same
     if args.config == "C2":
         prm16 = bench_params(k)
         prm16.metric = prm.metric
-        prm16.it1, prm16.it2, prm16.join_f16 = prm.it1, prm.it2, 1
+        prm16.it1, prm16.it2, prm16.join_f16 = prm.it1, prm.it2, 2
         ws16 = torch.empty(knn.workspace_bytes(n, d, prm16), dtype=torch.uint8, device=dev)
         knn.knn_build_ex(Xg, prm16, ws16, want_stats=False)
         torch.cuda.synchronize()

@@ -70,7 +70,11 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            fp16 number (byte-valued features, say) the copy is exact and the graph is the same
  *            as with 0; elsewhere the join ranks its candidates on rounded vectors (11 significant
  *            bits) and the final recomputation (finalize = 1) restores exact distances.  Values
- *            beyond +-65504 have no fp16 number: such data must not use it.  Default 0
+ *            beyond +-65504 have no fp16 number: such data must not use 1.
+ *            2: as 1, but only if every value of X turned out to be an fp16 number when the copy
+ *            was made (a flag on the device; both variants of the join are launched and the one
+ *            whose turn it is not ends at once): the graph is always the same as with 0.
+ *            Default 0
  */
 typedef struct tg_knn_params {
     int32_t k;

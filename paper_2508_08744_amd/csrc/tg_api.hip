@@ -46,7 +46,7 @@ static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
     if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);
     if (!(p->delta >= 0.0f && p->delta < 1.0f)) return fail(TG_ERR_INVALID_ARG, "delta must be in [0, 1)");
     if (p->screen != 0 && p->screen != 1) return fail(TG_ERR_INVALID_ARG, "screen = %d must be 0 or 1", p->screen);
-    if (p->join_f16 != 0 && p->join_f16 != 1) return fail(TG_ERR_INVALID_ARG, "join_f16 = %d must be 0 or 1", p->join_f16);
+    if (p->join_f16 < 0 || p->join_f16 > 2) return fail(TG_ERR_INVALID_ARG, "join_f16 = %d must be 0, 1 or 2", p->join_f16);
     return TG_OK;
 }
 
@@ -98,7 +98,8 @@ struct tg_knn_handle {
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     float* xqm;          // its row constants
     u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
-    uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1)
+    uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1, 2)
+    u32* d_f16_ok;       // join_f16 = 2: device flag, 1 while every value of X is an fp16 number
     int round;           // rounds run so far (both phases)
     int rounds1, rounds2;
     bool phase2;
@@ -137,6 +138,8 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     // the register-resident join reads 64, 96 or 128 columns per row (4, 6 or 8 steps of 16); longer rows are whole steps of 32
     h->g.ldh = ld <= 64 ? 64 : ld <= 96 ? 96 : ld <= 128 ? 128 : (d + 31) & ~31;
     h->xh = p.join_f16 ? c.take<uint16_t>((size_t)n * h->g.ldh) : nullptr;
+    h->d_f16_ok = p.join_f16 == 2 ? c.take<u32>(64) : nullptr;
+    h->g.f16_ok = h->d_f16_ok;
     h->g.Xh = h->xh;
     h->sm.S = p.S; h->sm.R = p.R;
     h->sm.deg = c.take<u32>(n);
@@ -242,7 +245,8 @@ static void ensure_norms(tg_knn_handle* h)
     if (h->norms_done) return;
     int sp = begin_span(h, SPAN_NORMS, 0);
     tg_launch_norms(h->g, h->stream);
-    if (h->xh) tg_launch_narrow(h->g, h->xh, h->stream);
+    if (h->d_f16_ok) tg_launch_fill_u32(h->d_f16_ok, 1, 1u, h->stream);
+    if (h->xh) tg_launch_narrow(h->g, h->xh, h->d_f16_ok, h->stream);
     end_span(h, sp);
     h->norms_done = true;
 }

@@ -128,6 +128,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (g.f16_ok && (*g.f16_ok != 0u) != NARROW) return;      // the other variant's turn
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     if (MODE == 0) {
         for (int c = tid; c < TG_BLOCK_COLS * 8; c += JOIN_THREADS) s_cell[c] = TG_EMPTY_KEY;
@@ -414,6 +415,7 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = tg_lane();
     const int r16 = lane & 15, q4 = lane >> 4;
     const float INF = __builtin_inff();
+    if (g.f16_ok && (*g.f16_ok != 0u) != NARROW) return;      // the other variant's turn
     const int64_t count = wl ? (int64_t)*wl_cnt : direct_count;
     const int64_t nwaves = (int64_t)gridDim.x * 4;
 
@@ -750,11 +752,12 @@ static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c,
     (void)once;
     const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;   // a stored block never exceeds BC rows
     const unsigned grid = (unsigned)(g.n < JOIN_GRID ? g.n : JOIN_GRID);
+    // with the device flag both variants are launched, and the one it does not name ends at once
     if (g.Xh)
         hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, true>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
                            hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
                            (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
-    else
+    if (!g.Xh || g.f16_ok)
         hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, false>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
                            hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
                            (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
@@ -781,7 +784,8 @@ static void launch_wave_k(const TgGraph& g, const TgSample& sm, const TgCand& c,
         hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS / 2, true, true>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
                            (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
                            (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
-    else if (g.ld == 16 * KS)
+    if (g.Xh && !g.f16_ok) return;
+    if (g.ld == 16 * KS)
         hipLaunchKernelGGL((join_wave_kernel<GMAX, 0, METRIC, KS, true, false>), dim3(grid), dim3(256), 0, s, g, sm, c, hs_slot, stat_bins,
                            (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr, (const u64*)(sm.wl + (int64_t)list * g.n),
                            (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
@@ -800,7 +804,7 @@ static void launch_wave_dump_k(const TgGraph& g, const int32_t* blk, const int32
     if (g.Xh)
         hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS / 2, true, true>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)),
                            dim3(256), 0, s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
-    else
+    if (!g.Xh || g.f16_ok)
         hipLaunchKernelGGL((join_wave_kernel<GMAX, 1, METRIC, KS, false, false>), dim3((unsigned)(wgs < JOIN_GRID ? wgs : JOIN_GRID)),
                            dim3(256), 0, s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr, (const u32*)nullptr, nb, gmin);
 }
@@ -865,7 +869,7 @@ void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_
         hipLaunchKernelGGL((join_kernel<64, 2, 2, 1, true>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
                            join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
                            (const u32*)nullptr, nb, skip_le);
-    else
+    if (!g.Xh || g.f16_ok)
         hipLaunchKernelGGL((join_kernel<64, 2, 2, 1, false>), dim3((unsigned)(nb < JOIN_GRID ? nb : JOIN_GRID)), dim3(JOIN_THREADS),
                            join_lds_bytes(64, TG_BLOCK_COLS), s, g, sm, c, 0ull, (u64*)nullptr, blk, sizes, out, (const u64*)nullptr,
                            (const u32*)nullptr, nb, skip_le);

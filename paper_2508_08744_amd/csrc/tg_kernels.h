@@ -36,6 +36,8 @@ struct TgGraph {
     int32_t ldq;        // d rounded up to 16: a row of codes never straddles more lines than it must
     const uint16_t* Xh; // n x ldh: the rows rounded to fp16 for the local join, or null (join in fp32)
     int32_t ldh;        // 64, 96 or 128 (the smallest that holds d), d rounded up to 32 beyond: columns d..ldh-1 are zero
+    const uint32_t* f16_ok; // device flag, or null: 1 while every value of X has turned out to be an fp16 number.  When set,
+                            // both variants of the join are launched and the one the flag does not name ends at once
 };
 
 struct TgSample {
@@ -59,7 +61,8 @@ struct TgCand {
 void tg_launch_norms(const TgGraph& g, hipStream_t s);
 void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges /* or null */, hipStream_t s);
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s);
-void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, hipStream_t s);
+void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag /* cleared when a value is no fp16 number, or null */,
+                      hipStream_t s);
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
 void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool edges_numbered, hipStream_t s);

@@ -169,8 +169,9 @@ void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s
 // fp16 copy of the rows for the local join: round to nearest even, eight values per thread,
 // zero beyond column d.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __restrict__ Xh)
+__global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __restrict__ Xh, u32* exact_flag)
 {
+    bool inexact = false;
     const int per_row = g.ldh >> 3;
     const size_t total = (size_t)g.n * per_row;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -180,14 +181,21 @@ __global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __rest
         const float* x = g.X + row * (size_t)g.ld;
         u32 h[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = c0 + e < g.d ? (u32)__half_as_ushort(__float2half_rn(x[c0 + e])) : 0u;
+        for (int e = 0; e < 8; ++e) {
+            const float val = c0 + e < g.d ? x[c0 + e] : 0.f;
+            const __half hv = __float2half_rn(val);
+            inexact |= __half2float(hv) != val;
+            h[e] = (u32)__half_as_ushort(hv);
+        }
         *reinterpret_cast<uint4*>(Xh + row * (size_t)g.ldh + c0) =
             make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
+    // one store per wave that met such a value, and none once the flag is down
+    if (exact_flag && __ballot(inexact) != 0ull && tg_lane() == 0 && *exact_flag != 0u) *exact_flag = 0u;
 }
-void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, hipStream_t s)
+void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag, hipStream_t s)
 {
-    hipLaunchKernelGGL(narrow_kernel, dim3(grid_for((size_t)g.n * (g.ldh >> 3), 256)), dim3(256), 0, s, g, Xh);
+    hipLaunchKernelGGL(narrow_kernel, dim3(grid_for((size_t)g.n * (g.ldh >> 3), 256)), dim3(256), 0, s, g, Xh, exact_flag);
 }
 
 // ---------------------------------------------------------------------------------------

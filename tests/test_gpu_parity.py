@@ -487,3 +487,25 @@ def test_f16_join_statistical_parity_on_real_valued_data(cfg, metric):
         o.run(prm.it1, prm.it2)
         gaps.append(oracle.recall(ids, truth) - oracle.recall(o.graph()[0], truth))
     assert np.mean(gaps) >= -RECALL_TOL, gaps
+
+
+@pytest.mark.parametrize("n,d,k,kw", [(2000, 128, 32, dict(C=128)), (1200, 200, 16, dict(C=64)), (1500, 48, 24, dict(C=64, ng_row=2, ng_col=2))])
+def test_f16_join_only_where_exact(n, d, k, kw):
+    """join_f16 = 2 narrows only when every value is an f16 number: on such data the graph equals the oracle's, on
+    real-valued data it equals the fp32 join's, bit for bit either way."""
+    Xi = inputs.make("C2", n=n, d=d, comps=4)
+    if d > 128:
+        Xi = np.floor(Xi / 4)
+    prm = knn.default_params(k, 6, seed=3, join_f16=2, **kw)
+    ids, dist, _ = knn.knn_build_ex(torch.from_numpy(Xi).cuda(), prm)
+    o = _oracle_for(Xi, prm)
+    o.run(prm.it1, prm.it2)
+    oi, od, _ = o.graph()
+    assert (ids.cpu().numpy() == oi).all() and (dist.cpu().numpy().astype(np.float64) == od).all()
+    Xr = inputs.make("C1", n=n, d=d)
+    Xr[n // 2, d // 2] = np.float32(1.0) + np.float32(2.0) ** -20          # one value that is no f16 number is enough
+    a_ids, a_dist, _ = knn.knn_build_ex(torch.from_numpy(Xr).cuda(), prm)
+    b_ids, b_dist, _ = knn.knn_build_ex(torch.from_numpy(Xr).cuda(), knn.default_params(k, 6, seed=3, join_f16=0, **kw))
+    assert bool((a_ids == b_ids).all()) and bool((a_dist == b_dist).all())
+    forced, _, _ = knn.knn_build_ex(torch.from_numpy(Xr).cuda(), knn.default_params(k, 6, seed=3, join_f16=1, **kw))
+    assert not bool((forced == b_ids).all()), "rounding real-valued rows should change some decisions"
