@@ -159,10 +159,15 @@ def main():
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
         "updates_per_round": last["updates"],
     }
+    if not extras:
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(args.config, prm, min(args.cpu_sample, n))
+        print(json.dumps(out))
+        return
     # the same build with the local join on the fp16 matrix instructions where that is exact (join_f16 = 2: the library
     # checks on the device that every value is an fp16 number, as byte-valued features are; off by default and not part
     # of `value`): the graph must come out bit for bit the same
-    if args.config == "C2":
+    if args.config == "C2" and n == cfg["n"]:
         prm16 = bench_params(k)
         prm16.metric = prm.metric
         prm16.it1, prm16.it2, prm16.join_f16 = prm.it1, prm.it2, 2
@@ -182,11 +187,6 @@ def main():
         del ws16, ids16, dist16
     # the next step after the hot path: rank-based pruning of the graph just built (outside `value`).
     # Algorithmic bytes per node: its row, the entries in front of every neighbour's own position, the output.
-    if not extras:
-        if not args.no_cpu_baseline:
-            out["cpu_baseline"] = cpu_baseline(args.config, prm, min(args.cpu_sample, n))
-        print(json.dumps(out))
-        return
     d_out = k // 2
     pr_ms = []
     for _ in range(5):
