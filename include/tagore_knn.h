@@ -67,14 +67,16 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            instructions from a copy of the vectors rounded to fp16 (round to nearest even;
  *            n x (64, 96, 128, or d rounded up to 32) x 2 bytes of workspace), accumulating in fp32; norms,
  *            thresholds, phase 2 and the reported distances stay fp32.  Where every value is an
- *            fp16 number (byte-valued features, say) the copy is exact and the graph is the same
- *            as with 0; elsewhere the join ranks its candidates on rounded vectors (11 significant
+ *            fp16 number (byte-valued features, say) the copy is exact (see 2 for what that
+ *            means for the graph); elsewhere the join ranks its candidates on rounded vectors (11 significant
  *            bits) and the final recomputation (finalize = 1) restores exact distances.  Values
  *            beyond +-65504 have no fp16 number: such data must not use 1.
  *            2: as 1, but only if every value of X turned out to be an fp16 number when the copy
  *            was made (a flag on the device; both variants of the join are launched and the one
- *            whose turn it is not ends at once): the graph is always the same as with 0.
- *            Default 0
+ *            whose turn it is not ends at once).  No operand is rounded then, so the join's
+ *            products are those of the fp32 join exactly; its fp32 sums are taken in another
+ *            order, so the graph is the same as with 0 bit for bit where those sums are exact
+ *            (integer-valued data below 2^24) and equally accurate elsewhere.  Default 0
  */
 typedef struct tg_knn_params {
     int32_t k;
