@@ -69,7 +69,8 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            thresholds, phase 2 and the reported distances stay fp32.  Where every value is an
  *            fp16 number (byte-valued features, say) the copy is exact (see 2 for what that
  *            means for the graph); elsewhere the join ranks its candidates on rounded vectors (11 significant
- *            bits) and the final recomputation (finalize = 1) restores exact distances.  Values
+ *            bits), and the list update measures every candidate that enters a list again in fp32
+ *            from the vectors, so lists and thresholds hold exact distances.  Values
  *            beyond +-65504 have no fp16 number: such data must not use 1.
  *            2: as 1, but only if every value of X turned out to be an fp16 number when the copy
  *            was made (a flag on the device; both variants of the join are launched and the one

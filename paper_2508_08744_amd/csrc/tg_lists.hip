@@ -508,8 +508,12 @@ __device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, boo
 // ---------------------------------------------------------------------------------------
 #define UPDATE_MAX_C 256
 #define UPDATE_SET_WORDS 512     // more than 64 + UPDATE_MAX_C ids
+// REMEASURE (the join ranked on rows rounded to fp16): every arrival is measured again in fp32 from the
+// vectors before the list is written, so the lists and their thresholds hold exact distances.
+template <bool REMEASURE>
 __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg, int64_t v0)
 {
+    extern __shared__ float smem[];      // REMEASURE: a row of X and 128 words of scratch per wave
     __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
     __shared__ u32 seen_s[LISTS_WAVES][UPDATE_SET_WORDS];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -572,6 +576,18 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
             L = tg_wave_merge_low(L, ck);
             if (lane >= k) L = TG_EMPTY_KEY;
         }
+        if (REMEASURE) {
+            const bool arrival = lane < k && (L & 2ull) != 0ull;
+            if (__ballot(arrival) != 0ull) {
+                float* xs = smem + (size_t)wave * g.ld;
+                u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+                stage_row(g, v, xs);
+                const float rn_v = g.metric == 2 ? g.rnorm[v] : 1.0f;
+                const float exact = wave_direct_dist<8>(g, xs, rn_v, arrival ? (int)tg_key_id(L) : -1, wscr);
+                if (arrival) L = tg_key(exact, tg_key_id(L), (u32)L & 3u);
+                L = tg_wave_sort(L);           // lanes past k hold the empty key and stay behind
+            }
+        }
     }
     if (deg) number_sampled_edges(v, k, S, tg_key_id(L), ((u32)L & 1u) != 0, deg, g.gid_next);
     if (!any_cand && mf == 0) return;
@@ -586,9 +602,17 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool number_edges, hipStream_t s)
 {
     if (c.C > UPDATE_MAX_C) return;    // the boundary refuses such C; the queue in LDS holds no more
+    // rows rounded for the join whatever their values (not the mode that narrows only where that is exact): measure arrivals again
+    const bool remeasure = g.Xh && !g.f16_ok;
+    const size_t shm = remeasure ? (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32) : 0;
     tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-        hipLaunchKernelGGL(update_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), 0, s, g, sm.S,
-                           c, updates, number_edges ? sm.deg : (u32*)nullptr, v0);
+        const dim3 grid((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES));
+        if (remeasure)
+            hipLaunchKernelGGL(update_kernel<true>, grid, dim3(64 * LISTS_WAVES), shm, s, g, sm.S, c, updates,
+                               number_edges ? sm.deg : (u32*)nullptr, v0);
+        else
+            hipLaunchKernelGGL(update_kernel<false>, grid, dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
+                               number_edges ? sm.deg : (u32*)nullptr, v0);
     });
 }
 
