@@ -102,3 +102,18 @@ def test_whole_build_random_cases():
         where = dict(case=case, n=n, d=d, k=k, metric=metric, it1=it1, it2=it2, seed=int(prm.seed), **kw)
         assert (ids.cpu().numpy() == oi).all(), where
         assert (dist.cpu().numpy().astype(np.float64) == od).all(), where
+
+
+@pytest.mark.parametrize("d,join_f16", [(4096, 0), (4096, 1), (4093, 0), (2050, 2)])
+def test_longest_rows(d, join_f16):
+    """Rows at the documented maximum length (and just below, unaligned): the whole build against the oracle."""
+    rng = np.random.default_rng(d)
+    n, k = 300, 8
+    X = rng.integers(0, 4, size=(n, d)).astype(np.float32)
+    prm = knn.default_params(k, 4, seed=2, C=32, join_f16=join_f16)
+    ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = oracle.NNDescent(X, k, S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row, ng_col=prm.ng_col, m=prm.m, seed=2)
+    o.run(prm.it1, prm.it2)
+    oi, od, _ = o.graph()
+    assert (ids.cpu().numpy() == oi).all()
+    assert (dist.cpu().numpy().astype(np.float64) == od).all()
