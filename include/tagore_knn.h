@@ -162,7 +162,8 @@ int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out);
 /* Current lists as they are (no finalize): ids n x k int32, dist n x k fp32, fresh n x k
  * uint8 (1 = new / unvisited); all device, any may be NULL. */
 int tg_knn_export(tg_knn_handle* h, int32_t* ids, float* dist, uint8_t* fresh);
-/* Replace the lists (rows must be sorted by (dist,id), ids valid); all device. */
+/* Replace the lists (rows must be sorted by (dist,id)); all device.  Ids outside [0, n) are refused
+ * (checked on the host: this call synchronises the stream). */
 int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* dist, const uint8_t* fresh);
 /* Step (1) of a phase-1 round on its own (section 3.1.1): draws the reverse samples of
  * the coming round and writes every anchor's block: blk device n x 128 int32 (NEW ids

@@ -104,6 +104,7 @@ struct tg_knn_handle {
     int rounds1, rounds2;
     bool phase2;
     bool norms_done;
+    bool lists_ready;    // tg_knn_init or tg_knn_import has written the lists
     bool edges_numbered; // the kernel that wrote the current lists has numbered their sampled edges (deg, gid_next)
     // timing
     std::vector<hipEvent_t> ev;
@@ -210,6 +211,7 @@ extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
     h->norms_done = false;
+    h->lists_ready = false;
     h->edges_numbered = false;
     if (h->x_padded) tg_launch_pad_rows(X, n, d, h->x_padded, h->g.ld, h->stream);
     tg_launch_fill_u32(h->sm.deg, (size_t)n, 0u, h->stream);
@@ -262,6 +264,7 @@ extern "C" int tg_knn_init(tg_knn_handle* h)
     h->edges_numbered = true;
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
+    h->lists_ready = true;
     return launch_status("init");
 }
 
@@ -282,6 +285,7 @@ static int read_updates(tg_knn_handle* h, int round, int64_t* updates)
 static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     if (h->phase2) return fail(TG_ERR_INVALID_ARG, "phase 1 round after the switch to phase 2");
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
@@ -308,6 +312,7 @@ extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates) { return 
 extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     tg_launch_mark_all_fresh(h->g, h->stream);
     if (h->edges_numbered) {   // phase 2 reuses the buffer that holds the numbers
         tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
@@ -327,6 +332,7 @@ extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
 extern "C" int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     if (!h->phase2) return fail(TG_ERR_INVALID_ARG, "phase 2 round before tg_knn_begin_phase2");
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
@@ -345,6 +351,7 @@ extern "C" int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates)
 extern "C" int tg_knn_finalize(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
     int sp = begin_span(h, SPAN_FINALIZE, 0);
     tg_launch_finalize(h->g, h->p.finalize, out_ids, out_dist, h->stream);
@@ -399,6 +406,7 @@ extern "C" int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out)
 extern "C" int tg_knn_export(tg_knn_handle* h, int32_t* ids, float* dist, uint8_t* fresh)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     tg_launch_export(h->g, ids, dist, fresh, h->stream);
     return launch_status("export");
 }
@@ -406,16 +414,27 @@ extern "C" int tg_knn_export(tg_knn_handle* h, int32_t* ids, float* dist, uint8_
 extern "C" int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* dist, const uint8_t* fresh)
 {
     if (!h || !ids || !dist || !fresh) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    {
+        // the lists come from the caller: every id is checked on the host before a kernel follows it
+        std::vector<int32_t> hi((size_t)h->g.n * h->g.k);
+        HIP_TRY(hipMemcpyAsync(hi.data(), ids, hi.size() * sizeof(int32_t), hipMemcpyDeviceToHost, h->stream));
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        for (size_t i = 0; i < hi.size(); ++i)
+            if (hi[i] < 0 || hi[i] >= h->g.n)
+                return fail(TG_ERR_INVALID_ARG, "row %lld: id %d out of range", (long long)(i / h->g.k), hi[i]);
+    }
     ensure_norms(h);
     if (h->edges_numbered) tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
     h->edges_numbered = false;
     tg_launch_import(h->g, ids, dist, fresh, h->stream);
+    h->lists_ready = true;
     return launch_status("import");
 }
 
 extern "C" int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* sizes)
 {
     if (!h || !blk || !sizes) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->edges_numbered, h->stream);
     h->edges_numbered = false;
     tg_launch_dump_blocks(h->g, h->sm, blk, sizes, h->stream);

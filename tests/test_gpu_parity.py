@@ -509,3 +509,20 @@ def test_f16_join_only_where_exact(n, d, k, kw):
     assert bool((a_ids == b_ids).all()) and bool((a_dist == b_dist).all())
     forced, _, _ = knn.knn_build_ex(torch.from_numpy(Xr).cuda(), knn.default_params(k, 6, seed=3, join_f16=1, **kw))
     assert not bool((forced == b_ids).all()), "rounding real-valued rows should change some decisions"
+
+
+def test_list_operations_need_lists_and_valid_ids():
+    X = torch.zeros((200, 8), device="cuda")
+    b = knn.Builder(X, knn.default_params(4, 2))
+    for call in (b.phase1_round, b.begin_phase2, b.phase2_round, b.finalize, b.graph, b.sample_blocks):
+        with pytest.raises(knn.TagoreError):
+            call()
+    ids = torch.zeros((200, 4), dtype=torch.int32, device="cuda")
+    ids[17, 2] = 200
+    dist, fresh = torch.zeros((200, 4), device="cuda"), torch.zeros((200, 4), dtype=torch.uint8, device="cuda")
+    # (the binding has a check of its own; this is the library's, through the C boundary)
+    assert knn.lib().tg_knn_import(b._h, ids.data_ptr(), dist.data_ptr(), fresh.data_ptr()) == -1
+    assert b"out of range" in knn.lib().tg_last_error()
+    b.init()
+    b.phase1_round()
+    b.close()
