@@ -180,6 +180,7 @@ int tg_knn_join_distances(tg_knn_handle* h, const int32_t* blk, const int32_t* s
  * Exact k-NN of selected rows by exhaustive search on the GPU (ground truth for the
  * recall of section 7.1).  query_rows: device int64[nq] row indices into X (NULL = rows
  * 0..nq-1); out_ids device nq x k, out_dist device nq x k (may be NULL).  Order (dist, id).
+ * A row index outside [0, n) is refused (checked on the host).
  */
 int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric,
                  const int64_t* query_rows, int64_t nq, int32_t* out_ids, float* out_dist,

@@ -39,7 +39,8 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(const float* __restrict
 #pragma unroll
     for (int q = 0; q < EXQ; ++q) {
         const int64_t qi = qgroup * EXQ + q;
-        qrow[q] = qi < nq ? (rows ? rows[qi] : qi) : -1;
+        const int64_t asked = qi < nq ? (rows ? rows[qi] : qi) : -1;
+        qrow[q] = asked < n ? asked : -1;               // a row index outside [0, n) is no query: its output stays empty
         qrn[q] = (metric == 2 && qrow[q] >= 0) ? rnorm[qrow[q]] : 1.0f;
         for (int col = lane * 4; col < ld; col += 256) {
             float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -132,8 +133,9 @@ __global__ __launch_bounds__(256) void exact_merge_kernel(const u64* __restrict_
         if (lane >= k) top = TG_EMPTY_KEY;
     }
     if (lane < k) {
-        out_ids[qi * k + lane] = (int32_t)tg_key_id(top);
-        if (out_dist) out_dist[qi * k + lane] = tg_key_dist(top);
+        const bool none = top == TG_EMPTY_KEY;
+        out_ids[qi * k + lane] = none ? -1 : (int32_t)tg_key_id(top);
+        if (out_dist) out_dist[qi * k + lane] = none ? __builtin_inff() : tg_key_dist(top);
     }
 }
 

@@ -526,3 +526,10 @@ def test_list_operations_need_lists_and_valid_ids():
     b.init()
     b.phase1_round()
     b.close()
+
+
+def test_exact_knn_refuses_rows_outside_the_data():
+    X = torch.from_numpy(inputs.make("C1", n=500)).cuda()
+    for bad in (500, -7, 10**9):
+        with pytest.raises(knn.TagoreError):
+            knn.exact_knn(X, 5, "l2", torch.tensor([3, bad, 499], dtype=torch.int64))
