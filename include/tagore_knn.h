@@ -142,15 +142,15 @@ int tg_knn_create(tg_knn_handle** h, const float* X, int64_t n, int32_t d, const
                   void* workspace, size_t workspace_bytes, void* stream);
 int tg_knn_destroy(tg_knn_handle* h);
 
-/* Algorithm 1 lines 1-2: random lists, their distances, sorted, every entry "new". */
+/* Algorithm 1, initialisation: random lists, their distances, sorted, every entry "new". */
 int tg_knn_init(tg_knn_handle* h);
-/* Algorithm 1 lines 4-7: one phase-1 round (sample, local join, update).  updates: host,
+/* Algorithm 1, phase-1 loop: one phase-1 round (sample, local join, update).  updates: host,
  * may be NULL; when given, the call waits for the round and stores the number of list
  * entries it replaced. */
 int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates);
 /* Phase switch: every list entry becomes "unvisited". */
 int tg_knn_begin_phase2(tg_knn_handle* h);
-/* Algorithm 1 lines 9-12: one phase-2 round. */
+/* Algorithm 1, phase-2 loop: one phase-2 round. */
 int tg_knn_phase2_round(tg_knn_handle* h, int64_t* updates);
 /* Writes the graph: with finalize = 1 distances are recomputed directly and rows re-sorted. */
 int tg_knn_finalize(tg_knn_handle* h, int32_t* out_ids, float* out_dist);

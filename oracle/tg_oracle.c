@@ -277,7 +277,7 @@ static int cand_cmp(const void *a, const void *b)
 }
 
 /* ------------------------------------------------------------------ */
-/* Algorithm 1, lines 1-2: random neighbour lists.                     */
+/* Algorithm 1, initialisation: random neighbour lists.                */
 /* Node v draws ids  floor(n * U_t)  for t = 0,1,2,...  and keeps the  */
 /* first k that differ from v and from each other; their distances are */
 /* computed, the list is sorted, and every entry starts as "new".      */
@@ -421,7 +421,7 @@ static int64_t merge_all(onnd_t *o)
 }
 
 /* ------------------------------------------------------------------ */
-/* Phase 1 round (Algorithm 1 lines 4-7; steps (1)-(3) of 3.1.1).      */
+/* Phase 1 round (Algorithm 1, first loop; steps (1)-(3) of 3.1.1).    */
 /* ------------------------------------------------------------------ */
 typedef struct { uint32_t prio; int32_t src; } rev_t;
 
@@ -612,7 +612,7 @@ void onnd_begin_phase2(void *h)
 }
 
 /* ------------------------------------------------------------------ */
-/* Phase 2 round (Algorithm 1 lines 9-12): node v expands its first m  */
+/* Phase 2 round (Algorithm 1, second loop): node v expands its first m */
 /* unvisited neighbours u, reads G[u] as it stood when the round began,*/
 /* measures v against those nodes, and updates G[v] only.              */
 /* ------------------------------------------------------------------ */

@@ -1,6 +1,6 @@
-// Neighbour-list kernels: norms, random initial lists (Algorithm 1 lines 1-2), the
+// Neighbour-list kernels: norms, random initial lists (Algorithm 1, initialisation), the
 // lock-free list update of section 4.2, the phase-2 expand-and-update round
-// (Algorithm 1 lines 9-12), finalize, and state export/import.
+// (Algorithm 1, phase-2 loop), finalize, and state export/import.
 //
 // Ownership rule that makes the update lock-free: exactly one wavefront reads and
 // rewrites a given list in a given kernel; other nodes reach a list only through its
@@ -424,7 +424,7 @@ __device__ inline void number_sampled_edges(int64_t v, int k, int S, u32 id, boo
 }
 
 // ---------------------------------------------------------------------------------------
-// Algorithm 1 lines 1-2.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
+// Algorithm 1, initialisation.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
 // hash and keeps the first k that differ from v and from all earlier draws.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int S, u32* deg, int64_t v0)
@@ -630,7 +630,7 @@ void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------------
-// Algorithm 1 lines 9-12, one wave per node v: take the first m unvisited entries u of
+// Algorithm 1, phase-2 loop, one wave per node v: take the first m unvisited entries u of
 // G[v], mark them visited, read G[u] from the lists as they stood when the round began
 // (g.gid; this round writes g.gid_next), measure v against the ids that are neither v nor
 // listed nor met earlier in this round, and merge them into G[v].

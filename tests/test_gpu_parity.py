@@ -164,7 +164,7 @@ def test_join_statistics_count_the_needed_pairs():
 
 @pytest.mark.parametrize("k,m", [(16, 2), (24, 3), (40, 2)])
 def test_phase2_counts_every_candidate_once(k, m):
-    """Algorithm 1 lines 9-12: the candidates of a round are the ids listed by the m expanded
+    """Algorithm 1, phase-2 loop: the candidates of a round are the ids listed by the m expanded
     neighbours that are neither v, nor in G[v], nor met before in the same round."""
     X = inputs.make("C2", n=2000, d=32, comps=4)
     prm = knn.default_params(k, 6, seed=2, m=m)

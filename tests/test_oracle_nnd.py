@@ -352,7 +352,7 @@ def test_new_old_pair_reaches_both_lists():
 
 
 def test_phase2_semantics():
-    # Algorithm 1 lines 9-12 and the non-revisitation rule of section 4.1
+    # the phase-2 loop of Algorithm 1 and the non-revisitation rule of section 4.1
     X = inputs.make("C1", n=500, d=8)
     k, m = 10, 2
     o = oracle.NNDescent(X, k, C=32, m=m, seed=3)
