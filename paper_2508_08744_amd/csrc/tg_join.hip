@@ -552,7 +552,6 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        const u32* s_salt = sh_salt[wave][buf];
         const u32* s_okd = sh_okd[wave][buf];
         const u32* s_kid = sh_kid[wave][buf];
         const int* s_ids = sh_ids[wave][buf];
