@@ -66,6 +66,8 @@ def lib():
         L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.ofilter_dist.restype = i32
         L.ofilter_dist.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, ctypes.c_float, i32, vp, vp, vp]
+        L.ofilter.restype = i32
+        L.ofilter.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.omerge_local.restype = i32
         L.omerge_local.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, vp]
         L.oracle_merge_list.restype = i64
@@ -170,6 +172,25 @@ def filter_dist(X, ids, hops: int, cand_size: int, alpha: float, d_out: int, n_d
     margin = np.empty(n_do, dtype=np.float64)
     rc = lib().ofilter_dist(X.ctypes.data, n, X.shape[1], ids.ctypes.data, k, n_do, hops, cand_size,
                             float(alpha), d_out, out.ctypes.data, deg.ctypes.data, margin.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return out, deg, margin
+
+
+def filter_angle(X, ids, hops: int, cand_size: int, gamma_deg: float, d_out: int, n_do=None):
+    """Angle-based pruning (section 3.2, the NSSG rule: a candidate is inserted iff its direction from p makes
+    an angle above gamma with that of every neighbour inserted before) over the 1-hop or 2-hop candidates.
+    Returns (out_ids n_do x d_out padded with -1, degrees, margins)."""
+    X = _f32(X)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n, k = ids.shape
+    assert X.shape[0] == n
+    n_do = n if n_do is None else int(n_do)
+    out = np.empty((n_do, d_out), dtype=np.int32)
+    deg = np.empty(n_do, dtype=np.int32)
+    margin = np.empty(n_do, dtype=np.float64)
+    rc = lib().ofilter(X.ctypes.data, n, X.shape[1], ids.ctypes.data, k, n_do, hops, cand_size, 1, float(gamma_deg), d_out,
+                       out.ctypes.data, deg.ctypes.data, margin.ctypes.data)
     if rc != 0:
         raise ValueError("bad arguments")
     return out, deg, margin

@@ -1,7 +1,8 @@
 /*
- * CPU oracle for the distance-based pruning of a k-NN graph in the Collect-Filter-Store
- * procedure (paper section 5.1, the algorithm "CFS procedure of pruning"; the NSG and
- * Vamana rows of the table of pruning strategies and their description in section 3.2).
+ * CPU oracle for the distance-based and the angle-based pruning of a k-NN graph in the
+ * Collect-Filter-Store procedure (paper section 5.1, the algorithm "CFS procedure of
+ * pruning"; the NSG, Vamana and NSSG rows of the table of pruning strategies and their
+ * description in section 3.2).
  *
  * THIS IS TEST INFRASTRUCTURE: a plain, slow, single-threaded definition written out,
  * used only by the test-suite.  It shares no code with the HIP library.
@@ -16,11 +17,17 @@
  *                dis(p, p') < alpha * dis(p*, p')            (alpha = 1: NSG; alpha > 1: Vamana)
  *            until R holds d_out nodes.  dis is the Euclidean distance; this library stores
  *            its square, so the test is  sq(p, p') < alpha^2 * sq(p*, p').
+ *            Angle rule (NSSG): p' is inserted iff for every p* already in R the angle between
+ *            p -> p* and p -> p' exceeds gamma.  With a = sq(p, p*), b = sq(p, p'), c = sq(p*, p')
+ *            the cosine of that angle is (a + b - c) / (2 sqrt(a b)), so the test is
+ *                t < 0  or  t^2 < 4 cos^2(gamma) (a b),   t = a + b - c      (0 < gamma <= 90 degrees).
  *   Store    R in insertion order, padded with -1.
  *
  * Precision: squared distances are summed in double from the float inputs and then rounded
- * to float; the comparison above is taken in float (alpha^2 and the product rounded to
- * float), the precision the GPU decides in.  On integer-valued data below 2^24 every one of
+ * to float; the comparisons above are taken in float, every operation rounded to float in the
+ * order written: alpha^2 * sq;  t = (a + b) - c, t * t, c4 * (a * b) with c4 = 4 cos^2(gamma)
+ * formed in double and rounded once (a cosine below 1e-12 counts as 0: gamma = 90 degrees).
+ * This is the precision the GPU decides in.  On integer-valued data below 2^24 every one of
  * these values is exact.
  *
  * Pinning (tests/test_oracle_filter.py): closed forms on a line and on a circle, the strict
@@ -65,14 +72,19 @@ static int cand_less(const void *pa, const void *pb)
  * the sum of the squared norms of the nodes involved (0 when equal keys were ordered by id).
  * A row whose margin is far above float rounding has one possible result in any arithmetic.
  * Returns 0, or -1 on bad arguments. */
-int ofilter_dist(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t n_do,
-                 int hops, int cand_size, float alpha, int d_out,
-                 int32_t *out_ids, int32_t *out_deg, double *out_margin)
+/* rule 0: distance rule, thres = alpha >= 1.  rule 1: angle rule, thres = gamma in degrees, 0 < gamma <= 90. */
+int ofilter(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t n_do,
+            int hops, int cand_size, int rule, float thres, int d_out,
+            int32_t *out_ids, int32_t *out_deg, double *out_margin)
 {
     if (!X || !ids || !out_ids || n < 1 || d < 1 || k < 1 || n_do < 0 || n_do > n) return -1;
-    if ((hops != 1 && hops != 2) || cand_size < 1 || d_out < 1 || !(alpha >= 1.0f)) return -1;
+    if ((hops != 1 && hops != 2) || cand_size < 1 || d_out < 1) return -1;
+    if (rule == 0 ? !(thres >= 1.0f) : (rule != 1 || !(thres > 0.0f && thres <= 90.0f))) return -1;
     g_X = X; g_d = d;
-    const float a2 = alpha * alpha;
+    const float a2 = thres * thres;
+    double cg = cos((double)thres * 3.14159265358979323846 / 180.0);
+    if (fabs(cg) < 1e-12) cg = 0.0;
+    const float c4 = (float)(4.0 * cg * cg);
     int64_t cap = (int64_t)k + (hops == 2 ? (int64_t)k * k : 0);
     cand_t *cand = (cand_t *)malloc((size_t)cap * sizeof(cand_t));
     int64_t *stamp = (int64_t *)malloc((size_t)n * sizeof(int64_t));
@@ -120,10 +132,25 @@ int ofilter_dist(const float *X, int64_t n, int d, const int32_t *ids, int k, in
             double m_keep = INFINITY, m_drop = 0.0;
             for (int r = 0; r < deg; ++r) {
                 float drc = (float)sq64(R[r], c);
-                float rhs = a2 * drc;
                 double sc = np_ + norm64(c) + norm64(R[r]);
-                double g = fabs((double)lhs - (double)rhs) / (sc > 0 ? sc : 1.0);
-                if (lhs < rhs) { if (g < m_keep) m_keep = g; }
+                int pass;
+                double g;
+                if (rule == 0) {
+                    float rhs = a2 * drc;
+                    pass = lhs < rhs;
+                    g = fabs((double)lhs - (double)rhs) / (sc > 0 ? sc : 1.0);
+                } else {
+                    float a = (float)sq64(p, R[r]);
+                    float t = (a + lhs) - drc;
+                    float tt = t * t;
+                    float ab = a * lhs;
+                    float rhs = c4 * ab;
+                    pass = t < 0.0f || tt < rhs;
+                    /* distance from flipping: of t from 0, or of t^2 from the threshold, in squared-length units */
+                    double g1 = fabs((double)t), g2 = fabs((double)tt - (double)rhs) / (fabs((double)t) + sqrt((double)rhs) + 1e-300);
+                    g = (t < 0.0f ? g1 : (g1 < g2 ? g1 : g2)) / (sc > 0 ? sc : 1.0);
+                }
+                if (pass) { if (g < m_keep) m_keep = g; }
                 else { keep = 0; if (g > m_drop) m_drop = g; }
             }
             double mcand = keep ? m_keep : m_drop;      /* dropped: safe if one occluder is safe */
@@ -137,4 +164,11 @@ int ofilter_dist(const float *X, int64_t n, int d, const int32_t *ids, int k, in
     }
     free(cand); free(stamp); free(R);
     return 0;
+}
+
+int ofilter_dist(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t n_do,
+                 int hops, int cand_size, float alpha, int d_out,
+                 int32_t *out_ids, int32_t *out_deg, double *out_margin)
+{
+    return ofilter(X, n, d, ids, k, n_do, hops, cand_size, 0, alpha, d_out, out_ids, out_deg, out_margin);
 }
