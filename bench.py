@@ -201,7 +201,8 @@ def main():
     out["prune_rank"] = {"k": k, "d_out": d_out, "ms": pr_ms, "points_per_s": n / (pr_ms * 1e-3),
                          "roofline": {"bound": "hbm", "achieved": pr_bytes / (pr_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                       "unit": "GB/s", "frac": pr_bytes / (pr_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
-    # and the distance-based pruning (Vamana's rule over the neighbours, NSG's over two hops) of the same graph.
+    # and the distance-based pruning (Vamana's rule over the neighbours, NSG's over two hops) and the angle-based
+    # one (NSSG's rule at 60 degrees, over the neighbours and over two hops) of the same graph.
     # Algorithmic bytes per node: the rows of its candidates (all k neighbours; over two hops every distinct
     # candidate once, counted on a sample of nodes) and of itself, the id rows read, the output.
     pd_cases = []
@@ -210,20 +211,25 @@ def main():
         two = torch.cat([uniq[:, :, None].expand(-1, -1, 1), ids[uniq.reshape(-1)].reshape(4096, k, k).long()], dim=2).reshape(4096, -1)
         two = two.sort(dim=1).values
         q_mean = float(((two[:, 1:] != two[:, :-1]).sum(dim=1) + 1).float().mean())     # distinct ids within two hops (self included)
-        for hops, alpha, cands in ((1, 1.2, float(k)), (2, 1.0, q_mean)):
+        for name, rule, hops, thres, cands in (("prune_dist_1hop", "alpha", 1, 1.2, float(k)), ("prune_dist_2hop", "alpha", 2, 1.0, q_mean),
+                                               ("prune_angle_1hop", "gamma_deg", 1, 60.0, float(k)),
+                                               ("prune_angle_2hop", "gamma_deg", 2, 60.0, q_mean)):      # NSSG's setting in the paper
             ms_l = []
             for _ in range(5):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                pd_out = knn.prune_dist(Xg, ids, k, alpha=alpha, hops=hops)
+                if rule == "alpha":
+                    pd_out = knn.prune_dist(Xg, ids, k, alpha=thres, hops=hops)
+                else:
+                    pd_out = knn.prune_angle(Xg, ids, k, gamma_deg=thres, hops=hops)
                 e1.record()
                 torch.cuda.synchronize()
                 ms_l.append(e0.elapsed_time(e1))
             ms_pd = sorted(ms_l)[len(ms_l) // 2]
             by = n * (4.0 * d * (cands + 1) + 4.0 * k * (1 if hops == 1 else 1 + k) + 4.0 * k)
-            pd_cases.append((hops, alpha, pd_out))
-            out["prune_dist_%dhop" % hops] = {
-                "alpha": alpha, "d_out": k, "cand_size": 64, "candidates_per_node": cands, "ms": ms_pd,
+            pd_cases.append((name, rule, hops, thres, pd_out))
+            out[name] = {
+                rule: thres, "d_out": k, "mean_degree": float((pd_out >= 0).sum(dim=1).float().mean()), "cand_size": 64, "candidates_per_node": cands, "ms": ms_pd,
                 "points_per_s": n / (ms_pd * 1e-3),
                 "roofline": {"bound": "hbm", "achieved": by / (ms_pd * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": by / (ms_pd * 1e-3) / 1e9 / HBM_PEAK_GBS}}
@@ -283,12 +289,12 @@ def main():
                 "sample": "the merge of the last cluster (%d nodes) into the lists of the other seven, %.1f s" % (int(mm.numel()), dt),
                 "identical": bool((a_ids.cpu().numpy() == w_ids).all() and (a_dist.cpu().numpy() == w_dist).all())}
         ids_h = ids.cpu().numpy()
-        for hops, alpha, pd_out in pd_cases:
+        for name, rule, hops, thres, pd_out in pd_cases:
             n_do = min(n, 20000 if hops == 1 else 3000)
             t0 = time.perf_counter()
-            want, _, _ = oracle.filter_dist(X, ids_h, hops, 64, alpha, k, n_do=n_do)
+            want, _, _ = (oracle.filter_dist if rule == "alpha" else oracle.filter_angle)(X, ids_h, hops, 64, thres, k, n_do=n_do)
             dt = time.perf_counter() - t0
-            out["prune_dist_%dhop" % hops]["cpu_baseline"] = {
+            out[name]["cpu_baseline"] = {
                 "value": n_do / dt, "unit": "points/s", "cores": 1, "kind": "oracle",
                 "sample": "rows of the first %d nodes of the graph just built, %.1f s" % (n_do, dt),
                 "identical": bool((pd_out[:n_do].cpu().numpy() == want).all())}

@@ -223,6 +223,21 @@ int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, 
                   int32_t* out_ids, int32_t* out_deg, void* stream);
 
 /*
+ * Angle-based pruning of a k-NN graph by the same Collect-Filter-Store procedure (section 5.1) with
+ * the serial rule of NSSG (section 3.2).  Everything is as for tg_prune_dist except the Filter:
+ * closest first, p' is inserted iff the angle at p between p* and p' exceeds gamma for every p*
+ * inserted before it, until d_out are in.  gamma_deg: the angle in degrees, 0 < gamma_deg <= 90
+ * (60 is the usual choice).  With a = sq(p, p*), b = sq(p, p'), c = sq(p*, p') and t = (a + b) - c
+ * the test is  t < 0  or  t * t < c4 * (a * b),  c4 = 4 cos^2(gamma) rounded to fp32 (exactly 0 at
+ * 90 degrees), every operation in fp32 in the order written, c = |p*|^2 + |p'|^2 - 2 <p*, p'>.
+ * A candidate at p's own position, or at the position of an inserted node, is never inserted.
+ * Errors as for tg_prune_dist, TG_ERR_INVALID_ARG for gamma_deg outside (0, 90].
+ */
+int tg_prune_angle(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k,
+                   int32_t hops, int32_t cand_size, float gamma_deg, int32_t d_out,
+                   int32_t* out_ids, int32_t* out_deg, void* stream);
+
+/*
  * Merge of a local index into the global neighbour lists (section 6.1: a node belongs to several
  * clusters, every cluster gets a local index, and the node's list becomes merge(list so far, its list
  * in the local index)).  g_ids, g_dist: device n x k, updated in place; an unused entry has id -1 and

@@ -4,6 +4,7 @@
 #include "tg_device.h"
 #include "tg_kernels.h"
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -590,8 +591,8 @@ extern "C" int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32
     return launch_status("rank-based pruning");
 }
 
-extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops,
-                             int32_t cand_size, float alpha, int32_t d_out, int32_t* out_ids, int32_t* out_deg, void* stream)
+static int check_filter(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops, int32_t cand_size,
+                        int32_t d_out, const int32_t* out_ids)
 {
     if (!X || !knn_ids || !out_ids) return fail(TG_ERR_INVALID_ARG, "NULL argument");
     if (n < 1 || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "n = %lld outside 1..2^30-1", (long long)n);
@@ -600,11 +601,33 @@ extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t
     if (hops != 1 && hops != 2) return fail(TG_ERR_INVALID_ARG, "hops = %d must be 1 or 2", hops);
     if (cand_size < 1 || cand_size > 64) return fail(TG_ERR_INVALID_ARG, "cand_size = %d outside 1..64", cand_size);
     if (d_out < 1 || d_out > 64) return fail(TG_ERR_INVALID_ARG, "d_out = %d outside 1..64", d_out);
-    if (!(alpha >= 1.0f) || !(alpha <= 1e6f)) return fail(TG_ERR_INVALID_ARG, "alpha must be in [1, 1e6]");
     if (hops == 2 && k > 32) return fail(TG_ERR_UNSUPPORTED, "hops = 2 needs k <= 32 (k = %d)", k);
-    tg_launch_filter_dist(X, n, d, knn_ids, k, hops, cand_size, alpha, d_out, out_ids, out_deg,
-                          reinterpret_cast<hipStream_t>(stream));
+    return TG_OK;
+}
+
+extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops,
+                             int32_t cand_size, float alpha, int32_t d_out, int32_t* out_ids, int32_t* out_deg, void* stream)
+{
+    const int rc = check_filter(X, n, d, knn_ids, k, hops, cand_size, d_out, out_ids);
+    if (rc != TG_OK) return rc;
+    if (!(alpha >= 1.0f) || !(alpha <= 1e6f)) return fail(TG_ERR_INVALID_ARG, "alpha must be in [1, 1e6]");
+    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, false, alpha * alpha, d_out, out_ids, out_deg,
+                     reinterpret_cast<hipStream_t>(stream));
     return launch_status("distance-based pruning");
+}
+
+extern "C" int tg_prune_angle(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops,
+                              int32_t cand_size, float gamma_deg, int32_t d_out, int32_t* out_ids, int32_t* out_deg, void* stream)
+{
+    const int rc = check_filter(X, n, d, knn_ids, k, hops, cand_size, d_out, out_ids);
+    if (rc != TG_OK) return rc;
+    if (!(gamma_deg > 0.0f) || !(gamma_deg <= 90.0f)) return fail(TG_ERR_INVALID_ARG, "gamma must be in (0, 90] degrees");
+    // 4 cos^2(gamma), formed in double and rounded once; the cosine of 90 degrees is taken as 0
+    double cg = cos((double)gamma_deg * 3.14159265358979323846 / 180.0);
+    if (fabs(cg) < 1e-12) cg = 0.0;
+    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, true, (float)(4.0 * cg * cg), d_out, out_ids, out_deg,
+                     reinterpret_cast<hipStream_t>(stream));
+    return launch_status("angle-based pruning");
 }
 
 extern "C" int tg_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, const int32_t* l_ids, const float* l_dist,

@@ -1,9 +1,13 @@
-// Distance-based pruning of a k-NN graph in the Collect-Filter-Store procedure (section 5.1;
-// the NSG and Vamana rows of the table of pruning strategies, section 3.2).  For node p the
-// candidates are its neighbours (hops = 1) or those and their neighbours (hops = 2), ordered
-// by (dis(p, c), id) and cut to cand_size; they are taken closest first and p' is inserted
-// iff dis(p, p') < alpha dis(p*, p') for every p* inserted before, until d_out are in.
-// Distances are squared here, so the test uses alpha^2.
+// Distance-based and angle-based pruning of a k-NN graph in the Collect-Filter-Store procedure
+// (section 5.1; the NSG, Vamana and NSSG rows of the table of pruning strategies, section 3.2).
+// For node p the candidates are its neighbours (hops = 1) or those and their neighbours
+// (hops = 2), ordered by (dis(p, c), id) and cut to cand_size; they are taken closest first and
+// p' is inserted iff, for every p* inserted before,
+//   distance rule:  dis(p, p') < alpha dis(p*, p')   (distances are squared here: alpha^2), or
+//   angle rule:     the angle between p -> p* and p -> p' exceeds gamma; with the squared
+//                   lengths a = |p p*|^2, b = |p p'|^2, c = |p* p'|^2 and t = a + b - c that is
+//                   t < 0 or t^2 < 4 cos^2(gamma) a b   (no square root, no division),
+// until d_out are in.
 //
 // One wave per node.  Section 5.2 evaluates a batch of candidates against the neighbour that
 // was inserted last, one batch per insertion.  Here the candidate rows (at most 64) are loaded
@@ -35,7 +39,7 @@ struct FilterArgs {
     const int32_t* ids;
     int32_t k, kp;          // kp: k rounded up to a power of two
     int32_t hops, cand_size;
-    float a2;
+    float thr;              // alpha^2 (distance rule) or 4 cos^2(gamma) (angle rule)
     int32_t d_out;
     int32_t* out_ids;
     int32_t* out_deg;
@@ -124,7 +128,7 @@ __device__ inline void filter_wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS>
+template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS, bool ANGLE>
 __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 {
     extern __shared__ u32 dyn[];         // hops = 2: per wave an id set and a queue of collected ids
@@ -268,9 +272,10 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         occ[lane] = 0u;
         occ[lane + 64] = 0u;
         filter_wave_sync();
-        // occ[C] = the candidates R that would occlude C: not dis(p, C) < alpha^2 dis(R, C).  The lane
-        // holds its column's four rows as a nibble; the mirrored pairs (rows and columns exchanged)
-        // of a tile off the diagonal come out of ballots.
+        // occ[C] = the candidates R that would occlude C: not dis(p, C) < alpha^2 dis(R, C), or an angle
+        // at p of at most gamma (that relation is symmetric in R and C).  The lane holds its column's
+        // four rows as a nibble; the mirrored pairs (rows and columns exchanged) of a tile off the
+        // diagonal come out of ballots.
 #pragma unroll
         for (int i = 0; i < NG; ++i) {
             if (i >= groups) break;
@@ -282,17 +287,29 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 const float nC = nrm[16 * j + r16];
                 const float dC = dp[j];
                 const floatx4 g = acc[i][j];
-                const float rhs0 = A.a2 * ((nR.x + nC) - 2.0f * g.x);
-                const float rhs1 = A.a2 * ((nR.y + nC) - 2.0f * g.y);
-                const float rhs2 = A.a2 * ((nR.z + nC) - 2.0f * g.z);
-                const float rhs3 = A.a2 * ((nR.w + nC) - 2.0f * g.w);
-                const u32 nib = (u32)!(dC < rhs0) | ((u32)!(dC < rhs1) << 1) | ((u32)!(dC < rhs2) << 2) | ((u32)!(dC < rhs3) << 3);
+                const float rc0 = (nR.x + nC) - 2.0f * g.x;        // dis(R, C)
+                const float rc1 = (nR.y + nC) - 2.0f * g.y;
+                const float rc2 = (nR.z + nC) - 2.0f * g.z;
+                const float rc3 = (nR.w + nC) - 2.0f * g.w;
+                bool o0, o1, o2, o3, m0, m1, m2, m3;               // R occludes C; C occludes R
+                if (ANGLE) {
+                    const float t0 = (dR.x + dC) - rc0, t1 = (dR.y + dC) - rc1, t2 = (dR.z + dC) - rc2, t3 = (dR.w + dC) - rc3;
+                    o0 = m0 = !((t0 < 0.0f) | (t0 * t0 < A.thr * (dR.x * dC)));
+                    o1 = m1 = !((t1 < 0.0f) | (t1 * t1 < A.thr * (dR.y * dC)));
+                    o2 = m2 = !((t2 < 0.0f) | (t2 * t2 < A.thr * (dR.z * dC)));
+                    o3 = m3 = !((t3 < 0.0f) | (t3 * t3 < A.thr * (dR.w * dC)));
+                } else {
+                    const float rhs0 = A.thr * rc0, rhs1 = A.thr * rc1, rhs2 = A.thr * rc2, rhs3 = A.thr * rc3;
+                    o0 = !(dC < rhs0); o1 = !(dC < rhs1); o2 = !(dC < rhs2); o3 = !(dC < rhs3);
+                    m0 = !(dR.x < rhs0); m1 = !(dR.y < rhs1); m2 = !(dR.z < rhs2); m3 = !(dR.w < rhs3);
+                }
+                const u32 nib = (u32)o0 | ((u32)o1 << 1) | ((u32)o2 << 2) | ((u32)o3 << 3);
                 atomicOr(occ + 2 * (16 * j + r16) + (i >> 1), nib << (16 * (i & 1) + 4 * q4));
                 if (j > i) {
-                    const u64 b0 = __ballot(!(dR.x < rhs0));
-                    const u64 b1 = __ballot(!(dR.y < rhs1));
-                    const u64 b2 = __ballot(!(dR.z < rhs2));
-                    const u64 b3 = __ballot(!(dR.w < rhs3));
+                    const u64 b0 = __ballot(m0);
+                    const u64 b1 = __ballot(m1);
+                    const u64 b2 = __ballot(m2);
+                    const u64 b3 = __ballot(m3);
                     if (r16 == 0) {
                         const int R = 16 * i + 4 * q4, sh = 16 * q4, word = j >> 1, up = 16 * (j & 1);
                         atomicOr(occ + 2 * (R + 0) + word, (u32)((b0 >> sh) & 0xFFFFull) << up);
@@ -350,35 +367,42 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
     }
 }
 
-template <int NG, bool TWO_HOPS>
+template <int NG, bool TWO_HOPS, bool ANGLE>
 static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, size_t shm, hipStream_t s)
 {
     // two row groups take their columns in chunks of 64, four in chunks of 32: few registers, so that
     // four (three) waves per SIMD cover each other's loads
     constexpr int KS = NG > 2 ? 2 : 4;
     const bool full = vec && (A.d % (16 * KS) == 0);         // no column guards needed
-    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, true, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
-    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, true, TWO_HOPS>), grid, dim3(256), shm, s, A);
-    else hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, false, TWO_HOPS>), grid, dim3(256), shm, s, A);
+    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, true, true, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
+    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, true, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
+    else hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, false, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
 }
 
-void tg_launch_filter_dist(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, float alpha,
-                           int d_out, int32_t* out_ids, int32_t* out_deg, hipStream_t s)
+template <bool ANGLE>
+static void launch_filter_rule(const FilterArgs& A, bool vec, int most, dim3 grid, size_t shm, hipStream_t s)
+{
+    // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
+    if (A.hops == 2) launch_filter<4, true, ANGLE>(A, vec, grid, shm, s);
+    else if (most <= 32) launch_filter<2, false, ANGLE>(A, vec, grid, shm, s);
+    else launch_filter<4, false, ANGLE>(A, vec, grid, shm, s);
+}
+
+void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, bool angle, float thr,
+                      int d_out, int32_t* out_ids, int32_t* out_deg, hipStream_t s)
 {
     FilterArgs A;
     A.X = X; A.n = n; A.d = d; A.ids = ids; A.k = k;
     A.kp = 1;
     while (A.kp < k) A.kp <<= 1;
     A.hops = hops; A.cand_size = cand_size;
-    A.a2 = alpha * alpha;
+    A.thr = thr;
     A.d_out = d_out; A.out_ids = out_ids; A.out_deg = out_deg;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     const int most = hops == 1 ? k : (cand_size < 64 ? cand_size : 64);      // candidates that reach the filter
     int64_t wgs = (n + 3) / 4;
     if (wgs > FILTER_GRID) wgs = FILTER_GRID;
     const size_t shm = hops == 2 ? (size_t)4 * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS) * sizeof(u32) : 0;
-    // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
-    if (hops == 2) launch_filter<4, true>(A, vec, dim3((unsigned)wgs), shm, s);
-    else if (most <= 32) launch_filter<2, false>(A, vec, dim3((unsigned)wgs), shm, s);
-    else launch_filter<4, false>(A, vec, dim3((unsigned)wgs), shm, s);
+    if (angle) launch_filter_rule<true>(A, vec, most, dim3((unsigned)wgs), shm, s);
+    else launch_filter_rule<false>(A, vec, most, dim3((unsigned)wgs), shm, s);
 }

@@ -45,7 +45,7 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_merge_local", "tg_lists_clear",
+           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_merge_local", "tg_lists_clear",
            "tg_last_error"]
 
 _lib = None
@@ -82,6 +82,7 @@ def lib():
         L.tg_merge_local.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, vp, vp]
         L.tg_lists_clear.argtypes = [vp, vp, i64, i32, vp]
         L.tg_prune_dist.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
+        L.tg_prune_angle.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.tg_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -251,8 +252,17 @@ def prune_rank(ids, d_out, want_counts=False):
     return (out, cnt) if want_counts else out
 
 
+def prune_angle(X, ids, d_out, gamma_deg=60.0, hops=1, cand_size=64, want_degrees=False):
+    """tg_prune_angle: NSSG pruning (angles above gamma_deg between kept neighbours) over the 1-hop or 2-hop candidates."""
+    return _prune_filter("tg_prune_angle", X, ids, d_out, gamma_deg, hops, cand_size, want_degrees)
+
+
 def prune_dist(X, ids, d_out, alpha=1.0, hops=1, cand_size=64, want_degrees=False):
     """tg_prune_dist: NSG (alpha = 1) / Vamana (alpha > 1) pruning over the 1-hop or 2-hop candidates."""
+    return _prune_filter("tg_prune_dist", X, ids, d_out, alpha, hops, cand_size, want_degrees)
+
+
+def _prune_filter(entry, X, ids, d_out, thres, hops, cand_size, want_degrees):
     X = _dev_f32(X)
     if not (ids.is_cuda and ids.dtype == torch.int32 and ids.dim() == 2 and ids.is_contiguous()):
         raise ValueError("ids must be a contiguous int32 CUDA tensor of shape (n, k)")
@@ -261,8 +271,8 @@ def prune_dist(X, ids, d_out, alpha=1.0, hops=1, cand_size=64, want_degrees=Fals
         raise ValueError("X and ids disagree on n")
     out = torch.empty((n, d_out), dtype=torch.int32, device=ids.device)
     deg = torch.empty(n, dtype=torch.int32, device=ids.device) if want_degrees else None
-    _check(lib().tg_prune_dist(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, float(alpha), d_out,
-                               out.data_ptr(), deg.data_ptr() if want_degrees else None, _stream_ptr()))
+    _check(getattr(lib(), entry)(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, float(thres), d_out,
+                                 out.data_ptr(), deg.data_ptr() if want_degrees else None, _stream_ptr()))
     return (out, deg) if want_degrees else out
 
 

@@ -71,6 +71,13 @@ def test_c2_full_size():
             distinct = torch.where(pad, -2 - torch.arange(k, device="cuda", dtype=torch.int32)[None, :], out)
             merged = torch.cat([distinct, ids], dim=1).sort(dim=1).values
             assert int((merged[:, 1:] == merged[:, :-1]).sum()) == int(deg.sum())
+    # --- angle-based pruning (NSSG's rule at 60 degrees over the neighbours), the same way
+    out, deg = knn.prune_angle(Xg, ids, k, gamma_deg=60.0, want_degrees=True)
+    want, want_deg, _ = oracle.filter_angle(X, ids_h, 1, 64, 60.0, k, n_do=20000)
+    assert (out[:20000].cpu().numpy() == want).all() and (deg[:20000].cpu().numpy() == want_deg).all()
+    assert int(deg.min()) >= 1 and int(deg.max()) <= k and bool((out[:, 0] == ids[:, 0]).all())
+    pad = out < 0
+    assert bool((pad.sum(dim=1) == k - deg).all()) and bool((pad[:, 1:] >= pad[:, :-1]).all())
 
 
 def test_more_nodes_than_one_launch_can_carry():
