@@ -177,7 +177,11 @@ extern "C" size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_para
 static int begin_span(tg_knn_handle* h, int kind, int round)
 {
     hipEvent_t a, b;
-    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1;
+    if (hipEventCreate(&a) != hipSuccess) return -1;        // no timing for this span; the work goes on
+    if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
+        return -1;
+    }
     h->ev.push_back(a);
     h->ev.push_back(b);
     h->spans.push_back({kind, round, (int)h->ev.size() - 2, (int)h->ev.size() - 1});
