@@ -66,6 +66,8 @@ def lib():
         L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.ofilter_dist.restype = i32
         L.ofilter_dist.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, ctypes.c_float, i32, vp, vp, vp]
+        L.oangle_at.restype = ctypes.c_float
+        L.oangle_at.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_float]
         L.ofilter.restype = i32
         L.ofilter.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.omerge_local.restype = i32
@@ -194,6 +196,36 @@ def filter_angle(X, ids, hops: int, cand_size: int, gamma_deg: float, d_out: int
     if rc != 0:
         raise ValueError("bad arguments")
     return out, deg, margin
+
+
+def filter_dpg(X, ids, hops: int, cand_size: int, d_out: int, n_do=None):
+    """Dispersion pruning (section 3.2, the DPG rule: greedy insertion of the candidate whose angles to the inserted
+    nodes add up to the most) over the 1-hop or 2-hop candidates.  Returns (out_ids in insertion order padded with
+    -1, degrees, margins in radians)."""
+    X = _f32(X)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n, k = ids.shape
+    assert X.shape[0] == n
+    n_do = n if n_do is None else int(n_do)
+    out = np.empty((n_do, d_out), dtype=np.int32)
+    deg = np.empty(n_do, dtype=np.int32)
+    margin = np.empty(n_do, dtype=np.float64)
+    rc = lib().ofilter(X.ctypes.data, n, X.shape[1], ids.ctypes.data, k, n_do, hops, cand_size, 2, 0.0, d_out,
+                       out.ctypes.data, deg.ctypes.data, margin.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return out, deg, margin
+
+
+def angle_at(a, b, c):
+    """The angle (radians, float32) at p between p -> r and p -> c from the squared lengths |p r|^2, |p c|^2, |r c|^2,
+    elementwise, as the dispersion rule computes it."""
+    a, b, c = (np.ascontiguousarray(v, dtype=np.float32).ravel() for v in (a, b, c))
+    out = np.empty(a.shape, dtype=np.float32)
+    f = lib().oangle_at
+    for i in range(a.size):
+        out[i] = f(float(a[i]), float(b[i]), float(c[i]))
+    return out
 
 
 def merge_local(g_ids, g_dist, l_ids, l_dist, l2g):

@@ -21,12 +21,23 @@
  *            p -> p* and p -> p' exceeds gamma.  With a = sq(p, p*), b = sq(p, p'), c = sq(p*, p')
  *            the cosine of that angle is (a + b - c) / (2 sqrt(a b)), so the test is
  *                t < 0  or  t^2 < 4 cos^2(gamma) (a b),   t = a + b - c      (0 < gamma <= 90 degrees).
+ *            Dispersion rule (DPG; section 5.1 reaches it with the angle metric and a threshold of 0): R is
+ *            to make the sum of the pairwise angles at p large, by greedy insertion.  The nearest candidate
+ *            is inserted first; then, until R holds d_out nodes or no candidate is left, the candidate
+ *            whose angles to the nodes in R add up to the most is inserted (equal sums: the nearer one).
+ *            The angle is acos(t / (2 sqrt(a b))) (0 when a b = 0: a node at p's position has no
+ *            direction), with the arc cosine taken from the eight-term polynomial of Abramowitz and
+ *            Stegun 4.4.46, acos(x) = sqrt(1 - x) (a0 + a1 x + ... + a7 x^7) on [0, 1] (|error| <= 2e-8)
+ *            and acos(-x) = pi - acos(x), so that both sides can take every step in the same arithmetic.
  *   Store    R in insertion order, padded with -1.
  *
  * Precision: squared distances are summed in double from the float inputs and then rounded
  * to float; the comparisons above are taken in float, every operation rounded to float in the
  * order written: alpha^2 * sq;  t = (a + b) - c, t * t, c4 * (a * b) with c4 = 4 cos^2(gamma)
  * formed in double and rounded once (a cosine below 1e-12 counts as 0: gamma = 90 degrees).
+ * The dispersion rule takes a b, sqrt, the quotient, 1 - |x|, sqrt, the polynomial (Horner, one fused
+ * multiply-add per coefficient), the product and pi - r in float, each rounded once, and adds a
+ * candidate's angles in the order of insertion.
  * This is the precision the GPU decides in.  On integer-valued data below 2^24 every one of
  * these values is exact.
  *
@@ -57,6 +68,29 @@ static double norm64(int64_t a)
     return s;
 }
 
+/* angle at p between p -> r and p -> c from the squared lengths a = |p r|^2, b = |p c|^2, c = |r c|^2 */
+float oangle_at(float a, float b, float c)
+{
+    const float ab = a * b;
+    if (!(ab > 0.0f)) return 0.0f;
+    const float den = 2.0f * sqrtf(ab);
+    const float t = (a + b) - c;
+    float x = t / den;
+    if (x > 1.0f) x = 1.0f;
+    if (x < -1.0f) x = -1.0f;
+    const float ax = fabsf(x);
+    float pol = -0.0012624911f;
+    pol = fmaf(pol, ax, 0.0066700901f);
+    pol = fmaf(pol, ax, -0.0170881256f);
+    pol = fmaf(pol, ax, 0.0308918810f);
+    pol = fmaf(pol, ax, -0.0501743046f);
+    pol = fmaf(pol, ax, 0.0889789874f);
+    pol = fmaf(pol, ax, -0.2145988016f);
+    pol = fmaf(pol, ax, 1.5707963050f);
+    const float r = sqrtf(1.0f - ax) * pol;
+    return x < 0.0f ? 3.14159265358979323846f - r : r;
+}
+
 typedef struct { float dist; int32_t id; } cand_t;
 
 static int cand_less(const void *pa, const void *pb)
@@ -72,14 +106,18 @@ static int cand_less(const void *pa, const void *pb)
  * the sum of the squared norms of the nodes involved (0 when equal keys were ordered by id).
  * A row whose margin is far above float rounding has one possible result in any arithmetic.
  * Returns 0, or -1 on bad arguments. */
-/* rule 0: distance rule, thres = alpha >= 1.  rule 1: angle rule, thres = gamma in degrees, 0 < gamma <= 90. */
+/* rule 0: distance rule, thres = alpha >= 1.  rule 1: angle rule, thres = gamma in degrees, 0 < gamma <= 90.
+ * rule 2: dispersion rule, thres unused; the margin of its rows is the smallest lead, in radians, of an inserted
+ * candidate's sum over the runner-up's (and the ordering gaps as for the other rules). */
 int ofilter(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t n_do,
             int hops, int cand_size, int rule, float thres, int d_out,
             int32_t *out_ids, int32_t *out_deg, double *out_margin)
 {
     if (!X || !ids || !out_ids || n < 1 || d < 1 || k < 1 || n_do < 0 || n_do > n) return -1;
     if ((hops != 1 && hops != 2) || cand_size < 1 || d_out < 1) return -1;
-    if (rule == 0 ? !(thres >= 1.0f) : (rule != 1 || !(thres > 0.0f && thres <= 90.0f))) return -1;
+    if (rule < 0 || rule > 2) return -1;
+    if (rule == 0 && !(thres >= 1.0f)) return -1;
+    if (rule == 1 && !(thres > 0.0f && thres <= 90.0f)) return -1;
     g_X = X; g_d = d;
     const float a2 = thres * thres;
     double cg = cos((double)thres * 3.14159265358979323846 / 180.0);
@@ -89,6 +127,8 @@ int ofilter(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t
     cand_t *cand = (cand_t *)malloc((size_t)cap * sizeof(cand_t));
     int64_t *stamp = (int64_t *)malloc((size_t)n * sizeof(int64_t));
     int32_t *R = (int32_t *)malloc((size_t)d_out * sizeof(int32_t));
+    float *score = (float *)malloc((size_t)(cand_size > 0 ? cand_size : 1) * sizeof(float));
+    char *in = (char *)malloc((size_t)(cand_size > 0 ? cand_size : 1));
     for (int64_t i = 0; i < n; ++i) stamp[i] = -1;
     for (int64_t p = 0; p < n_do; ++p) {
         /* Collect */
@@ -125,7 +165,27 @@ int ofilter(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t
         }
         /* Filter */
         int deg = 0;
-        for (int64_t i = 0; i < mc && deg < d_out; ++i) {
+        if (rule == 2) {
+            for (int64_t i = 0; i < mc; ++i) { score[i] = 0.0f; in[i] = 0; }
+            int64_t last = -1;
+            while (deg < d_out && deg < mc) {
+                int64_t best = -1, second = -1;
+                for (int64_t i = 0; i < mc; ++i) {
+                    if (in[i]) continue;
+                    if (last >= 0) score[i] += oangle_at(cand[last].dist, cand[i].dist, (float)sq64(cand[last].id, cand[i].id));
+                    if (best < 0 || score[i] > score[best]) { second = best; best = i; }
+                    else if (second < 0 || score[i] > score[second]) second = i;
+                }
+                if (second >= 0 && last >= 0) {
+                    double g = (double)score[best] - (double)score[second];
+                    if (g < margin) margin = g;
+                }
+                in[best] = 1;
+                R[deg++] = cand[best].id;
+                last = best;
+            }
+        }
+        for (int64_t i = 0; rule != 2 && i < mc && deg < d_out; ++i) {
             int32_t c = cand[i].id;
             float lhs = cand[i].dist;
             int keep = 1;
@@ -162,7 +222,7 @@ int ofilter(const float *X, int64_t n, int d, const int32_t *ids, int k, int64_t
         if (out_deg) out_deg[p] = deg;
         if (out_margin) out_margin[p] = margin;
     }
-    free(cand); free(stamp); free(R);
+    free(cand); free(stamp); free(R); free(score); free(in);
     return 0;
 }
 
