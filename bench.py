@@ -213,23 +213,26 @@ def main():
         q_mean = float(((two[:, 1:] != two[:, :-1]).sum(dim=1) + 1).float().mean())     # distinct ids within two hops (self included)
         for name, rule, hops, thres, cands in (("prune_dist_1hop", "alpha", 1, 1.2, float(k)), ("prune_dist_2hop", "alpha", 2, 1.0, q_mean),
                                                ("prune_angle_1hop", "gamma_deg", 1, 60.0, float(k)),
-                                               ("prune_angle_2hop", "gamma_deg", 2, 60.0, q_mean)):      # NSSG's setting in the paper
+                                               ("prune_angle_2hop", "gamma_deg", 2, 60.0, q_mean),       # NSSG's setting in the paper
+                                               ("prune_dispersion_1hop", "d_out", 1, k // 2, float(k))):  # DPG: half of the neighbours
             ms_l = []
             for _ in range(5):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 if rule == "alpha":
                     pd_out = knn.prune_dist(Xg, ids, k, alpha=thres, hops=hops)
-                else:
+                elif rule == "gamma_deg":
                     pd_out = knn.prune_angle(Xg, ids, k, gamma_deg=thres, hops=hops)
+                else:
+                    pd_out = knn.prune_dispersion(Xg, ids, thres, hops=hops)
                 e1.record()
                 torch.cuda.synchronize()
                 ms_l.append(e0.elapsed_time(e1))
             ms_pd = sorted(ms_l)[len(ms_l) // 2]
-            by = n * (4.0 * d * (cands + 1) + 4.0 * k * (1 if hops == 1 else 1 + k) + 4.0 * k)
+            by = n * (4.0 * d * (cands + 1) + 4.0 * k * (1 if hops == 1 else 1 + k) + 4.0 * pd_out.shape[1])
             pd_cases.append((name, rule, hops, thres, pd_out))
             out[name] = {
-                rule: thres, "d_out": k, "mean_degree": float((pd_out >= 0).sum(dim=1).float().mean()), "cand_size": 64, "candidates_per_node": cands, "ms": ms_pd,
+                rule: thres, "d_out": pd_out.shape[1], "mean_degree": float((pd_out >= 0).sum(dim=1).float().mean()), "cand_size": 64, "candidates_per_node": cands, "ms": ms_pd,
                 "points_per_s": n / (ms_pd * 1e-3),
                 "roofline": {"bound": "hbm", "achieved": by / (ms_pd * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": by / (ms_pd * 1e-3) / 1e9 / HBM_PEAK_GBS}}
@@ -292,7 +295,10 @@ def main():
         for name, rule, hops, thres, pd_out in pd_cases:
             n_do = min(n, 20000 if hops == 1 else 3000)
             t0 = time.perf_counter()
-            want, _, _ = (oracle.filter_dist if rule == "alpha" else oracle.filter_angle)(X, ids_h, hops, 64, thres, k, n_do=n_do)
+            if rule == "d_out":
+                want, _, _ = oracle.filter_dpg(X, ids_h, hops, 64, thres, n_do=n_do)
+            else:
+                want, _, _ = (oracle.filter_dist if rule == "alpha" else oracle.filter_angle)(X, ids_h, hops, 64, thres, k, n_do=n_do)
             dt = time.perf_counter() - t0
             out[name]["cpu_baseline"] = {
                 "value": n_do / dt, "unit": "points/s", "cores": 1, "kind": "oracle",

@@ -238,6 +238,35 @@ int tg_prune_angle(const float* X, int64_t n, int32_t d, const int32_t* knn_ids,
                    int32_t* out_ids, int32_t* out_deg, void* stream);
 
 /*
+ * Dispersion pruning of a k-NN graph by the same Collect-Filter-Store procedure with the rule of DPG
+ * (section 3.2: the neighbours of p are to make the sum of their pairwise angles at p large, by
+ * greedy insertion; section 5.1 reaches this rule with the angle metric and a threshold of 0).
+ * Collect and the cut to cand_size are as for tg_prune_dist.  Filter: the nearest candidate is
+ * inserted first; then, until d_out nodes are in or no candidate is left, the candidate whose
+ * angles to the inserted nodes add up to the most is inserted; of equal sums the nearer candidate
+ * (order (dis, id)) wins.  Nothing is dropped while there is room: with d_out >= the number of
+ * candidates the row is a reordering of them.  Store: out_ids in insertion order (not by distance),
+ * then -1; out_deg = min(d_out, candidates).  The angle of a pair is tg_angle_at of the squared
+ * lengths sq(p, r), sq(p, c), sq(r, c); a candidate's angles are added in fp32 in insertion order.
+ * Errors as for tg_prune_dist.
+ */
+int tg_prune_dispersion(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k,
+                        int32_t hops, int32_t cand_size, int32_t d_out,
+                        int32_t* out_ids, int32_t* out_deg, void* stream);
+
+/*
+ * The angle the dispersion rule uses, elementwise on device arrays of `count` values: out[i] is the
+ * angle in radians at p between p -> r and p -> c for the squared lengths a[i] = |p r|^2,
+ * b[i] = |p c|^2, c[i] = |r c|^2, namely acos(x) with x = ((a + b) - c) / (2 sqrt(a b)) clamped to
+ * [-1, 1], and 0 when a b is not positive (a node at p's position has no direction).  The arc cosine
+ * is the eight-term polynomial of Abramowitz and Stegun 4.4.46: acos(x) = sqrt(1 - x) (a0 + a1 x +
+ * ... + a7 x^7) on [0, 1] (|error| <= 2e-8), pi - acos(-x) below 0; every operation is an fp32
+ * operation rounded once (Horner with one fused multiply-add per coefficient), so the result can be
+ * reproduced bit for bit on a host.  count = 0 is allowed.
+ */
+int tg_angle_at(const float* a, const float* b, const float* c, float* out, int64_t count, void* stream);
+
+/*
  * Merge of a local index into the global neighbour lists (section 6.1: a node belongs to several
  * clusters, every cluster gets a local index, and the node's list becomes merge(list so far, its list
  * in the local index)).  g_ids, g_dist: device n x k, updated in place; an unused entry has id -1 and

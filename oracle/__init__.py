@@ -66,8 +66,8 @@ def lib():
         L.oprune_rank.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.ofilter_dist.restype = i32
         L.ofilter_dist.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, ctypes.c_float, i32, vp, vp, vp]
-        L.oangle_at.restype = ctypes.c_float
-        L.oangle_at.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.oangle_at_many.restype = None
+        L.oangle_at_many.argtypes = [vp, vp, vp, vp, i64]
         L.ofilter.restype = i32
         L.ofilter.argtypes = [vp, i64, i32, vp, i32, i64, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.omerge_local.restype = i32
@@ -221,10 +221,9 @@ def angle_at(a, b, c):
     """The angle (radians, float32) at p between p -> r and p -> c from the squared lengths |p r|^2, |p c|^2, |r c|^2,
     elementwise, as the dispersion rule computes it."""
     a, b, c = (np.ascontiguousarray(v, dtype=np.float32).ravel() for v in (a, b, c))
+    assert a.size == b.size == c.size
     out = np.empty(a.shape, dtype=np.float32)
-    f = lib().oangle_at
-    for i in range(a.size):
-        out[i] = f(float(a[i]), float(b[i]), float(c[i]))
+    lib().oangle_at_many(a.ctypes.data, b.ctypes.data, c.ctypes.data, out.ctypes.data, a.size)
     return out
 
 

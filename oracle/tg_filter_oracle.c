@@ -91,6 +91,11 @@ float oangle_at(float a, float b, float c)
     return x < 0.0f ? 3.14159265358979323846f - r : r;
 }
 
+void oangle_at_many(const float *a, const float *b, const float *c, float *out, int64_t count)
+{
+    for (int64_t i = 0; i < count; ++i) out[i] = oangle_at(a[i], b[i], c[i]);
+}
+
 typedef struct { float dist; int32_t id; } cand_t;
 
 static int cand_less(const void *pa, const void *pb)

@@ -615,7 +615,7 @@ extern "C" int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t
     const int rc = check_filter(X, n, d, knn_ids, k, hops, cand_size, d_out, out_ids);
     if (rc != TG_OK) return rc;
     if (!(alpha >= 1.0f) || !(alpha <= 1e6f)) return fail(TG_ERR_INVALID_ARG, "alpha must be in [1, 1e6]");
-    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, false, alpha * alpha, d_out, out_ids, out_deg,
+    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, 0, alpha * alpha, d_out, out_ids, out_deg,
                      reinterpret_cast<hipStream_t>(stream));
     return launch_status("distance-based pruning");
 }
@@ -629,9 +629,27 @@ extern "C" int tg_prune_angle(const float* X, int64_t n, int32_t d, const int32_
     // 4 cos^2(gamma), formed in double and rounded once; the cosine of 90 degrees is taken as 0
     double cg = cos((double)gamma_deg * 3.14159265358979323846 / 180.0);
     if (fabs(cg) < 1e-12) cg = 0.0;
-    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, true, (float)(4.0 * cg * cg), d_out, out_ids, out_deg,
+    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, 1, (float)(4.0 * cg * cg), d_out, out_ids, out_deg,
                      reinterpret_cast<hipStream_t>(stream));
     return launch_status("angle-based pruning");
+}
+
+extern "C" int tg_prune_dispersion(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k, int32_t hops,
+                                   int32_t cand_size, int32_t d_out, int32_t* out_ids, int32_t* out_deg, void* stream)
+{
+    const int rc = check_filter(X, n, d, knn_ids, k, hops, cand_size, d_out, out_ids);
+    if (rc != TG_OK) return rc;
+    tg_launch_filter(X, n, d, knn_ids, k, hops, cand_size, 2, 0.0f, d_out, out_ids, out_deg, reinterpret_cast<hipStream_t>(stream));
+    return launch_status("dispersion pruning");
+}
+
+extern "C" int tg_angle_at(const float* a, const float* b, const float* c, float* out, int64_t count, void* stream)
+{
+    if (count < 0 || count >= (1ll << 31)) return fail(TG_ERR_INVALID_ARG, "count = %lld outside 0..2^31-1", (long long)count);
+    if (count == 0) return TG_OK;
+    if (!a || !b || !c || !out) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    tg_launch_angle_at(a, b, c, out, count, reinterpret_cast<hipStream_t>(stream));
+    return launch_status("angles");
 }
 
 extern "C" int tg_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int32_t k, const int32_t* l_ids, const float* l_dist,

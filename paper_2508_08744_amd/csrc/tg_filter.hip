@@ -7,7 +7,9 @@
 //   angle rule:     the angle between p -> p* and p -> p' exceeds gamma; with the squared
 //                   lengths a = |p p*|^2, b = |p p'|^2, c = |p* p'|^2 and t = a + b - c that is
 //                   t < 0 or t^2 < 4 cos^2(gamma) a b   (no square root, no division),
-// until d_out are in.
+// until d_out are in.  The dispersion rule (DPG) has no threshold: the nearest candidate is
+// inserted first, then again and again the candidate whose angles at p to the inserted nodes add
+// up to the most (equal sums: the nearer one), until d_out are in or none is left.
 //
 // One wave per node.  Section 5.2 evaluates a batch of candidates against the neighbour that
 // was inserted last, one batch per insertion.  Here the candidate rows (at most 64) are loaded
@@ -122,16 +124,81 @@ __device__ inline bool filter_set_insert(u32* tab, u32 id, bool active)
     return present;
 }
 
+// Angle at p between p -> r and p -> c from the squared lengths a = |p r|^2, b = |p c|^2, c = |r c|^2:
+// acos((a + b - c) / (2 sqrt(a b))), the arc cosine from the eight-term polynomial of Abramowitz and
+// Stegun 4.4.46 (acos x = sqrt(1 - x) (a0 + .. + a7 x^7) on [0, 1], pi - acos(-x) below 0).  Every
+// operation is rounded once, in this order, so that a host program can follow it bit for bit.
+// A node at p's position (a b = 0) has no direction: angle 0.
+__device__ inline float filter_angle_at(float a, float b, float c)
+{
+#pragma clang fp contract(off)
+    const float ab = a * b;
+    const float den = 2.0f * sqrtf(ab);
+    const float t = (a + b) - c;
+    float x = t / den;
+    x = x > 1.0f ? 1.0f : x;
+    x = x < -1.0f ? -1.0f : x;
+    const float ax = fabsf(x);
+    float pol = -0.0012624911f;
+    pol = fmaf(pol, ax, 0.0066700901f);
+    pol = fmaf(pol, ax, -0.0170881256f);
+    pol = fmaf(pol, ax, 0.0308918810f);
+    pol = fmaf(pol, ax, -0.0501743046f);
+    pol = fmaf(pol, ax, 0.0889789874f);
+    pol = fmaf(pol, ax, -0.2145988016f);
+    pol = fmaf(pol, ax, 1.5707963050f);
+    const float r = sqrtf(1.0f - ax) * pol;
+    const float th = x < 0.0f ? 3.14159265358979323846f - r : r;
+    return ab > 0.0f ? th : 0.0f;
+}
+
+__global__ void angle_at_kernel(const float* a, const float* b, const float* c, float* out, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = filter_angle_at(a[i], b[i], c[i]);
+}
+void tg_launch_angle_at(const float* a, const float* b, const float* c, float* out, int64_t count, hipStream_t s)
+{
+    hipLaunchKernelGGL(angle_at_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, a, b, c, out, count);
+}
+
+// maximum over the wave: xor butterfly by DPP inside each row of 16 lanes, then the four rows meet in scalar registers
+__device__ inline u32 filter_wave_max(u32 x)
+{
+    x = max(x, tg_partner32<1>(x));
+    x = max(x, tg_partner32<2>(x));
+    x = max(x, tg_partner32<7>(x));
+    x = max(x, tg_partner32<15>(x));
+    const u32 r0 = (u32)__builtin_amdgcn_readlane((int)x, 0), r1 = (u32)__builtin_amdgcn_readlane((int)x, 16);
+    const u32 r2 = (u32)__builtin_amdgcn_readlane((int)x, 32), r3 = (u32)__builtin_amdgcn_readlane((int)x, 48);
+    return max(max(r0, r1), max(r2, r3));
+}
+
 __device__ inline void filter_wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS, bool ANGLE>
+#define FILTER_RULE_DIST 0
+#define FILTER_RULE_ANGLE 1
+#define FILTER_RULE_DISPERSION 2
+// words of dynamic LDS per wave: the id set and queue of the 2-hop collection, and, later in the same
+// words, the matrix of angles of the dispersion rule (rows of 16 NG + 1 words)
+__host__ __device__ constexpr int filter_dyn_words(int ng, bool two_hops, int rule)
+{
+    const int collect = two_hops ? FILTER_SET_WORDS + FILTER_QUEUE_WORDS : 0;
+    const int angles = rule == FILTER_RULE_DISPERSION ? 16 * ng * (16 * ng + 1) : 0;
+    return collect > angles ? collect : angles;
+}
+
+template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS, int RULE>
 __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 {
-    extern __shared__ u32 dyn[];         // hops = 2: per wave an id set and a queue of collected ids
+    constexpr bool ANGLE = RULE == FILTER_RULE_ANGLE;
+    constexpr int DYN = filter_dyn_words(NG, TWO_HOPS, RULE);
+    constexpr int AS = 16 * NG + 1;      // row stride of the matrix of angles
+    extern __shared__ u32 dyn[];         // per wave: see filter_dyn_words
     __shared__ int s_cid[4][64];
     __shared__ __align__(16) float s_dpc[4][64];
     __shared__ __align__(16) float s_nrm[4][64];
@@ -177,7 +244,7 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
             cid[lane] = u_ok ? u : (int)p;
             filter_wave_sync();
         } else {
-            u32* set = dyn + wave * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS);
+            u32* set = dyn + wave * DYN;
             int* queue = reinterpret_cast<int*>(set + FILTER_SET_WORDS);
             for (int i = lane; i < FILTER_SET_WORDS; i += 64) set[i] = FILTER_FREE;
             filter_wave_sync();
@@ -291,6 +358,18 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 const float rc1 = (nR.y + nC) - 2.0f * g.y;
                 const float rc2 = (nR.z + nC) - 2.0f * g.z;
                 const float rc3 = (nR.w + nC) - 2.0f * g.w;
+                if (RULE == FILTER_RULE_DISPERSION) {
+                    // the angle of every pair, stored both ways round (row R, column C and the reverse)
+                    float* ang = reinterpret_cast<float*>(dyn + wave * DYN);
+                    const int R = 16 * i + 4 * q4, C = 16 * j + r16;
+                    const float th0 = filter_angle_at(dR.x, dC, rc0), th1 = filter_angle_at(dR.y, dC, rc1);
+                    const float th2 = filter_angle_at(dR.z, dC, rc2), th3 = filter_angle_at(dR.w, dC, rc3);
+                    ang[(R + 0) * AS + C] = th0; ang[(R + 1) * AS + C] = th1;
+                    ang[(R + 2) * AS + C] = th2; ang[(R + 3) * AS + C] = th3;
+                    ang[C * AS + R + 0] = th0; ang[C * AS + R + 1] = th1;
+                    ang[C * AS + R + 2] = th2; ang[C * AS + R + 3] = th3;
+                    continue;
+                }
                 bool o0, o1, o2, o3, m0, m1, m2, m3;               // R occludes C; C occludes R
                 if (ANGLE) {
                     const float t0 = (dR.x + dC) - rc0, t1 = (dR.y + dC) - rc1, t2 = (dR.z + dC) - rc2, t3 = (dR.w + dC) - rc3;
@@ -350,6 +429,33 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
         // inserted", every pass settles at least the next candidate in order, so the set stops
         // changing after at most m passes, and what it then holds obeys the rule.
         const bool in_cut = !dead && __popcll(before) < A.cand_size;       // the cut to cand_size counts candidates only
+        if (RULE == FILTER_RULE_DISPERSION) {
+            // ---- greedy insertion: one candidate per pass ----
+            const float* ang = reinterpret_cast<const float*>(dyn + wave * DYN);
+            const int want = min(A.d_out, __popcll(__ballot(in_cut)));
+            const u32 rnk = (u32)__popcll(before);                  // place among the candidates, nearest first
+            float score = 0.0f;                                     // sum of the angles to the inserted nodes
+            bool open = in_cut;
+            int my_pos = -1;
+            u64 pick = __ballot(in_cut && rnk == 0u);               // the nearest candidate goes first
+            for (int it = 0; it < want && pick != 0ull; ++it) {
+                const int r_new = __ffsll((unsigned long long)pick) - 1;
+                if (lane == r_new) { my_pos = it; open = false; }
+                if (it + 1 >= want) break;
+                score += lane < 16 * NG ? ang[r_new * AS + lane] : 0.0f;
+                // sums are no less than +0, so their bit patterns order them; + 1 puts every open lane above the rest
+                const u32 sb = open ? __float_as_uint(score) + 1u : 0u;
+                const u32 top = filter_wave_max(sb);
+                const bool first = open && sb == top;
+                const u32 near = 64u - filter_wave_max(first ? 64u - rnk : 0u);
+                pick = __ballot(first && rnk == near);
+            }
+            if (my_pos >= 0) A.out_ids[p * A.d_out + my_pos] = my_id;
+            if (lane >= want && lane < A.d_out) A.out_ids[p * A.d_out + lane] = -1;
+            if (A.out_deg && lane == 0) A.out_deg[p] = want;
+            filter_wave_sync();
+            continue;
+        }
         u64 K = __ballot(in_cut);
         for (int pass = 0; pass < 65; ++pass) {
             const u64 Kn = __ballot(in_cut && (occ_by & K) == 0ull);
@@ -367,28 +473,37 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
     }
 }
 
-template <int NG, bool TWO_HOPS, bool ANGLE>
-static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, size_t shm, hipStream_t s)
+template <class K>
+static void filter_launch(K kernel, const FilterArgs& A, dim3 grid, size_t shm, hipStream_t s)
 {
+    // more than 64 KB of dynamic LDS has to be asked for
+    if (shm > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+    hipLaunchKernelGGL(kernel, grid, dim3(256), shm, s, A);
+}
+
+template <int NG, bool TWO_HOPS, int RULE>
+static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, hipStream_t s)
+{
+    const size_t shm = (size_t)4 * filter_dyn_words(NG, TWO_HOPS, RULE) * sizeof(u32);
     // two row groups take their columns in chunks of 64, four in chunks of 32: few registers, so that
     // four (three) waves per SIMD cover each other's loads
     constexpr int KS = NG > 2 ? 2 : 4;
     const bool full = vec && (A.d % (16 * KS) == 0);         // no column guards needed
-    if (full) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, true, true, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
-    else if (vec) hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, true, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
-    else hipLaunchKernelGGL((filter_dist_kernel<NG, KS, false, false, TWO_HOPS, ANGLE>), grid, dim3(256), shm, s, A);
+    if (full) filter_launch(filter_dist_kernel<NG, KS, true, true, TWO_HOPS, RULE>, A, grid, shm, s);
+    else if (vec) filter_launch(filter_dist_kernel<NG, KS, false, true, TWO_HOPS, RULE>, A, grid, shm, s);
+    else filter_launch(filter_dist_kernel<NG, KS, false, false, TWO_HOPS, RULE>, A, grid, shm, s);
 }
 
-template <bool ANGLE>
-static void launch_filter_rule(const FilterArgs& A, bool vec, int most, dim3 grid, size_t shm, hipStream_t s)
+template <int RULE>
+static void launch_filter_rule(const FilterArgs& A, bool vec, int most, dim3 grid, hipStream_t s)
 {
     // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
-    if (A.hops == 2) launch_filter<4, true, ANGLE>(A, vec, grid, shm, s);
-    else if (most <= 32) launch_filter<2, false, ANGLE>(A, vec, grid, shm, s);
-    else launch_filter<4, false, ANGLE>(A, vec, grid, shm, s);
+    if (A.hops == 2) launch_filter<4, true, RULE>(A, vec, grid, s);
+    else if (most <= 32) launch_filter<2, false, RULE>(A, vec, grid, s);
+    else launch_filter<4, false, RULE>(A, vec, grid, s);
 }
 
-void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, bool angle, float thr,
+void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, int rule, float thr,
                       int d_out, int32_t* out_ids, int32_t* out_deg, hipStream_t s)
 {
     FilterArgs A;
@@ -402,7 +517,7 @@ void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int 
     const int most = hops == 1 ? k : (cand_size < 64 ? cand_size : 64);      // candidates that reach the filter
     int64_t wgs = (n + 3) / 4;
     if (wgs > FILTER_GRID) wgs = FILTER_GRID;
-    const size_t shm = hops == 2 ? (size_t)4 * (FILTER_SET_WORDS + FILTER_QUEUE_WORDS) * sizeof(u32) : 0;
-    if (angle) launch_filter_rule<true>(A, vec, most, dim3((unsigned)wgs), shm, s);
-    else launch_filter_rule<false>(A, vec, most, dim3((unsigned)wgs), shm, s);
+    if (rule == FILTER_RULE_DISPERSION) launch_filter_rule<FILTER_RULE_DISPERSION>(A, vec, most, dim3((unsigned)wgs), s);
+    else if (rule == FILTER_RULE_ANGLE) launch_filter_rule<FILTER_RULE_ANGLE>(A, vec, most, dim3((unsigned)wgs), s);
+    else launch_filter_rule<FILTER_RULE_DIST>(A, vec, most, dim3((unsigned)wgs), s);
 }

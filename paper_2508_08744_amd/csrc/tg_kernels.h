@@ -88,8 +88,9 @@ void tg_launch_exact_knn(const float* X, int ld, const float* nrm, const float* 
 size_t tg_scan_tmp_elems(int64_t n);
 void tg_launch_prune_rank(const int32_t* ids, int64_t n, int k, int d_out, int32_t* out_ids, int32_t* counts /* or null */,
                           hipStream_t s);
-// thr: alpha^2 for the distance rule, 4 cos^2(gamma) for the angle rule
-void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, bool angle, float thr,
+// rule 0: distance rule, thr = alpha^2; 1: angle rule, thr = 4 cos^2(gamma); 2: dispersion rule, thr unused
+void tg_launch_angle_at(const float* a, const float* b, const float* c, float* out, int64_t count, hipStream_t s);
+void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, int rule, float thr,
                            int d_out, int32_t* out_ids, int32_t* out_deg /* or null */, hipStream_t s);
 void tg_launch_merge_local(int32_t* g_ids, float* g_dist, int64_t n, int k, const int32_t* l_ids, const float* l_dist,
                            int64_t n_local, int k_local, const int32_t* l2g, hipStream_t s);

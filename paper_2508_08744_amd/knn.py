@@ -45,7 +45,7 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_merge_local", "tg_lists_clear",
+           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_prune_dispersion", "tg_angle_at", "tg_merge_local", "tg_lists_clear",
            "tg_last_error"]
 
 _lib = None
@@ -83,6 +83,8 @@ def lib():
         L.tg_lists_clear.argtypes = [vp, vp, i64, i32, vp]
         L.tg_prune_dist.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
         L.tg_prune_angle.argtypes = [vp, i64, i32, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp, vp]
+        L.tg_prune_dispersion.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, vp, vp]
+        L.tg_angle_at.argtypes = [vp, vp, vp, vp, i64, vp]
         L.tg_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -262,6 +264,23 @@ def prune_dist(X, ids, d_out, alpha=1.0, hops=1, cand_size=64, want_degrees=Fals
     return _prune_filter("tg_prune_dist", X, ids, d_out, alpha, hops, cand_size, want_degrees)
 
 
+def prune_dispersion(X, ids, d_out, hops=1, cand_size=64, want_degrees=False):
+    """tg_prune_dispersion: DPG pruning (greedy choice of the neighbours whose angles at the node add up to the most)."""
+    return _prune_filter("tg_prune_dispersion", X, ids, d_out, None, hops, cand_size, want_degrees)
+
+
+def angle_at(a, b, c):
+    """tg_angle_at: the angle (radians) between two directions from squared lengths, elementwise."""
+    for v in (a, b, c):
+        if not (isinstance(v, torch.Tensor) and v.is_cuda and v.dtype == torch.float32 and v.dim() == 1 and v.is_contiguous()):
+            raise TypeError("a, b, c must be contiguous 1-D float32 CUDA tensors")
+    if not (a.numel() == b.numel() == c.numel()):
+        raise ValueError("a, b, c must have the same number of elements")
+    out = torch.empty_like(a)
+    _check(lib().tg_angle_at(a.data_ptr(), b.data_ptr(), c.data_ptr(), out.data_ptr(), a.numel(), _stream_ptr()))
+    return out
+
+
 def _prune_filter(entry, X, ids, d_out, thres, hops, cand_size, want_degrees):
     X = _dev_f32(X)
     if not (ids.is_cuda and ids.dtype == torch.int32 and ids.dim() == 2 and ids.is_contiguous()):
@@ -271,7 +290,8 @@ def _prune_filter(entry, X, ids, d_out, thres, hops, cand_size, want_degrees):
         raise ValueError("X and ids disagree on n")
     out = torch.empty((n, d_out), dtype=torch.int32, device=ids.device)
     deg = torch.empty(n, dtype=torch.int32, device=ids.device) if want_degrees else None
-    _check(getattr(lib(), entry)(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, float(thres), d_out,
+    rule = () if thres is None else (float(thres),)
+    _check(getattr(lib(), entry)(X.data_ptr(), n, X.shape[1], ids.data_ptr(), k, hops, cand_size, *rule, d_out,
                                  out.data_ptr(), deg.data_ptr() if want_degrees else None, _stream_ptr()))
     return (out, deg) if want_degrees else out
 

@@ -86,6 +86,15 @@ def test_invalid_arguments_are_rejected_on_the_host():
         n, d, k, hops, cs, gamma, d_out = a
         assert lib.tg_prune_angle(fake, n, d, fake, k, hops, cs, gamma, d_out, fake, None, None) == want, a
     assert lib.tg_prune_angle(fake, 100, 8, None, 16, 1, 64, 60.0, 8, fake, None, None) == -1
+    for a, want in [((100, 8, 16, 1, 64, 0), -1), ((100, 8, 16, 1, 64, 65), -1), ((100, 8, 16, 0, 64, 8), -1),
+                    ((100, 8, 16, 1, 0, 8), -1), ((100, 8, 65, 1, 64, 8), -1), ((100, 4097, 16, 1, 64, 8), -1),
+                    ((100, 8, 40, 2, 64, 8), -2)]:
+        n, d, k, hops, cs, d_out = a
+        assert lib.tg_prune_dispersion(fake, n, d, fake, k, hops, cs, d_out, fake, None, None) == want, a
+    assert lib.tg_prune_dispersion(fake, 100, 8, fake, 16, 1, 64, 8, None, None, None) == -1
+    assert lib.tg_angle_at(fake, fake, fake, fake, -1, None) == -1
+    assert lib.tg_angle_at(fake, None, fake, fake, 5, None) == -1
+    assert lib.tg_angle_at(None, None, None, None, 0, None) == 0
     assert lib.tg_prune_rank(fake, 100, 16, 17, fake, None, None) == -1
 
 

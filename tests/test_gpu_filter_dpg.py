@@ -1,0 +1,159 @@
+"""Dispersion pruning (the DPG rule of section 3.2 in the Collect-Filter-Store procedure of section 5.1)
+on the GPU against the oracle.
+
+The angle of a pair is a fixed sequence of fp32 operations, each rounded once (products, sums, a
+quotient, two square roots, a polynomial with fused multiply-adds), which the oracle follows step by
+step: tg_angle_at must agree with it bit for bit on any input.  On integer-valued data whose squared
+norms stay below 2^23 the squared lengths that go into it are exact on both sides, so the rows must
+agree bit for bit as well.  On real-valued data a row may differ only where the oracle reports a
+decision within fp32 rounding of a tie."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2508_08744_amd import inputs, knn
+
+pytestmark = pytest.mark.gpu
+
+
+def _integer_points(n, d, comps=12, shrink=1):
+    X = inputs.make("C2", n=n, d=d, comps=comps)
+    return np.floor(X / shrink).astype(np.float32)
+
+
+def _exact(X, ids, d_out, hops, cand_size):
+    want, want_deg, _ = oracle.filter_dpg(X, ids, hops, cand_size, d_out)
+    out, deg = knn.prune_dispersion(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), d_out, hops=hops,
+                                    cand_size=cand_size, want_degrees=True)
+    out, deg = out.cpu().numpy(), deg.cpu().numpy()
+    bad = np.nonzero((out != want).any(axis=1))[0]
+    assert bad.size == 0, (bad[:5], out[bad[:2]], want[bad[:2]])
+    assert (deg == want_deg).all()
+    return want, want_deg
+
+
+def test_angle_bit_for_bit():
+    rng = np.random.default_rng(31)
+    n = 2_000_000
+    # squared lengths of integer triangles (the values the pruning sees on byte-valued data), real-valued ones
+    # over many orders of magnitude, and the special cases: a zero length, degenerate triangles, ratios past +-1
+    a = rng.integers(0, 1 << 22, n).astype(np.float32)
+    b = rng.integers(0, 1 << 22, n).astype(np.float32)
+    lo, hi = (np.sqrt(a) - np.sqrt(b)) ** 2, (np.sqrt(a) + np.sqrt(b)) ** 2
+    c = np.floor(lo + (hi - lo) * rng.random(n)).astype(np.float32)
+    a2 = np.exp(rng.uniform(-30, 30, n)).astype(np.float32)
+    b2 = (a2 * np.exp(rng.uniform(-8, 8, n))).astype(np.float32)
+    c2 = ((np.sqrt(a2) - np.sqrt(b2)) ** 2 + 4 * np.sqrt(a2 * b2) * rng.random(n)).astype(np.float32)
+    sa = np.array([0, 4, 4, 4, 4, 1, 1, 1e-30, 3e38, 1], dtype=np.float32)
+    sb = np.array([9, 0, 9, 9, 9, 1, 1, 1e-30, 3e38, 1], dtype=np.float32)
+    sc = np.array([9, 4, 1, 25, 13, 0, 5, 1e-30, 1, 1], dtype=np.float32)
+    A, B, C = np.concatenate([a, a2, sa]), np.concatenate([b, b2, sb]), np.concatenate([c, c2, sc])
+    want = oracle.angle_at(A, B, C)
+    got = knn.angle_at(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.from_numpy(C).cuda()).cpu().numpy()
+    same = (got.view(np.uint32) == want.view(np.uint32)) | (np.isnan(got) & np.isnan(want))
+    assert same.all(), (np.nonzero(~same)[0][:5], A[~same][:5], B[~same][:5], C[~same][:5], got[~same][:5], want[~same][:5])
+    assert (want[:n] >= 0).all() and (want[:n] <= np.float32(np.pi)).all()
+
+
+@pytest.mark.parametrize("n,d,k,d_out,cand_size", [
+    (3000, 128, 32, 16, 64),        # the headline shape: half of the neighbours stay
+    (3000, 128, 32, 32, 64),        # room for all: a reordering
+    (2000, 128, 64, 32, 64),        # four row groups
+    (2000, 128, 48, 40, 40),        # cand_size cuts the candidates
+    (1500, 64, 24, 8, 64),
+    (1200, 96, 32, 16, 64),
+    (900, 100, 17, 9, 64),
+    (700, 30, 9, 4, 64),            # rows that are not 16-byte aligned
+    (600, 3, 5, 5, 64),             # few dimensions: many equal sums
+    (300, 1, 2, 2, 64),             # a line: angles 0 and pi only
+    (300, 1, 1, 1, 1),
+])
+def test_one_hop_bit_exact_on_integer_data(n, d, k, d_out, cand_size):
+    X = _integer_points(n, d)
+    ids, _ = oracle.brute_force_knn(X, k)
+    _exact(X, ids, d_out, 1, cand_size)
+
+
+@pytest.mark.parametrize("n,d,k,d_out,cand_size", [
+    (2500, 128, 32, 32, 64),
+    (2000, 128, 16, 24, 64),
+    (1500, 64, 20, 20, 33),
+    (800, 30, 7, 12, 64),
+    (500, 8, 3, 6, 5),
+])
+def test_two_hops_bit_exact_on_integer_data(n, d, k, d_out, cand_size):
+    X = _integer_points(n, d)
+    ids, _ = oracle.brute_force_knn(X, k)
+    _exact(X, ids, d_out, 2, cand_size)
+
+
+@pytest.mark.parametrize("d,hops", [(960, 1), (300, 2)])
+def test_several_chunks_of_columns(d, hops):
+    X = _integer_points(1000, d, shrink=8)
+    ids, _ = oracle.brute_force_knn(X, 32 if hops == 1 else 12)
+    _exact(X, ids, 16, hops, 64)
+
+
+def test_graph_from_the_builder():
+    X = inputs.make("C2", n=20000, d=128, comps=20)
+    Xg = torch.from_numpy(X).cuda()
+    ids, _ = knn.knn_build(Xg, 32, "l2", iters=8, seed=1)
+    ids = ids.cpu().numpy()
+    want, deg = _exact(X, ids, 16, 1, 64)
+    assert (deg == 16).all() and (want[:, 0] == ids[:, 0]).all()          # nothing is dropped while there is room
+    full, _ = _exact(X, ids, 32, 1, 64)
+    assert (np.sort(full, axis=1) == np.sort(ids, axis=1)).all() and (full[:, :16] == want).all()
+    # what the rule is for: the kept half is spread wider than the nearest half (sum of pairwise angles, numpy)
+    def dispersion(p, members):
+        V = X[members].astype(np.float64) - X[p].astype(np.float64)
+        V /= np.linalg.norm(V, axis=1, keepdims=True)
+        return np.arccos(np.clip(V @ V.T, -1, 1))[np.triu_indices(len(members), 1)].sum()
+    gain = [dispersion(p, want[p]) - dispersion(p, ids[p, :16]) for p in range(0, 20000, 100)]
+    assert np.mean(gain) > 0 and np.mean(np.array(gain) > 0) > 0.9
+    _exact(X[:6000], ids[:6000] % 6000, 24, 2, 64)
+
+
+def test_padding_duplicates_self_and_small_candidate_sets():
+    rng = np.random.default_rng(5)
+    n, k, d = 800, 16, 40
+    X = _integer_points(n, d)
+    X[1::7] = X[0::7][: len(X[1::7])]                                       # twins: also candidates at p's own position
+    ids = np.stack([rng.permutation(n)[:k] for _ in range(n)]).astype(np.int32)
+    ids[rng.integers(0, n, 300), rng.integers(0, k, 300)] = -1
+    ids[rng.integers(0, n, 100), rng.integers(0, k, 100)] = n + 7
+    rows = rng.integers(0, n, 100)
+    ids[rows, 5] = ids[rows, 2]
+    ids[:50, 3] = np.arange(50)
+    ids[0:700:7, 0] = np.arange(1, 701, 7)                                  # every such p lists its twin
+    ids[60:70] = -1
+    for hops in (1, 2):
+        for d_out in (1, 7, 20):
+            want, deg = _exact(X, ids, d_out, hops, 64)
+            assert (want[60:70] == -1).all() and (deg[60:70] == 0).all()
+
+
+@pytest.mark.parametrize("config,n,d,k,hops", [("C1", 4000, 32, 16, 1), ("C1", 3000, 32, 16, 2), ("C4", 3000, 96, 32, 1),
+                                               ("C3", 1500, 960, 32, 1)])
+def test_real_valued_data_differs_only_where_a_decision_was_a_near_tie(config, n, d, k, hops):
+    X = inputs.make(config, n=n, d=d, comps=10)
+    ids, _ = oracle.brute_force_knn(X, k)
+    want, want_deg, margin = oracle.filter_dpg(X, ids, hops, 64, 12)
+    out = knn.prune_dispersion(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), 12, hops=hops).cpu().numpy()
+    differ = (out != want).any(axis=1)
+    # the squared lengths carry about (d + 8) 2^-24 of the norms; an angle moves by that over its sine, a sum of
+    # up to eleven of them by a few times more: leads below this many radians may go the other way
+    tol = 64.0 * (d + 8) * 2.0 ** -24
+    assert (margin[differ] < tol).all(), (np.nonzero(differ)[0][:5], margin[differ][:5], tol)
+    assert differ.mean() < 0.03, differ.mean()
+
+
+def test_bad_arguments():
+    X = torch.zeros((100, 8), device="cuda")
+    ids = torch.zeros((100, 40), dtype=torch.int32, device="cuda")
+    for kw in (dict(d_out=0), dict(d_out=65), dict(d_out=4, hops=3), dict(d_out=4, cand_size=0),
+               dict(d_out=4, cand_size=65), dict(d_out=4, hops=2)):
+        with pytest.raises(knn.TagoreError):
+            knn.prune_dispersion(X, ids, **kw)
+    e = torch.zeros(0, device="cuda")
+    assert knn.angle_at(e, e, e).numel() == 0

@@ -71,6 +71,13 @@ def test_c2_full_size():
             distinct = torch.where(pad, -2 - torch.arange(k, device="cuda", dtype=torch.int32)[None, :], out)
             merged = torch.cat([distinct, ids], dim=1).sort(dim=1).values
             assert int((merged[:, 1:] == merged[:, :-1]).sum()) == int(deg.sum())
+    # --- dispersion pruning (DPG's rule: half of the neighbours stay), the same way
+    out, deg = knn.prune_dispersion(Xg, ids, k // 2, want_degrees=True)
+    want, want_deg, _ = oracle.filter_dpg(X, ids_h, 1, 64, k // 2, n_do=20000)
+    assert (out[:20000].cpu().numpy() == want).all() and (deg[:20000].cpu().numpy() == want_deg).all()
+    assert bool((deg == k // 2).all()) and bool((out[:, 0] == ids[:, 0]).all())
+    merged = torch.cat([out, ids], dim=1).sort(dim=1).values          # kept ids come from the row, none twice
+    assert int((merged[:, 1:] == merged[:, :-1]).sum()) == n * (k // 2)
     # --- angle-based pruning (NSSG's rule at 60 degrees over the neighbours), the same way
     out, deg = knn.prune_angle(Xg, ids, k, gamma_deg=60.0, want_degrees=True)
     want, want_deg, _ = oracle.filter_angle(X, ids_h, 1, 64, 60.0, k, n_do=20000)

@@ -60,6 +60,25 @@ def test_angle_pruning_random_cases():
         assert (deg.cpu().numpy() == want_deg).all(), where
 
 
+def test_dispersion_pruning_random_cases():
+    rng = np.random.default_rng(2028)
+    for case in range(60):
+        n = int(rng.integers(2, 300))
+        d = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 33, 64, 100, 128, 129, 200]))
+        hops = int(rng.integers(1, 3))
+        k = int(rng.integers(1, 33 if hops == 2 else 65))
+        cand_size = int(rng.integers(1, 65))
+        d_out = int(rng.integers(1, 65))
+        X = rng.integers(0, 40, size=(n, d)).astype(np.float32)           # exact in fp32, many equal sums and twins
+        ids = _graph(rng, n, k)
+        want, want_deg, _ = oracle.filter_dpg(X, ids, hops, cand_size, d_out)
+        out, deg = knn.prune_dispersion(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), d_out, hops=hops,
+                                        cand_size=cand_size, want_degrees=True)
+        where = dict(case=case, n=n, d=d, k=k, hops=hops, cand_size=cand_size, d_out=d_out)
+        assert (out.cpu().numpy() == want).all(), where
+        assert (deg.cpu().numpy() == want_deg).all(), where
+
+
 def test_rank_pruning_random_cases():
     rng = np.random.default_rng(2025)
     for case in range(60):
