@@ -143,7 +143,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: n=%d d=%d k=%d %s, Gaussian mixture (SIFT-1M stand-in)" % (args.config, n, d, k, metric),
+        "config": {"workload": "%s: n=%d d=%d k=%d %s, Gaussian mixture (%s stand-in)" % (
+            args.config, n, d, k, metric, {"C1": "small test", "C2": "SIFT-1M", "C3": "Gist", "C4": "Deep", "C5": "Deep"}.get(args.config, "synthetic")),
                    "it1": prm.it1, "it2": prm.it2, "S": prm.S, "R": prm.R, "C": prm.C,
                    "ng_row": prm.ng_row, "ng_col": prm.ng_col, "m": prm.m, "seed": int(prm.seed)},
         "recall_at_k": recall,
