@@ -105,8 +105,10 @@ __device__ inline void emit_candidate(const TgCand& cd, const int* s_ids, const 
 // MODE 0: emit candidates for the stored blocks.  MODE 1: write the distance tile of caller-given blocks.
 // NARROW: the rows come from the fp16 copy; a slab then holds 2 DK columns in the same bytes, and a
 // step of 32 columns is one v_mfma_f32_16x16x32_f16 per tile.
-template <int DK, int NGR, int NGC, int MODE, bool NARROW = false>
-__global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
+// ROWS: the most members a block may have here, 64 or 128.  Blocks of at most 64 members need half the
+// registers for a slab on its way, so two slabs travel while a third is multiplied; with 128 it is one.
+template <int DK, int NGR, int NGC, int MODE, bool NARROW = false, int ROWS = TG_BLOCK_COLS>
+__global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(TgGraph g, TgSample sm, TgCand cd, u64 hs_slot,
                                                             u64* stat_bins, const int32_t* xblk,
                                                             const int32_t* xsizes, float* xout, const u64* wl,
                                                             const u32* wl_cnt, int64_t direct_count, int skip_le)
@@ -125,7 +127,9 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     constexpr int CS = 4 * DK / ES;      // columns per slab
     const int ldx = NARROW ? g.ldh : g.ld;                                   // columns per stored row
     const unsigned char* xbase = NARROW ? reinterpret_cast<const unsigned char*>(g.Xh) : reinterpret_cast<const unsigned char*>(g.X);
-    constexpr int PER = TG_BLOCK_COLS * F4 / JOIN_THREADS;   // float4 per thread and slab, at most
+    constexpr int PER = ROWS * F4 / JOIN_THREADS;            // float4 per thread and slab, at most
+    constexpr int DEPTH = ROWS <= 64 ? 2 : 1;                // slabs on their way
+    constexpr int TJ = ROWS / 32;                            // column tiles per wave
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     if (g.f16_ok && (*g.f16_ok != 0u) != NARROW) return;      // the other variant's turn
@@ -147,14 +151,14 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
         nT = nN + xsizes[v * 2 + 1];
         bids = reinterpret_cast<const u32*>(xblk) + v * TG_BLOCK_COLS;
     }
-    if (nN == 0 || nT < 2 || ((nT + 15) >> 4) <= skip_le) continue;
+    if (nN == 0 || nT < 2 || nT > ROWS || ((nT + 15) >> 4) <= skip_le) continue;      // (the lists never hold a larger block)
     __syncthreads();                       // the previous block's epilogue has left the LDS header
 
     // gather of one slab: global -> registers now, registers -> LDS once the tile is free.
     // A thread fetches the same column part of the same PER rows in every slab, so the row
     // addresses are formed once per block and the loads are unconditional (rows and columns
     // past the end read a valid address and are zeroed).
-    float4 pre[PER];
+    float4 pre[DEPTH][PER];
     const int cpart = (tid % F4) * (16 / ES);          // first column of this thread's 16-byte piece
     const unsigned char* rp[PER];
     bool rv[PER];
@@ -164,24 +168,25 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
         rv[it] = row < nT;
         rp[it] = xbase + ((int64_t)bids[rv[it] ? row : 0] * ldx + cpart) * ES;
     }
-    auto issue = [&](int ks) {
+    auto issue = [&](int ks, float4 (&dst)[PER]) {
         const bool cv = ks + cpart < ldx;
         const int kso = cv ? ks : -cpart;
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
             const float4 val = *reinterpret_cast<const float4*>(rp[it] + (int64_t)kso * ES);
-            pre[it] = (rv[it] & cv) ? val : make_float4(0.f, 0.f, 0.f, 0.f);
+            dst[it] = (rv[it] & cv) ? val : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
-    auto commit = [&]() {
+    auto commit = [&](const float4 (&src)[PER]) {
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
             const int e = tid + JOIN_THREADS * it;
             const int row = e / F4;
-            if (row < nT) *reinterpret_cast<float4*>(tile + row * LDTB + (e % F4) * 16) = pre[it];
+            if (row < nT) *reinterpret_cast<float4*>(tile + row * LDTB + (e % F4) * 16) = src[it];
         }
     };
-    issue(0);
+    issue(0, pre[0]);
+    if (DEPTH == 2 && CS < ldx) issue(CS, pre[DEPTH - 1]);
 
     if (tid < nT) {
         const int id = (int)bids[tid];
@@ -203,64 +208,66 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     const int MT = (nN + 15) >> 4, NT = (nT + 15) >> 4;
     const int wr = wave & 1, wc = wave >> 1;
     const int g4 = lane >> 4, c16 = lane & 15;
-    // this wave's tiles: rows {wr, wr+2}, columns {wc, wc+2, wc+4, wc+6}; a tile is needed
-    // when it lies inside the block and is not strictly below the diagonal
-    bool act[2][4];
+    // this wave's tiles: rows {wr, wr+2}, columns {wc, wc+2, wc+4, wc+6} (the first two for blocks of at
+    // most 64 members); a tile is needed when it lies inside the block and is not strictly below the diagonal
+    bool act[2][TJ];
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
+        for (int tj = 0; tj < TJ; ++tj) {
             const int i = wr + 2 * ti, j = wc + 2 * tj;
             act[ti][tj] = i < MT && j < NT && j >= i;
         }
-    floatx4 acc[2][4];
+    floatx4 acc[2][TJ];
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) acc[ti][tj] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        for (int tj = 0; tj < TJ; ++tj) acc[ti][tj] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
-    for (int ks = 0; ks < ldx; ks += CS) {
+    // one slab: its values go from the registers into the tile, the registers take the slab DEPTH further on
+    // (which travels while the slabs before it are multiplied), the tile is multiplied
+    auto slab = [&](int ks, float4 (&stage)[PER]) {
         __syncthreads();
-        commit();
+        commit(stage);
         __syncthreads();
-        if (ks + CS < ldx) issue(ks + CS);      // next slab travels while this one is multiplied
+        if (ks + DEPTH * CS < ldx) issue(ks + DEPTH * CS, stage);
         if (NARROW) {
             // lane (r, q) reads the 8 consecutive columns 32 s + 8 q .. + 7 of its row: one matrix instruction per step
             const int kend = min(CS, ldx - ks);         // rows of the fp16 copy are whole steps, zero padded
             for (int kk = 0; kk < kend; kk += 32) {
-                float4 av[2], bv[4];
+                float4 av[2], bv[TJ];
 #pragma unroll
                 for (int ti = 0; ti < 2; ++ti)
                     if (wr + 2 * ti < MT) av[ti] = *reinterpret_cast<const float4*>(tile + ((wr + 2 * ti) * 16 + c16) * LDTB + (kk + 8 * g4) * 2);
 #pragma unroll
-                for (int tj = 0; tj < 4; ++tj)
+                for (int tj = 0; tj < TJ; ++tj)
                     if (wc + 2 * tj < NT) bv[tj] = *reinterpret_cast<const float4*>(tile + ((wc + 2 * tj) * 16 + c16) * LDTB + (kk + 8 * g4) * 2);
 #pragma unroll
                 for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-                    for (int tj = 0; tj < 4; ++tj)
+                    for (int tj = 0; tj < TJ; ++tj)
                         if (act[ti][tj])
                             acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, av[ti]),
                                                                                   __builtin_bit_cast(halfx8, bv[tj]), acc[ti][tj], 0, 0, 0);
             }
-            continue;
+            return;
         }
         const int kend = min(DK, (g.ld - ks + 15) & ~15);
         // Lane (r, q) = (lane % 16, lane / 16) reads 4 consecutive columns 16*s + 4*q .. +3 of its
         // row; step t of the four MFMAs then contracts columns {16*s + 4*q + t : q = 0..3}.  The
         // same column permutation is applied to both operands, so the sum is the full dot product.
         for (int kk = 0; kk < kend; kk += 16) {
-            float4 av[2], bv[4];
+            float4 av[2], bv[TJ];
 #pragma unroll
             for (int ti = 0; ti < 2; ++ti)
                 if (wr + 2 * ti < MT) av[ti] = *reinterpret_cast<const float4*>(tile + ((wr + 2 * ti) * 16 + c16) * LDTB + (kk + 4 * g4) * 4);
 #pragma unroll
-            for (int tj = 0; tj < 4; ++tj)
+            for (int tj = 0; tj < TJ; ++tj)
                 if (wc + 2 * tj < NT) bv[tj] = *reinterpret_cast<const float4*>(tile + ((wc + 2 * tj) * 16 + c16) * LDTB + (kk + 4 * g4) * 4);
 #pragma unroll
             for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-                for (int tj = 0; tj < 4; ++tj)
+                for (int tj = 0; tj < TJ; ++tj)
                     if (act[ti][tj]) {
                         acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ti].x, bv[tj].x, acc[ti][tj], 0, 0, 0);
                         acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ti].y, bv[tj].y, acc[ti][tj], 0, 0, 0);
@@ -268,15 +275,19 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
                         acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ti].w, bv[tj].w, acc[ti][tj], 0, 0, 0);
                     }
         }
+    };
+    for (int ks = 0; ks < ldx; ks += DEPTH * CS) {
+        slab(ks, pre[0]);
+        if (DEPTH == 2 && ks + CS < ldx) slab(ks + CS, pre[DEPTH - 1]);
     }
 
     // ---- epilogue.  Accumulator element e of tile (i, j) in lane (c16, g4) is the pair
     // (row a = 16 i + 4 g4 + e, column b = 16 j + c16).  "Empty" is (inf, TG_NO_ID).
     const float INF = __builtin_inff();
-    float cbd[4][NGR / 2];
-    u32 cbi[4][NGR / 2];
+    float cbd[TJ][NGR / 2];
+    u32 cbi[TJ][NGR / 2];
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj)
+    for (int tj = 0; tj < TJ; ++tj)
 #pragma unroll
         for (int rg = 0; rg < NGR / 2; ++rg) { cbd[tj][rg] = INF; cbi[tj][rg] = TG_NO_ID; }
 
@@ -301,7 +312,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
             u32 rbi[4] = {TG_NO_ID, TG_NO_ID, TG_NO_ID, TG_NO_ID};
             bool any = false;
 #pragma unroll
-            for (int tj = 0; tj < 4; ++tj) {
+            for (int tj = 0; tj < TJ; ++tj) {
                 if ((tj & (NGC / 2 - 1)) != cg) continue;
                 if (!act[ti][tj]) continue;
                 any = true;
@@ -344,7 +355,7 @@ __global__ __launch_bounds__(JOIN_THREADS) void join_kernel(TgGraph g, TgSample 
     }
     if (MODE == 0) {
 #pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
+        for (int tj = 0; tj < TJ; ++tj) {
             const int j = wc + 2 * tj;
             if (j >= NT) continue;
 #pragma unroll
@@ -693,7 +704,8 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 
 // ---------------------------------------------------------------------------------------
 // Work lists: anchors with something to join, by block size.  List 0: at most 3 row groups,
-// list 1: exactly 4, list 2: more (or everything when the wave kernel does not apply).
+// list 1: exactly 4, list 2: more.  Without the wave kernel (longer rows) list 1 takes every block
+// of at most 4 row groups and list 0 stays empty.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wave_ok)
 {
@@ -709,7 +721,7 @@ __global__ __launch_bounds__(256) void bin_kernel(TgSample sm, int64_t n, int wa
         rec_nT = nT;
         if (nN > 0 && nT >= 2) {
             const int NT = (nT + 15) >> 4;
-            bin = !wave_ok ? 2 : NT <= 3 ? 0 : NT == 4 ? 1 : 2;
+            bin = NT > 4 ? 2 : (NT == 4 || !wave_ok) ? 1 : 0;
         }
     }
     u32 mypos = 0;
@@ -743,34 +755,42 @@ static void allow_large_lds(K kernel, size_t bytes)
 
 #define JOIN_GRID 2048     // persistent launches: workgroups walk the work list with this stride
 
-template <int DK, int NGR, int NGC>
-static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, hipStream_t s)
+// the workgroup kernel on one work list; ROWS = the most members a block of that list has
+template <int DK, int NGR, int NGC, int ROWS>
+static void launch_join_list(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, int list, hipStream_t s)
 {
-    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0, false>, join_lds_bytes(DK, TG_BLOCK_COLS)),
-                        allow_large_lds(join_kernel<DK, NGR, NGC, 0, true>, join_lds_bytes(DK, TG_BLOCK_COLS)), true);
+    static bool once = (allow_large_lds(join_kernel<DK, NGR, NGC, 0, false, ROWS>, join_lds_bytes(DK, ROWS)),
+                        allow_large_lds(join_kernel<DK, NGR, NGC, 0, true, ROWS>, join_lds_bytes(DK, ROWS)), true);
     (void)once;
-    const int rows = sm.BC < TG_BLOCK_COLS ? sm.BC : TG_BLOCK_COLS;   // a stored block never exceeds BC rows
+    const int rows = sm.BC < ROWS ? sm.BC : ROWS;   // a stored block never exceeds BC rows
     const unsigned grid = (unsigned)(g.n < JOIN_GRID ? g.n : JOIN_GRID);
     // with the device flag both variants are launched, and the one it does not name ends at once
     if (g.Xh)
-        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, true>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
+        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, true, ROWS>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
                            hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
-                           (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
+                           (const u64*)(sm.wl + (int64_t)list * g.n), (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
     if (!g.Xh || g.f16_ok)
-        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, false>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
+        hipLaunchKernelGGL((join_kernel<DK, NGR, NGC, 0, false, ROWS>), dim3(grid), dim3(JOIN_THREADS), join_lds_bytes(DK, rows), s, g, sm, c,
                            hs_slot, stat_bins, (const int32_t*)nullptr, (const int32_t*)nullptr, (float*)nullptr,
-                           (const u64*)(sm.wl + 2 * g.n), (const u32*)(sm.wl_cnt + 2), (int64_t)0, 0);
+                           (const u64*)(sm.wl + (int64_t)list * g.n), (const u32*)(sm.wl_cnt + list), (int64_t)0, 0);
+}
+// wave_done: the register-resident kernel has served lists 0 and 1
+template <int DK, int NGR, int NGC>
+static void launch_join_t(const TgGraph& g, const TgSample& sm, const TgCand& c, u64 hs_slot, u64* stat_bins, bool wave_done, hipStream_t s)
+{
+    if (!wave_done) launch_join_list<DK, NGR, NGC, 64>(g, sm, c, hs_slot, stat_bins, 1, s);
+    launch_join_list<DK, NGR, NGC, TG_BLOCK_COLS>(g, sm, c, hs_slot, stat_bins, 2, s);
 }
 static void launch_join_ng(const TgGraph& g, const TgSample& sm, const TgCand& c, int ngr, int ngc, u64 hs_slot,
-                           u64* stat_bins, hipStream_t s)
+                           u64* stat_bins, bool wave_done, hipStream_t s)
 {
-    if (ngr == 2 && ngc == 2) launch_join_t<64, 2, 2>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 2 && ngc == 4) launch_join_t<64, 2, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 2 && ngc == 8) launch_join_t<64, 2, 8>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 4 && ngc == 2) launch_join_t<64, 4, 2>(g, sm, c, hs_slot, stat_bins, s);
-    else if (ngr == 4 && ngc == 4) launch_join_t<64, 4, 4>(g, sm, c, hs_slot, stat_bins, s);
-    else if (g.ld > 64 || (g.Xh && g.ldh > 128)) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, s);   // half as many slabs and barriers
-    else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, s);
+    if (ngr == 2 && ngc == 2) launch_join_t<64, 2, 2>(g, sm, c, hs_slot, stat_bins, wave_done, s);
+    else if (ngr == 2 && ngc == 4) launch_join_t<64, 2, 4>(g, sm, c, hs_slot, stat_bins, wave_done, s);
+    else if (ngr == 2 && ngc == 8) launch_join_t<64, 2, 8>(g, sm, c, hs_slot, stat_bins, wave_done, s);
+    else if (ngr == 4 && ngc == 2) launch_join_t<64, 4, 2>(g, sm, c, hs_slot, stat_bins, wave_done, s);
+    else if (ngr == 4 && ngc == 4) launch_join_t<64, 4, 4>(g, sm, c, hs_slot, stat_bins, wave_done, s);
+    else if (g.ld > 64 || (g.Xh && g.ldh > 128)) launch_join_t<128, 4, 8>(g, sm, c, hs_slot, stat_bins, wave_done, s);   // half as many slabs and barriers
+    else launch_join_t<64, 4, 8>(g, sm, c, hs_slot, stat_bins, wave_done, s);
 }
 
 template <int GMAX, int METRIC, int KS>
@@ -846,7 +866,7 @@ void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int n
         launch_wave_t<3>(g, sm, c, hs_slot, stat_bins, 0, s);
         launch_wave_t<4>(g, sm, c, hs_slot, stat_bins, 1, s);
     }
-    launch_join_ng(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, s);
+    launch_join_ng(g, sm, c, ng_row, ng_col, hs_slot, stat_bins, wv, s);
 }
 
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out,
