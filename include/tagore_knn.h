@@ -205,7 +205,8 @@ int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32_t d_out, i
  * the serial rule of NSG (alpha = 1) and Vamana (alpha > 1) of section 3.2.  Squared L2 only.
  * X: device n x d fp32 row-major (any alignment; 16-byte aligned rows are faster), knn_ids: device
  * n x k int32.  For every node p:
- *   Collect: hops = 1: p's neighbours; hops = 2: those and the neighbours of each of them (k <= 32).
+ *   Collect: hops = 1: p's neighbours; hops = 2: those and the neighbours of each of them (rows of more
+ *            than 32 ids take a slower instance of the kernel with a larger id set).
  *            p itself, ids outside [0, n) and repeats are no candidates.  The candidates are ordered
  *            by (dis(p, c), id) and the first cand_size (1..64) go on.
  *   Filter:  closest first, p' is inserted iff dis(p, p') < alpha dis(p*, p') for every p* inserted
@@ -216,7 +217,7 @@ int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32_t d_out, i
  *            out_deg device n int32: how many were inserted, or NULL.
  * The 'path' Collect of section 5.1 (candidates from a graph search) is not part of this library.
  * The inputs are not modified; nothing is allocated.  Errors: TG_ERR_INVALID_ARG for NULL or
- * out-of-range arguments, TG_ERR_UNSUPPORTED for hops = 2 with k > 32.
+ * out-of-range arguments.
  */
 int tg_prune_dist(const float* X, int64_t n, int32_t d, const int32_t* knn_ids, int32_t k,
                   int32_t hops, int32_t cand_size, float alpha, int32_t d_out,

@@ -605,7 +605,6 @@ static int check_filter(const float* X, int64_t n, int32_t d, const int32_t* knn
     if (hops != 1 && hops != 2) return fail(TG_ERR_INVALID_ARG, "hops = %d must be 1 or 2", hops);
     if (cand_size < 1 || cand_size > 64) return fail(TG_ERR_INVALID_ARG, "cand_size = %d outside 1..64", cand_size);
     if (d_out < 1 || d_out > 64) return fail(TG_ERR_INVALID_ARG, "d_out = %d outside 1..64", d_out);
-    if (hops == 2 && k > 32) return fail(TG_ERR_UNSUPPORTED, "hops = 2 needs k <= 32 (k = %d)", k);
     return TG_OK;
 }
 

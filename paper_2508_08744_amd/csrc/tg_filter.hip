@@ -27,8 +27,15 @@
 #include "tg_device.h"
 #include "tg_kernels.h"
 
-#define FILTER_SET_WORDS 2048       // id set of the 2-hop collection: at most 1 + 32 + 32 * 32 ids
-#define FILTER_QUEUE_WORDS 1088
+// Collect: the neighbours; those and theirs for rows of at most 32 ids; the same for rows of up to 64 ids
+// (a larger id set and queue per wave, which leaves room for two waves per workgroup)
+#define FILTER_ONE_HOP 1
+#define FILTER_TWO_HOPS 2
+#define FILTER_TWO_HOPS_WIDE 3
+// id set (a power of two, at most half full) and queue of the 2-hop collection: at most k + k * k ids
+__host__ __device__ constexpr int filter_set_words(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 8192 : 2048; }
+__host__ __device__ constexpr int filter_queue_words(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 4224 : 1088; }
+__host__ __device__ constexpr int filter_waves(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 2 : 4; }
 #define FILTER_GRID 16384
 #define FILTER_FREE 0xFFFFFFFFu
 
@@ -109,16 +116,17 @@ __device__ inline float filter_own(const float (&dp)[NG], int q4)
     return (q4 & 2) ? hi : lo;
 }
 
+template <int WORDS>
 __device__ inline bool filter_set_insert(u32* tab, u32 id, bool active)
 {
     bool present = false, pending = active;
-    u32 h = (id * 0x9E3779B1u) >> 21;                 // FILTER_SET_WORDS = 2^11
+    u32 h = (id * 0x9E3779B1u) >> (WORDS == 8192 ? 19 : 21);          // the top log2(WORDS) bits
     while (__ballot(pending)) {
         if (pending) {
             const u32 old = atomicCAS(tab + h, FILTER_FREE, id);
             if (old == FILTER_FREE) pending = false;
             else if (old == id) { present = true; pending = false; }
-            else h = (h + 1) & (FILTER_SET_WORDS - 1);
+            else h = (h + 1) & (WORDS - 1);
         }
     }
     return present;
@@ -185,18 +193,21 @@ __device__ inline void filter_wave_sync()
 #define FILTER_RULE_DISPERSION 2
 // words of dynamic LDS per wave: the id set and queue of the 2-hop collection, and, later in the same
 // words, the matrix of angles of the dispersion rule (rows of 16 NG + 1 words)
-__host__ __device__ constexpr int filter_dyn_words(int ng, bool two_hops, int rule)
+__host__ __device__ constexpr int filter_dyn_words(int ng, int collect, int rule)
 {
-    const int collect = two_hops ? FILTER_SET_WORDS + FILTER_QUEUE_WORDS : 0;
+    const int ids = collect == FILTER_ONE_HOP ? 0 : filter_set_words(collect) + filter_queue_words(collect);
     const int angles = rule == FILTER_RULE_DISPERSION ? 16 * ng * (16 * ng + 1) : 0;
-    return collect > angles ? collect : angles;
+    return ids > angles ? ids : angles;
 }
 
-template <int NG, int KS, bool FULL, bool VEC, bool TWO_HOPS, int RULE>
+template <int NG, int KS, bool FULL, bool VEC, int COLLECT, int RULE>
 __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 {
+    constexpr bool TWO_HOPS = COLLECT != FILTER_ONE_HOP;
+    constexpr int WAVES = filter_waves(COLLECT);
+    constexpr int SET_WORDS = filter_set_words(COLLECT);
     constexpr bool ANGLE = RULE == FILTER_RULE_ANGLE;
-    constexpr int DYN = filter_dyn_words(NG, TWO_HOPS, RULE);
+    constexpr int DYN = filter_dyn_words(NG, COLLECT, RULE);
     constexpr int AS = 16 * NG + 1;      // row stride of the matrix of angles
     extern __shared__ u32 dyn[];         // per wave: see filter_dyn_words
     __shared__ int s_cid[4][64];
@@ -215,7 +226,7 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
     const int k = A.k;
     const int nchunks = (A.d + 16 * KS - 1) / (16 * KS);
 
-    for (int64_t p = (int64_t)blockIdx.x * 4 + wave; p < A.n; p += (int64_t)gridDim.x * 4) {
+    for (int64_t p = (int64_t)blockIdx.x * WAVES + wave; p < A.n; p += (int64_t)gridDim.x * WAVES) {
         const float* xp = A.X + p * A.d;
         int m = 0;
         // ---- Collect ----
@@ -245,12 +256,12 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
             filter_wave_sync();
         } else {
             u32* set = dyn + wave * DYN;
-            int* queue = reinterpret_cast<int*>(set + FILTER_SET_WORDS);
-            for (int i = lane; i < FILTER_SET_WORDS; i += 64) set[i] = FILTER_FREE;
+            int* queue = reinterpret_cast<int*>(set + SET_WORDS);
+            for (int i = lane; i < SET_WORDS; i += 64) set[i] = FILTER_FREE;
             filter_wave_sync();
             int Q = 0;
             {
-                const bool fresh = u_ok && !filter_set_insert(set, (u32)u, u_ok);
+                const bool fresh = u_ok && !filter_set_insert<SET_WORDS>(set, (u32)u, u_ok);
                 const u64 mask = __ballot(fresh);
                 if (fresh) queue[__popcll(mask & tg_lanemask_lt())] = u;
                 Q = __popcll(mask);
@@ -264,7 +275,7 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
                 const bool uj_ok = __shfl((int)u_ok, on ? j : 0) != 0;
                 const int32_t w = (on && uj_ok) ? A.ids[(int64_t)uj * k + r] : -1;
                 const bool w_ok = w >= 0 && w < A.n && w != p;
-                const bool fresh = w_ok && !filter_set_insert(set, (u32)w, w_ok);
+                const bool fresh = w_ok && !filter_set_insert<SET_WORDS>(set, (u32)w, w_ok);
                 const u64 mask = __ballot(fresh);
                 if (fresh) queue[Q + __popcll(mask & tg_lanemask_lt())] = w;
                 Q += __popcll(mask);
@@ -474,33 +485,37 @@ __global__ __launch_bounds__(256) void filter_dist_kernel(FilterArgs A)
 }
 
 template <class K>
-static void filter_launch(K kernel, const FilterArgs& A, dim3 grid, size_t shm, hipStream_t s)
+static void filter_launch(K kernel, const FilterArgs& A, int waves, size_t shm, hipStream_t s)
 {
     // more than 64 KB of dynamic LDS has to be asked for
     if (shm > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
-    hipLaunchKernelGGL(kernel, grid, dim3(256), shm, s, A);
+    int64_t wgs = (A.n + waves - 1) / waves;        // a wave per node; workgroups beyond the grid walk on
+    if (wgs > FILTER_GRID) wgs = FILTER_GRID;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)wgs), dim3(64 * waves), shm, s, A);
 }
 
-template <int NG, bool TWO_HOPS, int RULE>
-static void launch_filter(const FilterArgs& A, bool vec, dim3 grid, hipStream_t s)
+template <int NG, int COLLECT, int RULE>
+static void launch_filter(const FilterArgs& A, bool vec, hipStream_t s)
 {
-    const size_t shm = (size_t)4 * filter_dyn_words(NG, TWO_HOPS, RULE) * sizeof(u32);
+    constexpr int grid = filter_waves(COLLECT);     // waves per workgroup; filter_launch sizes the grid from it
+    const size_t shm = (size_t)filter_waves(COLLECT) * filter_dyn_words(NG, COLLECT, RULE) * sizeof(u32);
     // two row groups take their columns in chunks of 64, four in chunks of 32: few registers, so that
     // four (three) waves per SIMD cover each other's loads
     constexpr int KS = NG > 2 ? 2 : 4;
     const bool full = vec && (A.d % (16 * KS) == 0);         // no column guards needed
-    if (full) filter_launch(filter_dist_kernel<NG, KS, true, true, TWO_HOPS, RULE>, A, grid, shm, s);
-    else if (vec) filter_launch(filter_dist_kernel<NG, KS, false, true, TWO_HOPS, RULE>, A, grid, shm, s);
-    else filter_launch(filter_dist_kernel<NG, KS, false, false, TWO_HOPS, RULE>, A, grid, shm, s);
+    if (full) filter_launch(filter_dist_kernel<NG, KS, true, true, COLLECT, RULE>, A, grid, shm, s);
+    else if (vec) filter_launch(filter_dist_kernel<NG, KS, false, true, COLLECT, RULE>, A, grid, shm, s);
+    else filter_launch(filter_dist_kernel<NG, KS, false, false, COLLECT, RULE>, A, grid, shm, s);
 }
 
 template <int RULE>
-static void launch_filter_rule(const FilterArgs& A, bool vec, int most, dim3 grid, hipStream_t s)
+static void launch_filter_rule(const FilterArgs& A, bool vec, int most, hipStream_t s)
 {
     // the 2-hop collection measures 64 candidates at a time, which needs the four-group instance
-    if (A.hops == 2) launch_filter<4, true, RULE>(A, vec, grid, s);
-    else if (most <= 32) launch_filter<2, false, RULE>(A, vec, grid, s);
-    else launch_filter<4, false, RULE>(A, vec, grid, s);
+    if (A.hops == 2 && A.k > 32) launch_filter<4, FILTER_TWO_HOPS_WIDE, RULE>(A, vec, s);
+    else if (A.hops == 2) launch_filter<4, FILTER_TWO_HOPS, RULE>(A, vec, s);
+    else if (most <= 32) launch_filter<2, FILTER_ONE_HOP, RULE>(A, vec, s);
+    else launch_filter<4, FILTER_ONE_HOP, RULE>(A, vec, s);
 }
 
 void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int k, int hops, int cand_size, int rule, float thr,
@@ -515,9 +530,7 @@ void tg_launch_filter(const float* X, int64_t n, int d, const int32_t* ids, int 
     A.d_out = d_out; A.out_ids = out_ids; A.out_deg = out_deg;
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     const int most = hops == 1 ? k : (cand_size < 64 ? cand_size : 64);      // candidates that reach the filter
-    int64_t wgs = (n + 3) / 4;
-    if (wgs > FILTER_GRID) wgs = FILTER_GRID;
-    if (rule == FILTER_RULE_DISPERSION) launch_filter_rule<FILTER_RULE_DISPERSION>(A, vec, most, dim3((unsigned)wgs), s);
-    else if (rule == FILTER_RULE_ANGLE) launch_filter_rule<FILTER_RULE_ANGLE>(A, vec, most, dim3((unsigned)wgs), s);
-    else launch_filter_rule<FILTER_RULE_DIST>(A, vec, most, dim3((unsigned)wgs), s);
+    if (rule == FILTER_RULE_DISPERSION) launch_filter_rule<FILTER_RULE_DISPERSION>(A, vec, most, s);
+    else if (rule == FILTER_RULE_ANGLE) launch_filter_rule<FILTER_RULE_ANGLE>(A, vec, most, s);
+    else launch_filter_rule<FILTER_RULE_DIST>(A, vec, most, s);
 }

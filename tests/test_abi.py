@@ -76,19 +76,19 @@ def test_invalid_arguments_are_rejected_on_the_host():
     for a, want in [((100, 8, 16, 1, 64, 1.0, 0), -1), ((100, 8, 16, 1, 64, 1.0, 65), -1), ((100, 8, 16, 3, 64, 1.0, 8), -1),
                     ((100, 8, 16, 1, 0, 1.0, 8), -1), ((100, 8, 16, 1, 65, 1.0, 8), -1), ((100, 8, 16, 1, 64, 0.99, 8), -1),
                     ((100, 8, 16, 1, 64, float("nan"), 8), -1), ((0, 8, 16, 1, 64, 1.0, 8), -1), ((100, 0, 16, 1, 64, 1.0, 8), -1),
-                    ((100, 8, 65, 1, 64, 1.0, 8), -1), ((100, 8, 40, 2, 64, 1.0, 8), -2)]:
+                    ((100, 8, 65, 1, 64, 1.0, 8), -1), ((100, 8, 65, 2, 64, 1.0, 8), -1)]:
         n, d, k, hops, cs, alpha, d_out = a
         assert lib.tg_prune_dist(fake, n, d, fake, k, hops, cs, alpha, d_out, fake, None, None) == want, a
     assert lib.tg_prune_dist(None, 100, 8, fake, 16, 1, 64, 1.0, 8, fake, None, None) == -1
     for a, want in [((100, 8, 16, 1, 64, 60.0, 0), -1), ((100, 8, 16, 3, 64, 60.0, 8), -1), ((100, 8, 16, 1, 65, 60.0, 8), -1),
                     ((100, 8, 16, 1, 64, 0.0, 8), -1), ((100, 8, 16, 1, 64, 90.01, 8), -1), ((100, 8, 16, 1, 64, -60.0, 8), -1),
-                    ((100, 8, 16, 1, 64, float("nan"), 8), -1), ((100, 8, 40, 2, 64, 60.0, 8), -2)]:
+                    ((100, 8, 16, 1, 64, float("nan"), 8), -1), ((100, 8, 65, 2, 64, 60.0, 8), -1)]:
         n, d, k, hops, cs, gamma, d_out = a
         assert lib.tg_prune_angle(fake, n, d, fake, k, hops, cs, gamma, d_out, fake, None, None) == want, a
     assert lib.tg_prune_angle(fake, 100, 8, None, 16, 1, 64, 60.0, 8, fake, None, None) == -1
     for a, want in [((100, 8, 16, 1, 64, 0), -1), ((100, 8, 16, 1, 64, 65), -1), ((100, 8, 16, 0, 64, 8), -1),
                     ((100, 8, 16, 1, 0, 8), -1), ((100, 8, 65, 1, 64, 8), -1), ((100, 4097, 16, 1, 64, 8), -1),
-                    ((100, 8, 40, 2, 64, 8), -2)]:
+                    ((100, 8, 65, 2, 64, 8), -1)]:
         n, d, k, hops, cs, d_out = a
         assert lib.tg_prune_dispersion(fake, n, d, fake, k, hops, cs, d_out, fake, None, None) == want, a
     assert lib.tg_prune_dispersion(fake, 100, 8, fake, 16, 1, 64, 8, None, None, None) == -1

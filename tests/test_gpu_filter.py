@@ -55,6 +55,9 @@ def test_one_hop_bit_exact_on_integer_data(n, d, k, d_out, alpha, cand_size):
     (1500, 64, 20, 20, 1.0, 33),
     (800, 30, 7, 12, 1.4, 64),
     (500, 8, 3, 6, 1.0, 5),
+    (1200, 128, 64, 32, 1.0, 64),       # rows of more than 32 ids: the instance with the larger id set
+    (900, 48, 40, 24, 1.3, 50),
+    (700, 20, 33, 64, 1.1, 64),
 ])
 def test_two_hops_bit_exact_on_integer_data(n, d, k, d_out, alpha, cand_size):
     X = _integer_points(n, d)
@@ -131,6 +134,6 @@ def test_bad_arguments():
     X = torch.zeros((100, 8), device="cuda")
     ids = torch.zeros((100, 40), dtype=torch.int32, device="cuda")
     for kw in (dict(d_out=0), dict(d_out=65), dict(d_out=4, alpha=0.9), dict(d_out=4, hops=3), dict(d_out=4, cand_size=0),
-               dict(d_out=4, cand_size=65), dict(d_out=4, hops=2)):
+               dict(d_out=4, cand_size=65)):
         with pytest.raises(knn.TagoreError):
             knn.prune_dist(X, ids, **kw)

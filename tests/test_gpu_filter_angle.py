@@ -55,6 +55,8 @@ def test_one_hop_bit_exact_on_integer_data(n, d, k, d_out, gamma, cand_size):
     (1500, 64, 20, 20, 90.0, 33),
     (800, 30, 7, 12, 70.0, 64),
     (500, 8, 3, 6, 60.0, 5),
+    (1200, 128, 64, 32, 60.0, 64),      # rows of more than 32 ids: the instance with the larger id set
+    (900, 48, 40, 24, 45.0, 50),
 ])
 def test_two_hops_bit_exact_on_integer_data(n, d, k, d_out, gamma, cand_size):
     X = _integer_points(n, d)
@@ -121,6 +123,6 @@ def test_bad_arguments():
     ids = torch.zeros((100, 40), dtype=torch.int32, device="cuda")
     for kw in (dict(d_out=0), dict(d_out=65), dict(d_out=4, gamma_deg=0.0), dict(d_out=4, gamma_deg=91.0),
                dict(d_out=4, gamma_deg=float("nan")), dict(d_out=4, hops=3), dict(d_out=4, cand_size=0),
-               dict(d_out=4, cand_size=65), dict(d_out=4, hops=2)):
+               dict(d_out=4, cand_size=65)):
         with pytest.raises(knn.TagoreError):
             knn.prune_angle(X, ids, **kw)

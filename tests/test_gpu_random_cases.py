@@ -26,7 +26,7 @@ def test_distance_pruning_random_cases():
         n = int(rng.integers(2, 300))
         d = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 33, 64, 100, 128, 129, 200]))
         hops = int(rng.integers(1, 3))
-        k = int(rng.integers(1, 33 if hops == 2 else 65))
+        k = int(rng.integers(1, 65))
         cand_size = int(rng.integers(1, 65))
         d_out = int(rng.integers(1, 65))
         alpha = float(rng.choice([1.0, 1.0, 1.1, 1.5, 3.0]))
@@ -46,7 +46,7 @@ def test_angle_pruning_random_cases():
         n = int(rng.integers(2, 300))
         d = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 33, 64, 100, 128, 129, 200]))
         hops = int(rng.integers(1, 3))
-        k = int(rng.integers(1, 33 if hops == 2 else 65))
+        k = int(rng.integers(1, 65))
         cand_size = int(rng.integers(1, 65))
         d_out = int(rng.integers(1, 65))
         gamma = float(rng.choice([60.0, 60.0, 15.0, 45.0, 72.5, 90.0]))
@@ -66,7 +66,7 @@ def test_dispersion_pruning_random_cases():
         n = int(rng.integers(2, 300))
         d = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 33, 64, 100, 128, 129, 200]))
         hops = int(rng.integers(1, 3))
-        k = int(rng.integers(1, 33 if hops == 2 else 65))
+        k = int(rng.integers(1, 65))
         cand_size = int(rng.integers(1, 65))
         d_out = int(rng.integers(1, 65))
         X = rng.integers(0, 40, size=(n, d)).astype(np.float32)           # exact in fp32, many equal sums and twins
