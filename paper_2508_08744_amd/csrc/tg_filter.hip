@@ -28,14 +28,14 @@
 #include "tg_kernels.h"
 
 // Collect: the neighbours; those and theirs for rows of at most 32 ids; the same for rows of up to 64 ids
-// (a larger id set and queue per wave, which leaves room for two waves per workgroup)
+// (a larger id set and queue per wave, which leaves room for three waves per workgroup)
 #define FILTER_ONE_HOP 1
 #define FILTER_TWO_HOPS 2
 #define FILTER_TWO_HOPS_WIDE 3
 // id set (a power of two, at most half full) and queue of the 2-hop collection: at most k + k * k ids
 __host__ __device__ constexpr int filter_set_words(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 8192 : 2048; }
 __host__ __device__ constexpr int filter_queue_words(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 4224 : 1088; }
-__host__ __device__ constexpr int filter_waves(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 2 : 4; }
+__host__ __device__ constexpr int filter_waves(int collect) { return collect == FILTER_TWO_HOPS_WIDE ? 3 : 4; }
 #define FILTER_GRID 16384
 #define FILTER_FREE 0xFFFFFFFFu
 
