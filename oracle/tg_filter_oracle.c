@@ -44,6 +44,10 @@
  * Pinning (tests/test_oracle_filter.py): closed forms on a line and on a circle, the strict
  * inequality on an isosceles triangle, alpha -> infinity reduces to "the d_out nearest
  * candidates", duplicates, 2-hop collection against a set union in Python, invariants.
+ * The angle rule (tests/test_oracle_filter_angle.py): line, circle, a right angle with gamma = 90,
+ * angles measured with arccos, equality with the distance rule on a sphere.  The dispersion rule
+ * (tests/test_oracle_filter_dpg.py): the arc cosine against the library's, a hand-made example,
+ * a greedy in double precision written in the test, twins, prefix and scaling invariants.
  */
 #include <math.h>
 #include <stdint.h>
