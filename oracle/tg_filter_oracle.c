@@ -1,7 +1,7 @@
 /*
  * CPU oracle for the distance-based and the angle-based pruning of a k-NN graph in the
  * Collect-Filter-Store procedure (paper section 5.1, the algorithm "CFS procedure of
- * pruning"; the NSG, Vamana and NSSG rows of the table of pruning strategies and their
+ * pruning"; the NSG, Vamana, NSSG and DPG rows of the table of pruning strategies and their
  * description in section 3.2).
  *
  * THIS IS TEST INFRASTRUCTURE: a plain, slow, single-threaded definition written out,
