@@ -116,6 +116,31 @@ def test_padding_duplicates_self_and_small_candidate_sets():
             assert (want[60:70] == -1).all() and (deg[60:70] == 0).all()
 
 
+def test_wide_rows_with_padding_and_repeats_over_two_hops():
+    # rows of 40 and of 64 ids (the two-hop instance with the larger id set), with padding, ids without a row,
+    # repeats, self ids, empty rows and twins among the points
+    rng = np.random.default_rng(6)
+    n, d = 600, 24
+    X = _integer_points(n, d)
+    X[1::5] = X[0::5][: len(X[1::5])]
+    for k in (40, 64):
+        ids = rng.integers(0, n, size=(n, k)).astype(np.int32)
+        noise = rng.random((n, k))
+        ids[noise < 0.1] = -1
+        ids[(noise >= 0.1) & (noise < 0.13)] = n + 3
+        ids[:40, 7] = np.arange(40)
+        ids[100:110] = -1
+        for alpha, d_out, cand_size in ((1.0, 32, 64), (1.4, 64, 47)):
+            want, deg = _exact(X, ids, d_out, alpha, 2, cand_size)
+            assert (deg[100:110] == 0).all()
+        want, want_deg, _ = oracle.filter_angle(X, ids, 2, 64, 60.0, 24)
+        out = knn.prune_angle(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), 24, gamma_deg=60.0, hops=2)
+        assert (out.cpu().numpy() == want).all()
+        want, want_deg, _ = oracle.filter_dpg(X, ids, 2, 64, 24)
+        out = knn.prune_dispersion(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(), 24, hops=2)
+        assert (out.cpu().numpy() == want).all()
+
+
 @pytest.mark.parametrize("config,n,d,k,hops", [("C1", 4000, 32, 16, 1), ("C1", 3000, 32, 16, 2), ("C4", 3000, 96, 32, 1),
                                                ("C3", 1500, 960, 32, 1)])
 def test_real_valued_data_differs_only_where_a_decision_was_a_near_tie(config, n, d, k, hops):
