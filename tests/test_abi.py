@@ -114,3 +114,21 @@ def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(knn, "_LIB_PATH", "/nonexistent/libtagore_knn.so")
     with pytest.raises(RuntimeError):
         knn.lib()
+
+
+def test_binding_refuses_host_tensors():
+    # there is no CPU path behind the binding: tensors that are not on the device are turned away before
+    # the library is called, whatever the entry point
+    import torch
+    from paper_2508_08744_amd import knn
+    X = torch.zeros((100, 8))
+    ids = torch.zeros((100, 4), dtype=torch.int32)
+    for call in (lambda: knn.knn_build(X, 4), lambda: knn.knn_build_ex(X, knn.default_params(4, 2)),
+                 lambda: knn.exact_knn(X, 4), lambda: knn.prune_dist(X, ids, 2), lambda: knn.prune_angle(X, ids, 2),
+                 lambda: knn.prune_dispersion(X, ids, 2), lambda: knn.angle_at(X[0], X[0], X[0])):
+        with pytest.raises((TypeError, ValueError)):
+            call()
+    with pytest.raises((TypeError, ValueError)):
+        knn.prune_rank(ids, 2)
+    with pytest.raises((TypeError, ValueError)):
+        knn.merge_local(ids, X[:, :4].contiguous(), ids, X[:, :4].contiguous(), torch.arange(100, dtype=torch.int32))
