@@ -97,7 +97,7 @@ struct tg_knn_handle {
     u64* d_stat_bins;    // TG_MAX_ROUNDS x 2 x TG_STAT_BINS
     float* x_padded;     // own copy of X when the caller's rows are not 16-byte friendly
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
-    float* xqm;          // its row constants
+    float* xqm;          // its grid (three words, see TgGraph)
     u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
     uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1, 2)
     u32* d_f16_ok;       // join_f16 = 2: device flag, 1 while every value of X is an fp16 number
@@ -133,7 +133,7 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.kth = c.take<u64>(n);
     h->g.ldq = (d + 15) & ~15;
     h->xq = p.screen ? c.take<uint8_t>((size_t)n * h->g.ldq) : nullptr;
-    h->xqm = p.screen ? c.take<float>((size_t)n * 8) : nullptr;
+    h->xqm = p.screen ? c.take<float>(64) : nullptr;
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
     h->d_screen_on = c.take<u32>(64);

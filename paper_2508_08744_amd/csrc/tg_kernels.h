@@ -32,7 +32,8 @@ struct TgGraph {
     float* gdist;     // n x k
     unsigned long long* kth;   // n: key of each list's last entry with both low bits set
     const uint8_t* Xq;  // n x ldq bytes: 8-bit codes of every row (phase-2 screening), or null
-    const float* Xqm;   // n x 8: the row constants that go with the codes
+    const float* Xqm;   // the grid of the codes, three words: ordered bits of the smallest and of the largest value of X, float
+                        // bits of the largest distance of a row from its grid point
     int32_t ldq;        // d rounded up to 16: a row of codes never straddles more lines than it must
     const uint16_t* Xh; // n x ldh: the rows rounded to fp16 for the local join, or null (join in fp32)
     int32_t ldh;        // 64, 96 or 128 (the smallest that holds d), d rounded up to 32 beyond: columns d..ldh-1 are zero

@@ -93,76 +93,109 @@ void tg_launch_norms(const TgGraph& g, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------------------
-// 8-bit screening copy of X for phase 2.  Row x becomes codes q_i = round((x_i - lo) / s) in
-// 0..255 with lo = min x_i, s = (max x_i - lo) / 255, i.e. the vector xq_i = lo + s q_i, and
-// eight row constants (an array of their own, small enough to stay in cache): lo, s, err >= |x - xq|, sum q_i, |xq|^2, sum (|lo| + s q_i)^2,
-// 1/|x| (cosine) and a spare.  With them <xq, yq> follows from the integer dot product of
-// the codes, and |x - y| >= |xq - yq| - err_x - err_y bounds the true distance from below.
+// 8-bit screening copy of X for phase 2.  One grid for the whole data set: lo = the smallest value
+// of X, s = (the largest - lo) / 255; row x becomes the codes q_i = round((x_i - lo) / s) in 0..255,
+// i.e. the vector xq_i = lo + s q_i.  Then |xq - yq|^2 = s^2 sum (qx_i - qy_i)^2 and <xq, yq> follow
+// from integer dot products of the codes alone (nothing but the codes has to be fetched for a
+// candidate), and |x - y| >= |xq - yq| - 2 err bounds the true distance from below, err being the
+// largest |x - xq| of any row.  Byte-valued data have lo = 0, s = 1 and err = 0: the bound is the distance.
+// grid: [0] ordered bits of lo, [1] of the largest value, [2] float bits of err.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq, float* __restrict__ Xqm, int64_t v0)
+__global__ __launch_bounds__(256) void quantize_range_kernel(TgGraph g, u32* __restrict__ grid)
 {
-    const int64_t row = v0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    __shared__ u32 s_lo[16], s_hi[16];
     const int sub = threadIdx.x & 15;
-    const bool live = row < g.n;
-    const float* x = g.X + (live ? row : 0) * (int64_t)g.ld;
     float lo = __builtin_inff(), hi = -__builtin_inff();
-    for (int c = sub * 4; c < g.ld; c += 64) {
-        const float4 v = *reinterpret_cast<const float4*>(x + c);
-        const float e[4] = {v.x, v.y, v.z, v.w};
+    for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < g.n; row += (int64_t)gridDim.x * 16) {
+        const float* x = g.X + row * (int64_t)g.ld;
+        for (int c = sub * 4; c < g.ld; c += 64) {
+            const float4 v = *reinterpret_cast<const float4*>(x + c);
+            const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (c + i < g.d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }
+            for (int i = 0; i < 4; ++i)
+                if (c + i < g.d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }
+        }
     }
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) {
         lo = fminf(lo, __shfl_xor(lo, o));
         hi = fmaxf(hi, __shfl_xor(hi, o));
     }
-    const float s = hi > lo ? (hi - lo) / 255.0f : 1.0f;
+    if (sub == 0) { s_lo[threadIdx.x >> 4] = tg_ord(lo); s_hi[threadIdx.x >> 4] = tg_ord(hi); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 a = s_lo[0], b = s_hi[0];
+        for (int i = 1; i < 16; ++i) { a = min(a, s_lo[i]); b = max(b, s_hi[i]); }
+        atomicMin(grid + 0, a);
+        atomicMax(grid + 1, b);
+    }
+}
+// lo and s of the grid from its first two words (the same expressions wherever they are needed)
+__device__ inline void quantize_grid(const u32* grid, float& lo, float& s)
+{
+    lo = tg_unord(grid[0]);
+    const float hi = tg_unord(grid[1]);
+    s = hi > lo ? (hi - lo) / 255.0f : 1.0f;
+}
+__global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __restrict__ Xq, u32* __restrict__ grid)
+{
+    __shared__ float s_err[16];
+    const int sub = threadIdx.x & 15;
+    float lo, s;
+    quantize_grid(grid, lo, s);
     const float inv = 1.0f / s;
     const float alo = fabsf(lo);
     const int dq = g.ldq;
-    uint8_t* out = Xq + (live ? row : 0) * (int64_t)g.ldq;
-    float err2 = 0.0f, qn2 = 0.0f, an2 = 0.0f, sumq = 0.0f;
-    for (int c = sub * 4; c < dq; c += 64) {
-        u32 packed = 0u;
-        if (c < g.ld) {
-            const float4 v = *reinterpret_cast<const float4*>(x + c);
-            const float e[4] = {v.x, v.y, v.z, v.w};
+    float worst = 0.0f;          // largest |x - xq| of the rows this group of 16 lanes has coded
+    for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < g.n; row += (int64_t)gridDim.x * 16) {
+        const float* x = g.X + row * (int64_t)g.ld;
+        uint8_t* out = Xq + row * (int64_t)g.ldq;
+        float err2 = 0.0f, an2 = 0.0f;
+        for (int c = sub * 4; c < dq; c += 64) {
+            u32 packed = 0u;
+            if (c < g.ld) {
+                const float4 v = *reinterpret_cast<const float4*>(x + c);
+                const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (c + i < g.d) {
-                    const float q = fminf(255.0f, fmaxf(0.0f, rintf((e[i] - lo) * inv)));
-                    const float r = fmaf(s, q, lo);
-                    const float t = e[i] - r, a = fmaf(s, q, alo);
-                    err2 = fmaf(t, t, err2);
-                    qn2 = fmaf(r, r, qn2);
-                    an2 = fmaf(a, a, an2);
-                    sumq += q;
-                    packed |= (u32)q << (8 * i);
+                for (int i = 0; i < 4; ++i) {
+                    if (c + i < g.d) {
+                        const float q = fminf(255.0f, fmaxf(0.0f, rintf((e[i] - lo) * inv)));
+                        const float r = fmaf(s, q, lo);
+                        const float t = e[i] - r, a = fmaf(s, q, alo);
+                        err2 = fmaf(t, t, err2);
+                        an2 = fmaf(a, a, an2);
+                        packed |= (u32)q << (8 * i);
+                    }
                 }
             }
+            *reinterpret_cast<u32*>(out + c) = packed;
         }
-        if (live) *reinterpret_cast<u32*>(out + c) = packed;
-    }
 #pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-        err2 += __shfl_xor(err2, o);
-        qn2 += __shfl_xor(qn2, o);
-        an2 += __shfl_xor(an2, o);
-        sumq += __shfl_xor(sumq, o);
+        for (int o = 1; o < 16; o <<= 1) {
+            err2 += __shfl_xor(err2, o);
+            an2 += __shfl_xor(an2, o);
+        }
+        // |x - xq| for the exact grid point xq: the measured distance to its fp32 value, rounded up, plus the
+        // rounding of that value itself (half an ulp per component: far below 1e-6 of |lo| + s q)
+        worst = fmaxf(worst, sqrtf(err2) * 1.0001f + 1e-6f * sqrtf(an2));
     }
-    if (live && sub == 0) {
-        float4* m = reinterpret_cast<float4*>(Xqm + row * 8);
-        m[0] = make_float4(lo, s, sqrtf(err2) * 1.0001f, sumq);
-        m[1] = make_float4(qn2, an2, g.metric == 2 ? g.rnorm[row] : 0.0f, 0.0f);
+    if (sub == 0) s_err[threadIdx.x >> 4] = worst;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float e = s_err[0];
+        for (int i = 1; i < 16; ++i) e = fmaxf(e, s_err[i]);
+        atomicMax(grid + 2, __float_as_uint(e));          // not negative: the bit patterns order the values
     }
 }
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s)
 {
-    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-        hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)((cnt + 15) / 16)), dim3(256), 0, s, g, Xq, Xqm, v0);
-    });
+    u32* grid = reinterpret_cast<u32*>(Xqm);
+    tg_launch_fill_u32(grid + 0, 1, 0xFF800000u, s);      // ordered +infinity: the smallest value so far
+    tg_launch_fill_u32(grid + 1, 1, 0x007FFFFFu, s);      // ordered -infinity
+    tg_launch_fill_u32(grid + 2, 1, 0u, s);
+    const int64_t range_wgs = (g.n + 15) / 16;
+    hipLaunchKernelGGL(quantize_range_kernel, dim3((unsigned)(range_wgs < 2048 ? range_wgs : 2048)), dim3(256), 0, s, g, grid);
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)(range_wgs < 2048 ? range_wgs : 2048)), dim3(256), 0, s, g, Xq, grid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -300,19 +333,28 @@ __device__ inline float wave_direct_dist(const TgGraph& g, const float* xs, floa
 
 // ---------------------------------------------------------------------------------------
 // Screening for phase 2: of one candidate id per lane (cid < 0: none) keep those whose
-// distance to node v may still precede kd, judged on the 8-bit copy: the bound
-// |x - y| >= |xq - yq| - err_x - err_y (and its inner-product forms) is rigorous, the margins
-// below cover the fp32 rounding of both this estimate and the exact evaluation that follows,
-// so a dropped candidate could never have entered the list.  Eight lanes share a candidate
-// row (16 bytes each per 128 columns); survivors come back one per lane in a new order.
-// xq_s: v's codes and constants in LDS; wscr: 64 words of LDS private to this wave.
+// distance to node v may still precede kd, judged on the 8-bit copy.  With the codes qx of v
+// and qy of the candidate (integer dot products sum qx qy, sum qy qy, sum qy) and the grid
+// (lo, s, err >= |x - xq| for every row):
+//   |x - y| >= s sqrt(sum (qx - qy)^2) - 2 err                                   (squared L2)
+//   <x, y> <= <xq, yq> + err (|yq| + |x|),  <xq, yq> = d lo^2 + lo s (sum qx + sum qy) + s^2 sum qx qy,
+//   |yq|^2 = d lo^2 + 2 lo s sum qy + s^2 sum qy qy, and | |y| - |yq| | <= err    (inner product, cosine)
+// are rigorous; the margins below cover the fp32 rounding of both these estimates and the
+// exact evaluation that follows, so a dropped candidate could never have entered the list.
+// Eight lanes share a candidate row (16 bytes each per 128 columns); survivors come back one
+// per lane in a new order.  xq_s: v's codes in LDS; qxx, qx1: sum qx qx and sum qx of v;
+// wscr: 64 words of LDS private to this wave.
 // ---------------------------------------------------------------------------------------
 template <int CTRL>
 __device__ inline u32 dpp_u32(u32 x)
 {
     return (u32)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
 }
-__device__ inline int wave_screen(const TgGraph& g, const uint4* xq_s, float norm_v, int cid, u32* wscr, float kd)
+struct ScreenGrid {
+    float lo, s, err;
+};
+__device__ inline int wave_screen(const TgGraph& g, const ScreenGrid& grid, const uint4* xq_s, u32 qxx, u32 qx1, float norm_v,
+                                  float rn_v, int cid, u32* wscr, float kd)
 {
     const int lane = tg_lane();
     const int sub = lane & 7, c8 = lane >> 3;
@@ -324,66 +366,109 @@ __device__ inline int wave_screen(const TgGraph& g, const uint4* xq_s, float nor
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     const int nch = g.ldq >> 4;
-    u32 rows[8], dot[8];
+    const bool ragged = (nch & 7) != 0;
+    const bool l2 = g.metric == 0;
+    // the lane (c8, sub) speaks for candidate 8 sub + c8; the eight lanes of a group take the candidates
+    // 8 q + c8, q = 0..7, four at a time (two turns keep the sums of four candidates in registers, not of eight)
+    const int p = 8 * sub + c8;
+    const bool mine = p < nv;
+    const u32 row = wscr[mine ? p : nv - 1];
+    u32 xy = 0u, yy = 0u, y1 = 0u;
+#pragma unroll 1
+    for (int h = 0; h < 8; h += 4) {
+        if (8 * h >= nv) break;                   // none of these four candidates exists (uniform)
+        u32 rows[4], dxy[4], dyy[4], dy1[4];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int p = 8 * q + c8;
-        rows[q] = wscr[p < nv ? p : nv - 1];      // candidates past the end repeat the last one
-        dot[q] = 0u;
-    }
-    for (int ch0 = 0; ch0 < nch; ch0 += 8) {
-        const int ch = ch0 + sub;
-        const bool real = ch < nch;
-        const int cc = real ? ch : 0;
-        uint4 a = xq_s[cc];
-        if (!real) a = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-        for (int h = 0; h < 8; h += 4) {
+        for (int q = 0; q < 4; ++q) {
+            const int pq = 8 * (h + q) + c8;
+            rows[q] = wscr[pq < nv ? pq : nv - 1];      // candidates past the end repeat the last one
+            dxy[q] = 0u;
+            dyy[q] = 0u;
+            dy1[q] = 0u;
+        }
+        for (int ch0 = 0; ch0 < nch; ch0 += 8) {
+            const int ch = ch0 + sub;
+            const bool real = ch < nch;            // always, when a row is a whole number of 128 codes (uniform test)
+            const int cc = real ? ch : 0;
+            uint4 a = xq_s[cc];
             uint4 b[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                b[q] = *reinterpret_cast<const uint4*>(g.Xq + (int64_t)rows[h + q] * g.ldq + 16 * cc);
+            for (int q = 0; q < 4; ++q) b[q] = *reinterpret_cast<const uint4*>(g.Xq + (int64_t)rows[q] * g.ldq + 16 * cc);
+            if (ragged && !real) {
+                a = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) b[q] = make_uint4(0u, 0u, 0u, 0u);
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                u32 t = dot[h + q];
+                u32 t = dxy[q];
                 t = __builtin_amdgcn_udot4(a.x, b[q].x, t, false);
                 t = __builtin_amdgcn_udot4(a.y, b[q].y, t, false);
                 t = __builtin_amdgcn_udot4(a.z, b[q].z, t, false);
                 t = __builtin_amdgcn_udot4(a.w, b[q].w, t, false);
-                dot[h + q] = t;
+                dxy[q] = t;
+                u32 u = dyy[q];
+                u = __builtin_amdgcn_udot4(b[q].x, b[q].x, u, false);
+                u = __builtin_amdgcn_udot4(b[q].y, b[q].y, u, false);
+                u = __builtin_amdgcn_udot4(b[q].z, b[q].z, u, false);
+                u = __builtin_amdgcn_udot4(b[q].w, b[q].w, u, false);
+                dyy[q] = u;
+                if (!l2) {
+                    u32 w1 = dy1[q];
+                    w1 = __builtin_amdgcn_udot4(b[q].x, 0x01010101u, w1, false);
+                    w1 = __builtin_amdgcn_udot4(b[q].y, 0x01010101u, w1, false);
+                    w1 = __builtin_amdgcn_udot4(b[q].z, 0x01010101u, w1, false);
+                    w1 = __builtin_amdgcn_udot4(b[q].w, 0x01010101u, w1, false);
+                    dy1[q] = w1;
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 t = dxy[q], u = dyy[q];
+            t += dpp_u32<0xB1>(t);     // lane ^ 1
+            t += dpp_u32<0x4E>(t);     // lane ^ 2
+            t += dpp_u32<0x141>(t);    // mirror inside 8 lanes: the other quad
+            u += dpp_u32<0xB1>(u);
+            u += dpp_u32<0x4E>(u);
+            u += dpp_u32<0x141>(u);
+            xy = sub == h + q ? t : xy;
+            yy = sub == h + q ? u : yy;
+            if (!l2) {
+                u32 w1 = dy1[q];
+                w1 += dpp_u32<0xB1>(w1);
+                w1 += dpp_u32<0x4E>(w1);
+                w1 += dpp_u32<0x141>(w1);
+                y1 = sub == h + q ? w1 : y1;
             }
         }
     }
-    // the lane (c8, sub) speaks for candidate 8 sub + c8
-    const int p = 8 * sub + c8;
-    const bool mine = p < nv;
-    const u32 row = wscr[mine ? p : nv - 1];
-    const float4* my = reinterpret_cast<const float4*>(g.Xqm + (int64_t)row * 8);
-    const float4 m0 = my[0], m1 = my[1];
-    u32 d8 = 0u;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        u32 t = dot[q];
-        t += dpp_u32<0xB1>(t);     // lane ^ 1
-        t += dpp_u32<0x4E>(t);     // lane ^ 2
-        t += dpp_u32<0x141>(t);    // mirror inside 8 lanes: the other quad
-        d8 = sub == q ? t : d8;
-    }
-    const float4 v0 = reinterpret_cast<const float4*>(xq_s + nch)[0], v1 = reinterpret_cast<const float4*>(xq_s + nch)[1];
-    // <xq, yq> = d lo lo' + lo s' sum q' + lo' s sum q + s s' <q, q'>
-    const float dotq = (float)g.d * v0.x * m0.x + v0.x * m0.y * m0.w + m0.x * v0.y * v0.w + v0.y * m0.y * (float)d8;
-    const float slack = 2e-5f * (v1.y + m1.y);
     bool reject;
-    if (g.metric == 0) {
-        const float r = sqrtf(fmaxf(v1.x + m1.x - 2.0f * dotq - slack, 0.0f)) - (v0.z + m0.z);
+    if (l2) {
+        // sum (qx - qy)^2 in integers: exact (below 2^31 for rows of up to 4096 codes)
+        const u32 sq = (qxx + yy) - 2u * xy;
+        const float r = grid.s * sqrtf((float)sq) * (1.0f - 1e-6f) - 2.0f * grid.err;
         const float lb = r > 0.0f ? r * r : 0.0f;
         reject = lb * (1.0f - 1e-4f) > kd;
     } else {
-        // <x, y> <= <xq, yq> + err_x |yq| + |x| err_y
-        const float yn = sqrtf(m1.x);
-        const float ub = dotq + slack + (v0.z * yn + norm_v * m0.z) * 1.0001f;
-        if (g.metric == 1) reject = -ub - 1e-5f * norm_v * (yn + m0.z) > kd;
-        else reject = 1.0f - ub * v1.z * m1.z - 1e-4f > kd;
+        const float a0 = (float)g.d * grid.lo * grid.lo, a1 = grid.lo * grid.s, a2 = grid.s * grid.s;
+        const float s1 = (float)(qx1 + y1), fxy = (float)xy, fy1 = (float)y1, fyy = (float)yy;
+        const float dotq = a0 + a1 * s1 + a2 * fxy;
+        const float slack = 1e-6f * (a0 + fabsf(a1) * s1 + a2 * fxy);
+        const float yq2 = a0 + 2.0f * a1 * fy1 + a2 * fyy;
+        const float slack_y = 1e-6f * (a0 + 2.0f * fabsf(a1) * fy1 + a2 * fyy);
+        const float yq_hi = sqrtf(fmaxf(yq2 + slack_y, 0.0f)) * (1.0f + 1e-6f);
+        const float yq_lo = sqrtf(fmaxf(yq2 - slack_y, 0.0f)) * (1.0f - 1e-6f);
+        // <x, y> <= <xq, yq> + err |yq| + |x| err
+        const float ub = dotq + slack + grid.err * (yq_hi + norm_v) * 1.0001f;
+        if (g.metric == 1) {
+            reject = -ub - 1e-5f * norm_v * (yq_hi + grid.err) > kd;
+        } else {
+            // the largest cosine the bound allows: |y| is within err of |yq|
+            const float y_lo = yq_lo - grid.err, y_hi = yq_hi + grid.err;
+            const float cos_ub = ub >= 0.0f ? (y_lo > 0.0f ? ub * rn_v / y_lo * 1.0001f : __builtin_inff()) : ub * rn_v / y_hi * 0.9999f;
+            reject = 1.0f - cos_ub - 1e-4f > kd;
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -659,11 +744,31 @@ __device__ __forceinline__ void phase2_node(const TgGraph& g, int64_t v, int m, 
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
+    ScreenGrid grid = {0.0f, 1.0f, 0.0f};
+    u32 qxx = 0u, qx1 = 0u;          // sum qx qx and sum qx over v's codes
     if (SCREEN) {
+        const u32* gw = reinterpret_cast<const u32*>(g.Xqm);
+        quantize_grid(gw, grid.lo, grid.s);
+        grid.err = __uint_as_float(gw[2]);
         const int nch = g.ldq >> 4;
         const uint4* src = reinterpret_cast<const uint4*>(g.Xq + v * (int64_t)g.ldq);
-        const uint4* srcm = reinterpret_cast<const uint4*>(g.Xqm + v * 8);
-        for (int i = lane; i < nch + 2; i += 64) xq_s[i] = i < nch ? src[i] : srcm[i - nch];
+        for (int i = lane; i < nch; i += 64) {
+            const uint4 a = src[i];
+            xq_s[i] = a;
+            qxx = __builtin_amdgcn_udot4(a.x, a.x, qxx, false);
+            qxx = __builtin_amdgcn_udot4(a.y, a.y, qxx, false);
+            qxx = __builtin_amdgcn_udot4(a.z, a.z, qxx, false);
+            qxx = __builtin_amdgcn_udot4(a.w, a.w, qxx, false);
+            qx1 = __builtin_amdgcn_udot4(a.x, 0x01010101u, qx1, false);
+            qx1 = __builtin_amdgcn_udot4(a.y, 0x01010101u, qx1, false);
+            qx1 = __builtin_amdgcn_udot4(a.z, 0x01010101u, qx1, false);
+            qx1 = __builtin_amdgcn_udot4(a.w, 0x01010101u, qx1, false);
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            qxx += (u32)__shfl_xor((int)qxx, o);
+            qx1 += (u32)__shfl_xor((int)qx1, o);
+        }
     }
     for (int i = lane; i < set_words; i += 64) seen[i] = TG_SET_FREE;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -703,7 +808,7 @@ __device__ __forceinline__ void phase2_node(const TgGraph& g, int64_t v, int m, 
         int cand = drop ? -1 : (int)cid;
         if (SCREEN) {
             const float kd = tg_key_dist((u64)__builtin_amdgcn_readlane((int)(L >> 32), k - 1) << 32);
-            cand = wave_screen(g, xq_s, norm_v, cand, wscr, kd);
+            cand = wave_screen(g, grid, xq_s, qxx, qx1, norm_v, rn_v, cand, wscr, kd);
         }
         const u64 alive = __ballot(cand >= 0);
         if (alive == 0) continue;

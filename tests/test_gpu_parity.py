@@ -202,6 +202,24 @@ def test_screening_never_changes_the_graph(metric, d):
     assert out[0][2]["updates"] == out[1][2]["updates"]
 
 
+@pytest.mark.parametrize("metric", ["l2", "ip", "cosine"])
+def test_screening_never_changes_the_graph_where_it_drops_most(metric):
+    """Byte-valued data are their own codes, so the bound is as tight as it gets and nearly every candidate is
+    dropped on it: the graph must still be the one obtained by measuring every candidate, for all three metrics."""
+    X = inputs.make("C2", n=8000, d=100, comps=16)
+    Xg = torch.from_numpy(X).cuda()
+    out = []
+    for screen in (1, 0):
+        prm = knn.default_params(24, 8, metric=metric, seed=5, screen=screen)
+        ids, dist, st = knn.knn_build_ex(Xg, prm)
+        out.append((ids.cpu().numpy(), dist.cpu().numpy(), st))
+    assert (out[0][0] == out[1][0]).all() and (out[0][1] == out[1][1]).all()
+    assert out[0][2]["updates"] == out[1][2]["updates"]
+    r1 = out[0][2]["rounds_phase1"]
+    pairs, vecs = out[0][2]["join_pairs"][r1:], out[0][2]["join_vectors"][r1:]
+    assert sum(vecs) < 0.5 * sum(pairs), (pairs, vecs)          # the screen did drop candidates
+
+
 def test_screening_switches_itself_off_where_it_does_not_pay():
     """Byte-valued data: few candidates reach the fp32 evaluation in every phase-2 round.  Real-valued
     data in high dimension: most pass the 8-bit bound in the first screened round, and from the second
