@@ -251,7 +251,7 @@ static void ensure_norms(tg_knn_handle* h)
 {
     if (h->norms_done) return;
     int sp = begin_span(h, SPAN_NORMS, 0);
-    tg_launch_norms(h->g, h->stream);
+    tg_launch_norms(h->g, reinterpret_cast<uint32_t*>(h->xqm), h->stream);
     if (h->d_f16_ok) tg_launch_fill_u32(h->d_f16_ok, 1, 1u, h->stream);
     if (h->xh) tg_launch_narrow(h->g, h->xh, h->d_f16_ok, h->stream);
     end_span(h, sp);
@@ -575,7 +575,7 @@ extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int
     g.rnorm = w.take<float>(n);
     u64* partial = w.take<u64>((size_t)nq * slices * k);
     if (pad) tg_launch_pad_rows(X, n, d, xp, ld, s);
-    if (metric == 2) tg_launch_norms(g, s);
+    if (metric == 2) tg_launch_norms(g, nullptr, s);
     tg_launch_exact_knn(g.X, ld, g.nrm, g.rnorm, n, d, k, metric, query_rows, nq, out_ids, out_dist, partial, slices, s);
     int rc = launch_status("exact k-NN");
     hipError_t e = hipStreamSynchronize(s);

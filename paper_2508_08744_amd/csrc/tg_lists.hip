@@ -60,62 +60,39 @@ void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hip
 }
 
 // ---------------------------------------------------------------------------------------
-// squared norms: 16 lanes per row, float4 loads
+// squared norms: 16 lanes per row, float4 loads; workgroups walk the rows with the stride of
+// the grid.  With `range` (two words, ordered bits) the smallest and the largest value of X are
+// found on the way, for the grid of the 8-bit codes of phase 2.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X, int64_t n, int ld,
-                                                    float* __restrict__ nrm, float* __restrict__ rnorm, int64_t v0)
-{
-    int64_t row = v0 + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    int sub = threadIdx.x & 15;
-    float acc = 0.0f;
-    if (row < n) {
-        const float* x = X + row * (int64_t)ld;
-        for (int c = sub * 4; c < ld; c += 64) {
-            float4 v = *reinterpret_cast<const float4*>(x + c);
-            acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        }
-    }
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    acc += __shfl_xor(acc, 8);
-    if (row < n && sub == 0) {
-        nrm[row] = acc;
-        if (rnorm) rnorm[row] = 1.0f / sqrtf(acc);
-    }
-}
-void tg_launch_norms(const TgGraph& g, hipStream_t s)
-{
-    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-        hipLaunchKernelGGL(norms_kernel, dim3((unsigned)((cnt + 15) / 16)), dim3(256), 0, s, g.X, g.n, g.ld, g.nrm,
-                           g.metric == 2 ? g.rnorm : (float*)nullptr, v0);
-    });
-}
-
-// ---------------------------------------------------------------------------------------
-// 8-bit screening copy of X for phase 2.  One grid for the whole data set: lo = the smallest value
-// of X, s = (the largest - lo) / 255; row x becomes the codes q_i = round((x_i - lo) / s) in 0..255,
-// i.e. the vector xq_i = lo + s q_i.  Then |xq - yq|^2 = s^2 sum (qx_i - qy_i)^2 and <xq, yq> follow
-// from integer dot products of the codes alone (nothing but the codes has to be fetched for a
-// candidate), and |x - y| >= |xq - yq| - 2 err bounds the true distance from below, err being the
-// largest |x - xq| of any row.  Byte-valued data have lo = 0, s = 1 and err = 0: the bound is the distance.
-// grid: [0] ordered bits of lo, [1] of the largest value, [2] float bits of err.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void quantize_range_kernel(TgGraph g, u32* __restrict__ grid)
+__global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X, int64_t n, int d, int ld,
+                                                    float* __restrict__ nrm, float* __restrict__ rnorm, u32* __restrict__ range)
 {
     __shared__ u32 s_lo[16], s_hi[16];
     const int sub = threadIdx.x & 15;
     float lo = __builtin_inff(), hi = -__builtin_inff();
-    for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < g.n; row += (int64_t)gridDim.x * 16) {
-        const float* x = g.X + row * (int64_t)g.ld;
-        for (int c = sub * 4; c < g.ld; c += 64) {
+    for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < n; row += (int64_t)gridDim.x * 16) {
+        const float* x = X + row * (int64_t)ld;
+        float acc = 0.0f;
+        for (int c = sub * 4; c < ld; c += 64) {
             const float4 v = *reinterpret_cast<const float4*>(x + c);
-            const float e[4] = {v.x, v.y, v.z, v.w};
+            acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            if (range) {
+                const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (c + i < g.d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }
+                for (int i = 0; i < 4; ++i)
+                    if (c + i < d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }       // padding columns are no values
+            }
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        acc += __shfl_xor(acc, 4);
+        acc += __shfl_xor(acc, 8);
+        if (sub == 0) {
+            nrm[row] = acc;
+            if (rnorm) rnorm[row] = 1.0f / sqrtf(acc);
         }
     }
+    if (!range) return;
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) {
         lo = fminf(lo, __shfl_xor(lo, o));
@@ -126,10 +103,30 @@ __global__ __launch_bounds__(256) void quantize_range_kernel(TgGraph g, u32* __r
     if (threadIdx.x == 0) {
         u32 a = s_lo[0], b = s_hi[0];
         for (int i = 1; i < 16; ++i) { a = min(a, s_lo[i]); b = max(b, s_hi[i]); }
-        atomicMin(grid + 0, a);
-        atomicMax(grid + 1, b);
+        atomicMin(range + 0, a);
+        atomicMax(range + 1, b);
     }
 }
+void tg_launch_norms(const TgGraph& g, uint32_t* range, hipStream_t s)
+{
+    if (range) {
+        tg_launch_fill_u32(range + 0, 1, 0xFF800000u, s);      // ordered +infinity: the smallest value so far
+        tg_launch_fill_u32(range + 1, 1, 0x007FFFFFu, s);      // ordered -infinity
+    }
+    const int64_t wgs = (g.n + 15) / 16;
+    hipLaunchKernelGGL(norms_kernel, dim3((unsigned)(wgs < 2048 ? wgs : 2048)), dim3(256), 0, s, g.X, g.n, g.d, g.ld, g.nrm,
+                       g.metric == 2 ? g.rnorm : (float*)nullptr, range);
+}
+
+// ---------------------------------------------------------------------------------------
+// 8-bit screening copy of X for phase 2.  One grid for the whole data set: lo = the smallest value
+// of X, s = (the largest - lo) / 255; row x becomes the codes q_i = round((x_i - lo) / s) in 0..255,
+// i.e. the vector xq_i = lo + s q_i.  Then |xq - yq|^2 = s^2 sum (qx_i - qy_i)^2 and <xq, yq> follow
+// from integer dot products of the codes alone (nothing but the codes has to be fetched for a
+// candidate), and |x - y| >= |xq - yq| - 2 err bounds the true distance from below, err being the
+// largest |x - xq| of any row.  Byte-valued data have lo = 0, s = 1 and err = 0: the bound is the distance.
+// grid: [0] ordered bits of lo, [1] of the largest value (both found by the kernel of the norms), [2] float bits of err.
+// ---------------------------------------------------------------------------------------
 // lo and s of the grid from its first two words (the same expressions wherever they are needed)
 __device__ inline void quantize_grid(const u32* grid, float& lo, float& s)
 {
@@ -189,12 +186,10 @@ __global__ __launch_bounds__(256) void quantize_kernel(TgGraph g, uint8_t* __res
 }
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s)
 {
+    // the first two words of the grid (smallest and largest value of X) were found together with the norms
     u32* grid = reinterpret_cast<u32*>(Xqm);
-    tg_launch_fill_u32(grid + 0, 1, 0xFF800000u, s);      // ordered +infinity: the smallest value so far
-    tg_launch_fill_u32(grid + 1, 1, 0x007FFFFFu, s);      // ordered -infinity
     tg_launch_fill_u32(grid + 2, 1, 0u, s);
     const int64_t range_wgs = (g.n + 15) / 16;
-    hipLaunchKernelGGL(quantize_range_kernel, dim3((unsigned)(range_wgs < 2048 ? range_wgs : 2048)), dim3(256), 0, s, g, grid);
     hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)(range_wgs < 2048 ? range_wgs : 2048)), dim3(256), 0, s, g, Xq, grid);
 }
 
