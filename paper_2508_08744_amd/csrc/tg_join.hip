@@ -14,7 +14,7 @@
 #include "tg_kernels.h"
 
 #define JOIN_THREADS 256
-#define JOIN_HDR_BYTES 2560   // salt[128], kd[128], kid[128], ids[128], aux[128]
+#define JOIN_HDR_BYTES 2560   // salt[128], kd[128], spare[128], ids[128], aux[128]
 #define JOIN_CELL_BYTES (TG_BLOCK_COLS * 8 * 8)   // one cell per member and opponent group (workgroup kernel)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -79,10 +79,12 @@ __device__ inline float gram_to_dist(float gram, float aux_a, float aux_b)
     if (METRIC == 1) return -gram + 0.0f;
     return 1.0f - gram * (aux_a * aux_b) + 0.0f;   // symmetric in the two nodes, bit for bit
 }
-// (dist, id) precedes the target's last list entry (kd, kid)?
-__device__ inline bool precedes(float dist, u32 id, float kd, u32 kid)
+// May a candidate at this distance precede the target's last list entry, whose distance is kd?  The id of
+// that entry is not looked at: a candidate at exactly kd with a larger id passes too, and the list update,
+// which keeps the k smallest (distance, id), drops it again; nothing that belongs in the list is held back.
+__device__ inline bool reaches(float dist, float kd)
 {
-    return (dist < kd) | ((dist == kd) & (id < kid));
+    return dist <= kd;
 }
 
 // Candidate c of the member at block position tpos (node t), found by anchor v's block in
@@ -116,8 +118,7 @@ __global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(
     extern __shared__ __align__(16) unsigned char smem_raw[];
     u32* s_salt = reinterpret_cast<u32*>(smem_raw);                     // slot-hash salt of each member
     float* s_kd = reinterpret_cast<float*>(s_salt + TG_BLOCK_COLS);     // threshold: distance of the member's last entry
-    u32* s_kid = reinterpret_cast<u32*>(s_kd + TG_BLOCK_COLS);          //            and its id
-    int* s_ids = reinterpret_cast<int*>(s_kid + TG_BLOCK_COLS);
+    int* s_ids = reinterpret_cast<int*>(s_kd + 2 * TG_BLOCK_COLS);     // (128 words behind the thresholds are spare)
     float* s_aux = reinterpret_cast<float*>(s_ids + TG_BLOCK_COLS);     // squared norm (or 1/|x| for cosine)
     u64* s_cell = reinterpret_cast<u64*>(smem_raw + JOIN_HDR_BYTES);   // candidates of the block in hand
     unsigned char* tile = smem_raw + JOIN_HDR_BYTES + JOIN_CELL_BYTES;
@@ -191,11 +192,10 @@ __global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(
     if (tid < nT) {
         const int id = (int)bids[tid];
         s_ids[tid] = id;
-        s_aux[tid] = g.metric == 2 ? g.rnorm[id] : g.nrm[id];
+        s_aux[tid] = (MODE == 0) ? __uint_as_float((u32)g.kth[id]) : (g.metric == 2 ? g.rnorm[id] : g.nrm[id]);
         if (MODE == 0) {
-            const u64 kth = g.kth[id];
+            const u64 kth = g.kth[id];                       // threshold distance and norm in one word
             s_kd[tid] = tg_unord((u32)(kth >> 32));
-            s_kid[tid] = ((u32)kth) >> 2;
             s_salt[tid] = (u32)tg_mix64(hs_slot + (u64)id);
         }
     }
@@ -297,14 +297,14 @@ __global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(
         if (i >= MT) continue;
         // per-lane row data for e = 0..3
         float aux_a[4], kd_a[4];
-        u32 id_a[4], kid_a[4];
+        u32 id_a[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int a = 16 * i + 4 * g4 + e;
             const int aa = a < nN ? a : 0;
             aux_a[e] = s_aux[aa];
             id_a[e] = (u32)s_ids[aa];
-            if (MODE == 0) { kd_a[e] = s_kd[aa]; kid_a[e] = s_kid[aa]; }
+            if (MODE == 0) kd_a[e] = s_kd[aa];
         }
 #pragma unroll
         for (int cg = 0; cg < NGC / 2; ++cg) {
@@ -322,7 +322,6 @@ __global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(
                 const float aux_b = s_aux[bb];
                 const u32 id_b = (u32)s_ids[bb];
                 const float kd_b = MODE == 0 ? s_kd[bb] : 0.f;
-                const u32 kid_b = MODE == 0 ? s_kid[bb] : 0u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int a = 16 * i + 4 * g4 + e;
@@ -336,8 +335,8 @@ __global__ __launch_bounds__(JOIN_THREADS, ROWS <= 64 ? 3 : 2) void join_kernel(
                     } else {
                         // row node a meets column node b: b is a candidate of a and a of b, each
                         // only if it would precede the last entry of the target's list
-                        const bool pr = ok & precedes(dist, id_b, kd_a[e], kid_a[e]);
-                        const bool pc = ok & precedes(dist, id_a[e], kd_b, kid_b);
+                        const bool pr = ok & reaches(dist, kd_a[e]);
+                        const bool pc = ok & reaches(dist, kd_b);
                         pairmin(rbd[e], rbi[e], pr ? dist : INF, pr ? id_b : TG_NO_ID);
                         pairmin(cbd[tj][ti & (NGR / 2 - 1)], cbi[tj][ti & (NGR / 2 - 1)], pc ? dist : INF, pc ? id_a[e] : TG_NO_ID);
                     }
@@ -418,7 +417,6 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 {
     __shared__ u32 sh_salt[4][2][64];
     __shared__ u32 sh_okd[4][2][64];
-    __shared__ u32 sh_kid[4][2][64];
     __shared__ int sh_ids[4][2][64];
     __shared__ float sh_aux[4][2][64];
     // candidates of one block, one cell per (member, partner group); handed over a block later
@@ -485,13 +483,22 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         }
     };
     // per-member data (one member per lane): fetched into registers, parked in LDS one block ahead
+    // the threshold of a member's list and its norm come in one word (MODE 1 has no lists: the norm alone)
+    auto fetch_member = [&](int id, float& aux, u64& kth) {
+        if (MODE == 0) {
+            kth = g.kth[id];
+            aux = __uint_as_float((u32)kth);
+        } else {
+            kth = 0ull;
+            aux = METRIC == 2 ? g.rnorm[id] : g.nrm[id];
+        }
+    };
     auto park_member = [&](const WaveItem& it, int id, float aux, u64 kth, int buf) {
         if (lane < it.nT) {
             sh_ids[wave][buf][lane] = id;
             sh_aux[wave][buf][lane] = aux;
             if (MODE == 0) {
                 sh_okd[wave][buf][lane] = (u32)(kth >> 32);
-                sh_kid[wave][buf][lane] = ((u32)kth) >> 2;
                 sh_salt[wave][buf][lane] = (u32)tg_mix64(hs_slot + (u64)id);
             }
         }
@@ -542,7 +549,10 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
 #pragma unroll
         for (int t = 0; t < GMAX; ++t) load_group(t, idr[t]);
         const int m0 = (int)cur.bids[lane < cur.nT ? lane : 0];
-        park_member(cur, m0, METRIC == 2 ? g.rnorm[m0] : g.nrm[m0], MODE == 0 ? g.kth[m0] : 0ull, 0);
+        float a0;
+        u64 k0;
+        fetch_member(m0, a0, k0);
+        park_member(cur, m0, a0, k0, 0);
         fetch_row_ids(nxt, idn);
         mid = (int)nxt.bids[lane < nxt.nT ? lane : 0];
     }
@@ -564,7 +574,6 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const u32* s_okd = sh_okd[wave][buf];
-        const u32* s_kid = sh_kid[wave][buf];
         const int* s_ids = sh_ids[wave][buf];
         const float* s_aux = sh_aux[wave][buf];
         const int64_t v = cur.v;
@@ -604,7 +613,6 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                 // the lane that will speak for row 16 i + 4 q4 + (r16 & 3) keeps that row's threshold
                 const int a_mine = 16 * i + 4 * q4 + (r16 & 3);
                 const u32 okd_mine = MODE == 0 ? s_okd[a_mine < nN ? a_mine : 0] : 0u;
-                const u32 kid_mine = MODE == 0 ? s_kid[a_mine < nN ? a_mine : 0] : 0u;
 #pragma unroll
                 for (int j = i; j < GMAX; ++j) {
                     if (j >= NT) continue;
@@ -657,7 +665,8 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         const int e_mine = r16 & 3;
                         const u32 mo = e_mine == 0 ? ro[0] : e_mine == 1 ? ro[1] : e_mine == 2 ? ro[2] : ro[3];
                         const u32 mi = e_mine == 0 ? ri[0] : e_mine == 1 ? ri[1] : e_mine == 2 ? ri[2] : ri[3];
-                        if (r16 < 4 && ((mo < okd_mine) | ((mo == okd_mine) & (mi < kid_mine))))
+                        // (at the threshold's own distance a candidate passes whatever its id: the list update sorts that out)
+                        if (r16 < 4 && mo <= okd_mine)
                             atomicMin(cells + a_mine * GMAX + j, ((u64)mo << 32) | (u64)((mi << 2) | 3u));
                         // Column node b: closest row node of the tile over the lane's four rows.
                         u64 cb = ((u64)o[0] << 32) | id_a[0];
@@ -665,15 +674,14 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         for (int e = 1; e < 4; ++e) cb = tg_min64(cb, ((u64)o[e] << 32) | id_a[e]);
                         // (the four row quarters meet in the cell: it takes the minimum)
                         const u32 co = (u32)(cb >> 32), ci = (u32)cb;
-                        if ((co < okd_b) | ((co == okd_b) & (ci < s_kid[bb])))
+                        if (co <= okd_b)
                             atomicMin(cells + b * GMAX + i, ((u64)co << 32) | (u64)((ci << 2) | 3u));
                     }
                 }
             }
             if (i == 0) {
                 // the next block's ids have arrived behind the first tile row: ask for its norms and thresholds
-                m_aux = METRIC == 2 ? g.rnorm[mid] : g.nrm[mid];
-                m_kth = MODE == 0 ? g.kth[mid] : 0ull;
+                fetch_member(mid, m_aux, m_kth);
             }
             // Row group i is used by tile rows min(i, MT - 1) and earlier: once tile row i is done
             // (and it is not the last one) its registers can take in the next block.

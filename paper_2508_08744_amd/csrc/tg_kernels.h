@@ -30,7 +30,8 @@ struct TgGraph {
     uint32_t* gid;    // n x k list words of the current round: id | fresh << 31
     uint32_t* gid_next; // n x k, written by a phase-2 round; in phase 1 it holds the arrival number of every sampled edge
     float* gdist;     // n x k
-    unsigned long long* kth;   // n: key of each list's last entry with both low bits set
+    unsigned long long* kth;   // n: what the join needs of a node besides its vector: ordered distance of its list's last entry
+                               // (high word), bits of its squared norm, or inverse norm for cosine (low word)
     const uint8_t* Xq;  // n x ldq bytes: 8-bit codes of every row (phase-2 screening), or null
     const float* Xqm;   // the grid of the codes, three words: ordered bits of the smallest and of the largest value of X, float
                         // bits of the largest distance of a row from its grid point

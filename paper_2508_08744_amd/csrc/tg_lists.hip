@@ -470,6 +470,14 @@ __device__ inline int wave_screen(const TgGraph& g, const ScreenGrid& grid, cons
     return (mine && !reject) ? (int)row : -1;
 }
 
+// What the join needs of node v besides its vector, in one word: the ordered distance of the list's last
+// entry above, the bits of the node's squared norm (inverse norm for cosine) below.
+__device__ inline float join_aux(const TgGraph& g, int64_t v) { return g.metric == 2 ? g.rnorm[v] : g.nrm[v]; }
+__device__ inline u64 join_word(float aux, u64 last_key)
+{
+    return (last_key & 0xFFFFFFFF00000000ull) | (u64)__float_as_uint(aux);
+}
+
 // stage row v of X into this wave's LDS slice
 __device__ inline void stage_row(const TgGraph& g, int64_t v, float* xs)
 {
@@ -515,6 +523,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
     if (v >= g.n) return;
     float* xs = smem + (size_t)wave * g.ld;
     u32* wscr = reinterpret_cast<u32*>(smem + (size_t)LISTS_WAVES * g.ld) + wave * 128;
+    const float aux_v = join_aux(g, v);          // asked for now, needed at the end
     stage_row(g, v, xs);
 
     int cnt = 0;
@@ -545,7 +554,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
     if (lane < g.k) {
         g.gid[v * g.k + lane] = tg_key_id(key) | 0x80000000u;
         g.gdist[v * g.k + lane] = tg_key_dist(key);
-        if (lane == g.k - 1) g.kth[v] = key | 3ull;
+        if (lane == g.k - 1) g.kth[v] = join_word(aux_v, key);
     }
     if (deg) number_sampled_edges(v, g.k, S, tg_key_id(key), true, deg, g.gid_next);
 }
@@ -606,6 +615,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
+    const float aux_v = join_aux(g, v);          // asked for now, needed at the end
     // all filled slots of v, closed up in LDS (the slots are handed back empty)
     const u64 lt = tg_lanemask_lt();
     int nq = 0;
@@ -675,7 +685,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     if (lane < k) {
         g.gid[v * k + lane] = tg_key_id(L) | (((u32)L & 1u) << 31);
         g.gdist[v * k + lane] = tg_key_dist(L);
-        if (lane == k - 1) g.kth[v] = L | 3ull;
+        if (lane == k - 1) g.kth[v] = join_word(aux_v, L);
     }
     if (ins && lane == 0) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
 }
@@ -739,6 +749,7 @@ __device__ __forceinline__ void phase2_node(const TgGraph& g, int64_t v, int m, 
         w = g.gid[v * k + lane];
         dist = g.gdist[v * k + lane];
     }
+    const float aux_v = join_aux(g, v);          // asked for now, needed at the end
     ScreenGrid grid = {0.0f, 1.0f, 0.0f};
     u32 qxx = 0u, qx1 = 0u;          // sum qx qx and sum qx over v's codes
     if (SCREEN) {
@@ -838,7 +849,7 @@ __device__ __forceinline__ void phase2_node(const TgGraph& g, int64_t v, int m, 
     if (lane < k) {
         g.gid_next[v * k + lane] = tg_key_id(L) | (((u32)L & 1u) << 31);
         g.gdist[v * k + lane] = tg_key_dist(L);
-        if (lane == k - 1) g.kth[v] = L | 3ull;
+        if (lane == k - 1) g.kth[v] = join_word(aux_v, L);
     }
     if (lane == 0) {
         if (ins) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
@@ -989,7 +1000,7 @@ __global__ void import_kernel(TgGraph g, const int32_t* ids, const float* dist, 
     for (; i < count; i += stride) {
         g.gid[i] = (u32)ids[i] | ((u32)(fresh[i] != 0) << 31);
         g.gdist[i] = dist[i];
-        if ((int)(i % g.k) == g.k - 1) g.kth[i / g.k] = tg_key(dist[i], (u32)ids[i], 3u);
+        if ((int)(i % g.k) == g.k - 1) g.kth[i / g.k] = join_word(join_aux(g, (int64_t)(i / g.k)), tg_key(dist[i], (u32)ids[i], 3u));
     }
 }
 void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s)
