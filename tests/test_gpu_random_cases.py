@@ -143,6 +143,27 @@ def test_whole_build_random_cases():
         assert (dist.cpu().numpy().astype(np.float64) == od).all(), where
 
 
+@pytest.mark.parametrize("metric", ["l2", "ip"])               # the two metrics whose fp32 arithmetic is exact on integers
+def test_whole_build_with_ties_everywhere(metric):
+    """A few values in a few dimensions: many points coincide and most distances are shared by many pairs, so nearly
+    every threshold is met exactly by candidates with smaller and with larger ids.  The join lets a candidate at the
+    threshold's own distance through whatever its id and leaves the rest to the list update; the lists must still be
+    the oracle's, entry by entry, after every kind of round."""
+    rng = np.random.default_rng(31)
+    for n, d, k, vals in ((900, 2, 8, 6), (1500, 3, 20, 4), (700, 5, 33, 3)):
+        X = rng.integers(1, 1 + vals, size=(n, d)).astype(np.float32)
+        for it1, it2 in ((3, 0), (2, 2)):
+            prm = knn.default_params(k, 4, metric=metric, seed=7, it1=it1, it2=it2, C=128)
+            ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+            o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row,
+                                 ng_col=prm.ng_col, m=prm.m, seed=7)
+            o.run(it1, it2)
+            oi, od, _ = o.graph()
+            where = dict(n=n, d=d, k=k, it1=it1, it2=it2)
+            assert (ids.cpu().numpy() == oi).all(), where
+            assert (dist.cpu().numpy().astype(np.float64) == od).all(), where
+
+
 @pytest.mark.parametrize("d,join_f16", [(4096, 0), (4096, 1), (4093, 0), (2050, 2)])
 def test_longest_rows(d, join_f16):
     """Rows at the documented maximum length (and just below, unaligned): the whole build against the oracle."""
