@@ -18,6 +18,12 @@
  *     thread's last failure.  On TG_ERR_INVALID_ARG outputs are untouched.
  *   - Distances: TG_METRIC_L2 is the squared Euclidean distance, TG_METRIC_IP is
  *     -<x,y>, TG_METRIC_COSINE is 1 - <x,y>/(|x||y|)  (the paper leaves "dis" open).
+ *     X is expected to hold finite numbers whose squared norms are finite, and no all-zero
+ *     row under TG_METRIC_COSINE.  Rows without a defined distance are not refused (the
+ *     calls only enqueue work) but counted: tg_knn_stats.undefined_rows.  When it is not
+ *     0 the lists are unspecified (such a row can pose as everyone's nearest neighbour),
+ *     though every list still holds ids in [0, n), never its own node and no id twice:
+ *     no distance is ever turned into an index.
  *   - Lists are ordered by (distance, id) ascending; a list never holds its own node
  *     or the same id twice.
  */
@@ -105,6 +111,7 @@ typedef struct tg_knn_stats {
     float ms_update[TG_MAX_ROUNDS];      /* list update kernel (phase 1)                            */
     double join_pairs[TG_MAX_ROUNDS];    /* pairs the join of round r had to evaluate               */
     double join_vectors[TG_MAX_ROUNDS];  /* vectors the join of round r had to gather               */
+    int64_t undefined_rows;              /* rows of X without a defined distance (see "Distances"): 0 for valid input */
 } tg_knn_stats;
 
 typedef struct tg_knn_handle tg_knn_handle;

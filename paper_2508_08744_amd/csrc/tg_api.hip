@@ -99,6 +99,7 @@ struct tg_knn_handle {
     uint8_t* xq;         // 8-bit screening copy of X, written when phase 2 begins
     float* xqm;          // its grid (three words, see TgGraph)
     u32* d_screen_on;    // device flag: screening still pays (decided after each screened round)
+    u32* d_undefined;    // device counter: rows of X without a defined distance (written with the norms)
     uint16_t* xh;        // fp16 copy of X for the local join (join_f16 = 1, 2)
     u32* d_f16_ok;       // join_f16 = 2: device flag, 1 while every value of X is an fp16 number
     int round;           // rounds run so far (both phases)
@@ -137,6 +138,7 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
     h->d_screen_on = c.take<u32>(64);
+    h->d_undefined = h->d_screen_on + 32;        // a word of its own line in the same 256 bytes
     // the register-resident join reads 64, 96 or 128 columns per row (4, 6 or 8 steps of 16); longer rows are whole steps of 32
     h->g.ldh = ld <= 64 ? 64 : ld <= 96 ? 96 : ld <= 128 ? 128 : (d + 31) & ~31;
     h->xh = p.join_f16 ? c.take<uint16_t>((size_t)n * h->g.ldh) : nullptr;
@@ -251,7 +253,7 @@ static void ensure_norms(tg_knn_handle* h)
 {
     if (h->norms_done) return;
     int sp = begin_span(h, SPAN_NORMS, 0);
-    tg_launch_norms(h->g, reinterpret_cast<uint32_t*>(h->xqm), h->stream);
+    tg_launch_norms(h->g, reinterpret_cast<uint32_t*>(h->xqm), h->d_undefined, h->stream);
     if (h->d_f16_ok) tg_launch_fill_u32(h->d_f16_ok, 1, 1u, h->stream);
     if (h->xh) tg_launch_narrow(h->g, h->xh, h->d_f16_ok, h->stream);
     end_span(h, sp);
@@ -371,6 +373,11 @@ extern "C" int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out)
     HIP_TRY(hipStreamSynchronize(h->stream));
     out->rounds_phase1 = h->rounds1;
     out->rounds_phase2 = h->rounds2;
+    if (h->norms_done) {
+        u32 bad = 0;
+        HIP_TRY(hipMemcpy(&bad, h->d_undefined, sizeof(bad), hipMemcpyDeviceToHost));
+        out->undefined_rows = (int64_t)bad;
+    }
     if (h->round > 0) {
         std::vector<u64> upd((size_t)h->round * TG_STAT_BINS);
         HIP_TRY(hipMemcpy(upd.data(), h->d_updates, upd.size() * sizeof(u64), hipMemcpyDeviceToHost));
@@ -575,7 +582,7 @@ extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int
     g.rnorm = w.take<float>(n);
     u64* partial = w.take<u64>((size_t)nq * slices * k);
     if (pad) tg_launch_pad_rows(X, n, d, xp, ld, s);
-    if (metric == 2) tg_launch_norms(g, nullptr, s);
+    if (metric == 2) tg_launch_norms(g, nullptr, nullptr, s);
     tg_launch_exact_knn(g.X, ld, g.nrm, g.rnorm, n, d, k, metric, query_rows, nq, out_ids, out_dist, partial, slices, s);
     int rc = launch_status("exact k-NN");
     hipError_t e = hipStreamSynchronize(s);

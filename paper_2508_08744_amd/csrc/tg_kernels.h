@@ -60,7 +60,8 @@ struct TgCand {
     unsigned long long* slots;   // n x C keys, TG_EMPTY_KEY when free
 };
 
-void tg_launch_norms(const TgGraph& g, uint32_t* range, hipStream_t s);   // range: two words for the smallest and largest value of X, or NULL
+// range: two words for the smallest and largest value of X, or NULL; undefined: one word that counts the rows without a defined distance, or NULL
+void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hipStream_t s);
 void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges /* or null */, hipStream_t s);
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s);
 void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag /* cleared when a value is no fp16 number, or null */,

@@ -62,10 +62,13 @@ void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hip
 // ---------------------------------------------------------------------------------------
 // squared norms: 16 lanes per row, float4 loads; workgroups walk the rows with the stride of
 // the grid.  With `range` (two words, ordered bits) the smallest and the largest value of X are
-// found on the way, for the grid of the 8-bit codes of phase 2.
+// found on the way, for the grid of the 8-bit codes of phase 2.  With `undefined`, rows that have no
+// defined distance are counted there: a squared norm that is not a finite number (an infinite or
+// undefined value in the row, or an overflow), and a zero norm where the reciprocal is asked for.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X, int64_t n, int d, int ld,
-                                                    float* __restrict__ nrm, float* __restrict__ rnorm, u32* __restrict__ range)
+                                                    float* __restrict__ nrm, float* __restrict__ rnorm, u32* __restrict__ range,
+                                                    u32* __restrict__ undefined)
 {
     __shared__ u32 s_lo[16], s_hi[16];
     const int sub = threadIdx.x & 15;
@@ -90,6 +93,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
         if (sub == 0) {
             nrm[row] = acc;
             if (rnorm) rnorm[row] = 1.0f / sqrtf(acc);
+            if (undefined && (!(acc < __builtin_inff()) || (rnorm && !(acc > 0.0f)))) atomicAdd(undefined, 1u);
         }
     }
     if (!range) return;
@@ -107,15 +111,16 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
         atomicMax(range + 1, b);
     }
 }
-void tg_launch_norms(const TgGraph& g, uint32_t* range, hipStream_t s)
+void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hipStream_t s)
 {
+    if (undefined) tg_launch_fill_u32(undefined, 1, 0u, s);
     if (range) {
         tg_launch_fill_u32(range + 0, 1, 0xFF800000u, s);      // ordered +infinity: the smallest value so far
         tg_launch_fill_u32(range + 1, 1, 0x007FFFFFu, s);      // ordered -infinity
     }
     const int64_t wgs = (g.n + 15) / 16;
     hipLaunchKernelGGL(norms_kernel, dim3((unsigned)(wgs < 2048 ? wgs : 2048)), dim3(256), 0, s, g.X, g.n, g.d, g.ld, g.nrm,
-                       g.metric == 2 ? g.rnorm : (float*)nullptr, range);
+                       g.metric == 2 ? g.rnorm : (float*)nullptr, range, undefined);
 }
 
 // ---------------------------------------------------------------------------------------

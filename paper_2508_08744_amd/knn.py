@@ -31,7 +31,8 @@ class Stats(ctypes.Structure):
                 ("ms_norms", ctypes.c_float), ("ms_init", ctypes.c_float), ("ms_finalize", ctypes.c_float),
                 ("ms_sample", ctypes.c_float * TG_MAX_ROUNDS), ("ms_join", ctypes.c_float * TG_MAX_ROUNDS),
                 ("ms_update", ctypes.c_float * TG_MAX_ROUNDS),
-                ("join_pairs", ctypes.c_double * TG_MAX_ROUNDS), ("join_vectors", ctypes.c_double * TG_MAX_ROUNDS)]
+                ("join_pairs", ctypes.c_double * TG_MAX_ROUNDS), ("join_vectors", ctypes.c_double * TG_MAX_ROUNDS),
+                ("undefined_rows", ctypes.c_int64)]
 
     def as_dict(self):
         r = self.rounds_phase1 + self.rounds_phase2
@@ -39,7 +40,7 @@ class Stats(ctypes.Structure):
                     updates=list(self.updates[:r]), ms_norms=self.ms_norms, ms_init=self.ms_init,
                     ms_finalize=self.ms_finalize, ms_sample=list(self.ms_sample[:r]), ms_join=list(self.ms_join[:r]),
                     ms_update=list(self.ms_update[:r]), join_pairs=list(self.join_pairs[:r]),
-                    join_vectors=list(self.join_vectors[:r]))
+                    join_vectors=list(self.join_vectors[:r]), undefined_rows=self.undefined_rows)
 
 
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",

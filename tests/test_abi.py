@@ -132,3 +132,26 @@ def test_binding_refuses_host_tensors():
         knn.prune_rank(ids, 2)
     with pytest.raises((TypeError, ValueError)):
         knn.merge_local(ids, X[:, :4].contiguous(), ids, X[:, :4].contiguous(), torch.arange(100, dtype=torch.int32))
+
+
+def test_binding_structures_match_the_header(tmp_path):
+    """The ctypes mirrors of tg_knn_params and tg_knn_stats have the header's sizes and field offsets
+    (a C program compiled against include/tagore_knn.h prints them)."""
+    import subprocess
+    from paper_2508_08744_amd import knn
+    src = tmp_path / "layout.c"
+    fields_p = [f for f, _ in knn.Params._fields_]
+    fields_s = [f for f, _ in knn.Stats._fields_]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "tagore_knn.h"', 'int main(void) {',
+             'printf("%zu %zu\\n", sizeof(tg_knn_params), sizeof(tg_knn_stats));']
+    lines += ['printf("%%zu\\n", offsetof(tg_knn_params, %s));' % f for f in fields_p]
+    lines += ['printf("%%zu\\n", offsetof(tg_knn_stats, %s));' % f for f in fields_s]
+    lines += ['return 0; }']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(out[0]), int(out[1])] == [ctypes.sizeof(knn.Params), ctypes.sizeof(knn.Stats)]
+    want = [getattr(knn.Params, f).offset for f in fields_p] + [getattr(knn.Stats, f).offset for f in fields_s]
+    assert [int(x) for x in out[2:]] == want

@@ -404,6 +404,35 @@ def test_duplicate_points():
     _check_properties(X, ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64))
 
 
+@pytest.mark.parametrize("metric", ["l2", "ip", "cosine"])
+def test_rows_without_a_defined_distance_are_counted_and_leave_valid_lists(metric):
+    """Zero rows under the cosine distance (0 / 0) and rows with infinite or undefined values have no
+    defined distances.  The build counts them (stats: undefined_rows) instead of refusing them; the lists
+    are then unspecified, but no distance ever becomes an index, so every list still holds ids in range,
+    never its own node and no id twice, and the call succeeds."""
+    n, k = 3000, 16
+    X = inputs.make("C4", n=n, d=24, comps=6)
+    prm = knn.default_params(k, 6, metric=metric, seed=4)
+    _, _, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    assert st["undefined_rows"] == 0
+    X[5::97] = 0.0                                   # no direction
+    X[11::211, 3] = np.inf
+    X[17::223, 7] = -np.inf
+    X[23::227, 0] = np.nan
+    X[29::229, 1] = 3e19                             # a finite value whose square is not
+    with np.errstate(over="ignore", invalid="ignore"):
+        bad = ~np.isfinite((X.astype(np.float64) ** 2).sum(axis=1).astype(np.float32))
+    if metric == "cosine":
+        bad |= (X == 0).all(axis=1)
+    ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    assert st["undefined_rows"] == bad.sum() > 0
+    ids = ids.cpu().numpy()
+    assert ids.shape == (n, k) and (ids >= 0).all() and (ids < n).all()
+    assert (ids != np.arange(n)[:, None]).all()
+    s = np.sort(ids, axis=1)
+    assert (s[:, 1:] != s[:, :-1]).all()
+
+
 def test_set_graph_round_trip_and_stream():
     X = inputs.make("C2", n=800, d=20, comps=2)
     prm = knn.default_params(12, 4, seed=6)
