@@ -46,6 +46,15 @@ def test_padding_duplicates_and_bad_arguments():
     ids[rows, 5] = ids[rows, 2]                                            # an id listed twice
     ids[:50, 3] = np.arange(50)                                            # a node in its own row
     _check(ids, 9)
+    # few nodes: every row shares most of its ids with every other, so repeats, own ids, padding and ids
+    # without a row all sit where detours are counted
+    for n2, k2, seed in ((40, 16, 1), (24, 20, 2), (70, 33, 3), (100, 64, 4)):
+        r2 = np.random.default_rng(seed)
+        dense = r2.integers(0, n2, (n2, k2)).astype(np.int32)              # with repeats and own ids
+        dense[r2.random((n2, k2)) < 0.05] = -1
+        dense[r2.random((n2, k2)) < 0.05] = n2 + 7
+        _check(dense, max(1, k2 // 2))
+        _check(dense, k2)
     t = torch.from_numpy(ids).cuda()
     for bad in (0, k + 1):
         with pytest.raises(knn.TagoreError):

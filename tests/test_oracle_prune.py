@@ -92,3 +92,38 @@ def test_selection_order_ties_and_invalid_ids():
     assert cnt2[0, 3] == 0
     with pytest.raises(ValueError):
         oracle.prune_rank(ids, 5)
+
+
+def test_hand_made_rows_reordering_repeats_self_and_ids_without_a_row():
+    """Counts and the kept order worked out by hand from the definition (a detour of (A, F), F at position p,
+    is a node in front of p in A's row and in front of p in F's row)."""
+    n, k = 12, 4
+    filler = [8, 9, 10, 11]
+    ids = np.array([filler] * n, dtype=np.int32)
+    # A = 0: node 3 (position 2) has both closer neighbours in front of its own row: two detours; node 4 none
+    ids[0] = [1, 2, 3, 4]
+    ids[3] = [1, 2, 8, 9]
+    out, cnt = oracle.prune_rank(ids, 3)
+    assert cnt[0].tolist() == [0, 0, 2, 0]
+    assert out[0].tolist() == [1, 2, 4]                      # the farther node with fewer detours goes first
+    full, _ = oracle.prune_rank(ids, 4)
+    assert full[0].tolist() == [1, 2, 4, 3]
+    # a neighbour shared only at or behind F's position is no detour: node 4 lists 3 too late, node 2 lists 1 in time
+    ids[4] = [8, 9, 10, 3]
+    ids[2] = [1, 8, 9, 10]
+    _, cnt = oracle.prune_rank(ids, 4)
+    assert cnt[0].tolist() == [0, 1, 2, 0]
+    # F's row names F itself: F is not in front of its own position in A's row
+    ids[4] = [4, 8, 9, 10]
+    _, cnt = oracle.prune_rank(ids, 4)
+    assert cnt[0, 3] == 0
+    # A lists a node twice: one detour, not two
+    ids[5] = [1, 1, 6, 7]
+    ids[6] = [1, 8, 9, 10]
+    _, cnt = oracle.prune_rank(ids, 4)
+    assert cnt[5].tolist() == [0, 0, 1, 0]
+    # the same id without a row (n + 7) in A's row and in F's row is no node, hence no detour
+    ids[7] = [1, n + 7, 6, 2]
+    ids[6] = [n + 7, 8, 9, 10]
+    _, cnt = oracle.prune_rank(ids, 4)
+    assert cnt[7].tolist() == [0, 0, 0, 1]                   # only 2's row, [1, 8, 9, 10], brings one: node 1
