@@ -365,11 +365,13 @@ def test_phase2_semantics():
         ids0, d0, f0 = o.graph()
         o.phase2_round()
         ids1, d1, f1 = o.graph()
+        measured = 0
         for v in range(500):
             expanded = [int(u) for u, f in zip(ids0[v], f0[v]) if f][:m]
             pool = set()
             for u in expanded:
                 pool |= set(ids0[u].tolist())    # lists as they stood when the round began
+            measured += len(pool - {v} - set(ids0[v].tolist()))      # each once; never v itself or a listed node
             arrived = set(ids1[v].tolist()) - set(ids0[v].tolist())
             assert arrived <= pool - {v}
             # the list is exactly the best k of (old list + pool)
@@ -384,6 +386,7 @@ def test_phase2_semantics():
                     assert f == 0
                 else:
                     assert f == f0[v][ids0[v].tolist().index(u)]
+        assert o.counters()["pairs"] == measured
 
 
 def test_candidate_slots_spread_evenly():
@@ -403,3 +406,60 @@ def test_candidate_slots_spread_evenly():
     same = sum(oracle.slot_of(7, r, t, 10, 0, 64) // 8 == oracle.slot_of(7, r, t, 77, 0, 64) // 8
                for r in range(20) for t in range(50))
     assert 80 <= same <= 175        # about 1000 / 8 lines by chance
+
+
+@pytest.mark.parametrize("tile,ngr,ngc", [(2, 2, 2), (1, 2, 4), (3, 4, 2), (16, 4, 8)])
+def test_retention_keeps_one_candidate_per_target_and_group_of_opposite_positions(tile, ngr, ngc):
+    """Section 4.2 retention, counted: with the threshold off every pair passes, so a row member keeps one
+    candidate for every group of column positions it meets, a column member one for every group of row
+    positions: the number of candidates handed over follows from the block sizes alone."""
+    X = inputs.make("C1", n=200, d=8)
+    k = 10
+    o = oracle.NNDescent(X, k, S=k, R=6, C=32, retain=1, tile=tile, ng_row=ngr, ng_col=ngc, seed=3, use_threshold=False)
+    o.init()
+    o.phase1_round()
+    state = o.graph()
+    o.phase1_sample()
+    want = 0
+    for v in range(200):
+        NEW, OLD = o.block(v)
+        nN, nT = len(NEW), len(NEW) + len(OLD)
+        if nN == 0 or nT < 2:
+            continue
+        for a in range(nN):                                   # row member a meets the columns behind it
+            want += len({(b // tile) % ngc for b in range(a + 1, nT)})
+        for b in range(nT):                                   # column member b meets the rows in front of it
+            want += len({(a // tile) % ngr for a in range(min(b, nN))})
+    o.set_graph(*state)
+    o.phase1_round()
+    assert o.counters()["offered"] == want > 0
+
+
+def test_forward_sample_takes_the_first_S_of_each_class():
+    """Section 3.1.1 sampling with S < k: the block of v begins with its first S new entries in list order,
+    reverse edges come from sampled edges only, and only the sampled new entries turn old."""
+    X = inputs.make("C1", n=300, d=8)
+    k, S, R = 12, 3, 24
+    o = oracle.NNDescent(X, k, S=S, R=R, C=32, seed=8)
+    o.init()
+    o.phase1_round()
+    ids, dist, fresh = o.graph()
+    o.phase1_sample()
+    first_new = [[int(u) for u, f in zip(ids[v], fresh[v]) if f][:S] for v in range(300)]
+    first_old = [[int(u) for u, f in zip(ids[v], fresh[v]) if not f][:S] for v in range(300)]
+    more_new = 0
+    for v in range(300):
+        NEW, OLD = o.block(v)
+        more_new += int(fresh[v].sum() > S)
+        assert NEW[:len(first_new[v])].tolist() == first_new[v]
+        rev_new = set(NEW[len(first_new[v]):].tolist())
+        assert rev_new == {u for u in range(300) if v in first_new[u]} - set(first_new[v])      # R is large: no cap
+        assert set(OLD.tolist()) == (set(first_old[v]) | {u for u in range(300) if v in first_old[u]}) - set(NEW.tolist())
+    assert more_new > 100, "lists should hold more than S new entries"
+    o.phase1_round()
+    ids2, _, fresh2 = o.graph()
+    for v in range(300):
+        now = dict(zip(ids2[v].tolist(), fresh2[v].tolist()))
+        for u, f in zip(ids[v].tolist(), fresh[v].tolist()):
+            if u in now and f:
+                assert now[u] == (0 if u in first_new[v] else 1)       # sampled: old now; not sampled: still new
