@@ -194,6 +194,28 @@ int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric
                  void* stream);
 
 /*
+ * tg_exact_knn for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same result as tg_exact_knn, but the scratch (the
+ * per-slice partial lists, and for TG_METRIC_COSINE the norms of all n rows) lives in a static device
+ * array of tg_exact_knn_static_scratch_bytes() = 16 MiB that every GPU the library runs on holds until
+ * the process ends.  The call allocates and frees nothing, never synchronises, and copies nothing to the
+ * host; all work is enqueued on `stream`.
+ *   - Needs d % 4 == 0 and a 16-byte aligned X (TG_ERR_UNSUPPORTED otherwise: the padded copy
+ *     tg_exact_knn makes would have to be allocated).
+ *   - Needs 8 nq k (+ 8 n for the cosine, each part rounded up to 256 bytes) <= the scratch size;
+ *     larger problems are refused with TG_ERR_INVALID_ARG and a message that says how many bytes were needed.
+ *   - query_rows are not checked on the host (that would need a copy and a wait): a row index outside
+ *     [0, n) is no query, its output row is k times (-1, +infinity).
+ *   - Every call on a GPU uses that GPU's one array and finds the previous call's contents there; each
+ *     call writes every word it later reads, so nothing has to be cleared.  Calls that overlap in time
+ *     on one GPU (two streams, two threads) race on it: keep them on one stream, or order them.
+ */
+int tg_exact_knn_static(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric,
+                        const int64_t* query_rows, int64_t nq, int32_t* out_ids, float* out_dist,
+                        void* stream);
+size_t tg_exact_knn_static_scratch_bytes(void);
+
+/*
  * Rank-based pruning of a k-NN graph by detourable routes (section 3.2, the CAGRA row of the
  * table of pruning strategies; section 5.2).  knn_ids: device n x k int32, every row ordered
  * closest first (the output of tg_knn_build); the position of a neighbour in its row stands for

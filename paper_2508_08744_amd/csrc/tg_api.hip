@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -589,6 +590,75 @@ extern "C" int tg_exact_knn(const float* X, int64_t n, int32_t d, int32_t k, int
     (void)hipFree(ws);
     if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "exact k-NN failed: %s", hipGetErrorString(e));
     return rc;
+}
+
+// ---- exact k-NN without any allocation ------------------------------------------------------------
+// The scratch of tg_exact_knn (inverse norms for the cosine, the per-slice partial lists) in device memory
+// that belongs to the library: a file-scope array, one copy per GPU, held until the process ends.  Host
+// code never uses the array's name as an address: its device address is asked for once per device.
+#define TG_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[TG_STATIC_SCRATCH_BYTES];
+#define TG_MAX_DEVICES 64
+static void* g_scratch_ptr[TG_MAX_DEVICES];      // by device ordinal, filled on first use (under the lock)
+static std::mutex g_scratch_lock;
+
+static int static_scratch(void** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= TG_MAX_DEVICES) return fail(TG_ERR_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, TG_MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(TG_ERR_HIP, "no device address for the static scratch");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TG_OK;
+}
+
+extern "C" size_t tg_exact_knn_static_scratch_bytes(void) { return TG_STATIC_SCRATCH_BYTES; }
+
+extern "C" int tg_exact_knn_static(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, const int64_t* query_rows,
+                                   int64_t nq, int32_t* out_ids, float* out_dist, void* stream)
+{
+    if (!X || !out_ids) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (k < 1 || k > 64) return fail(TG_ERR_INVALID_ARG, "k = %d outside 1..64", k);
+    if (n <= k || n >= (1ll << 30)) return fail(TG_ERR_INVALID_ARG, "need k < n < 2^30");
+    if (d < 1 || d > 4096) return fail(TG_ERR_INVALID_ARG, "d = %d outside 1..4096", d);
+    if (metric < 0 || metric > 2) return fail(TG_ERR_INVALID_ARG, "unknown metric %d", metric);
+    if (nq < 0) return fail(TG_ERR_INVALID_ARG, "nq < 0");
+    if (!query_rows && nq > n) return fail(TG_ERR_INVALID_ARG, "nq > n without query_rows");
+    if ((d & 3) || (reinterpret_cast<uintptr_t>(X) & 15))
+        return fail(TG_ERR_UNSUPPORTED, "the allocation-free exact k-NN needs d %% 4 == 0 and a 16-byte aligned X (a padded copy would have to be allocated)");
+    if (nq == 0) return TG_OK;
+    // layout: inverse norms (cosine only), then the partial lists; fewer slices when they would not fit
+    Carver c{nullptr, 0};
+    if (metric == 2) { c.take<float>(n); c.take<float>(n); }
+    const size_t fixed = (c.used + 255) & ~(size_t)255;
+    int slices = tg_exact_slices(n, nq);
+    while (slices > 1 && fixed + (size_t)nq * slices * k * sizeof(u64) > TG_STATIC_SCRATCH_BYTES) --slices;
+    const size_t need = fixed + (size_t)nq * slices * k * sizeof(u64);
+    if (need > TG_STATIC_SCRATCH_BYTES)
+        return fail(TG_ERR_INVALID_ARG, "problem too large for the static scratch: %zu bytes needed (%s8 nq k), %u available",
+                    need, metric == 2 ? "8 n + " : "", (unsigned)TG_STATIC_SCRATCH_BYTES);
+    void* base = nullptr;
+    int rc = static_scratch(&base);
+    if (rc != TG_OK) return rc;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    Carver w{reinterpret_cast<char*>(base), 0};
+    TgGraph g = {};
+    g.n = n; g.d = d; g.ld = d; g.k = k; g.metric = metric;
+    g.X = X;
+    if (metric == 2) {
+        g.nrm = w.take<float>(n);
+        g.rnorm = w.take<float>(n);
+        tg_launch_norms(g, nullptr, nullptr, s);           // writes every word it later reads
+    }
+    u64* partial = w.take<u64>((size_t)nq * slices * k);   // every word read by the merge is written by the scan
+    tg_launch_exact_knn(g.X, g.ld, g.nrm, g.rnorm, n, d, k, metric, query_rows, nq, out_ids, out_dist, partial, slices, s);
+    return launch_status("exact k-NN (static scratch)");
 }
 
 extern "C" int tg_prune_rank(const int32_t* knn_ids, int64_t n, int32_t k, int32_t d_out, int32_t* out_ids, int32_t* out_counts,

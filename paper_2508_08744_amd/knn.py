@@ -46,7 +46,7 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_prune_dispersion", "tg_angle_at", "tg_merge_local", "tg_lists_clear",
+           "tg_knn_join_distances", "tg_exact_knn", "tg_exact_knn_static", "tg_exact_knn_static_scratch_bytes", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_prune_dispersion", "tg_angle_at", "tg_merge_local", "tg_lists_clear",
            "tg_last_error"]
 
 _lib = None
@@ -79,6 +79,9 @@ def lib():
         L.tg_knn_sample_blocks.argtypes = [vp, vp, vp]
         L.tg_knn_join_distances.argtypes = [vp, vp, vp, i64, vp]
         L.tg_exact_knn.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
+        L.tg_exact_knn_static.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
+        L.tg_exact_knn_static_scratch_bytes.restype = sz
+        L.tg_exact_knn_static_scratch_bytes.argtypes = []
         L.tg_prune_rank.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         L.tg_merge_local.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, vp, vp]
         L.tg_lists_clear.argtypes = [vp, vp, i64, i32, vp]
@@ -317,6 +320,28 @@ def merge_local(g_ids, g_dist, l_ids, l_dist, local_to_global):
         raise ValueError("shapes disagree")
     _check(lib().tg_merge_local(g_ids.data_ptr(), g_dist.data_ptr(), n, k, l_ids.data_ptr(), l_dist.data_ptr(), nl, kl,
                                 local_to_global.data_ptr(), _stream_ptr()))
+
+
+def exact_knn_static(X, k, metric="l2", rows=None, out=None):
+    """tg_exact_knn_static: tg_exact_knn on the library's static scratch (the call itself allocates nothing;
+    pass ``out = (ids, dist)`` to keep torch from allocating the outputs here)."""
+    X = _dev_f32(X)
+    n, d = X.shape
+    if rows is None:
+        nq, rp = n, None
+    else:
+        if not (rows.is_cuda and rows.dtype == torch.int64 and rows.is_contiguous()):
+            raise TypeError("rows must be a contiguous int64 CUDA tensor")
+        nq, rp = rows.numel(), rows.data_ptr()
+    if out is None:
+        out = (torch.empty((nq, k), dtype=torch.int32, device=X.device), torch.empty((nq, k), dtype=torch.float32, device=X.device))
+    ids, dist = out
+    if not (ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous() and tuple(ids.shape) == (nq, k)
+            and dist.is_cuda and dist.dtype == torch.float32 and dist.is_contiguous() and tuple(dist.shape) == (nq, k)):
+        raise TypeError("out must be (int32, float32) contiguous CUDA tensors of shape (nq, k)")
+    _check(lib().tg_exact_knn_static(X.data_ptr(), n, d, k, METRICS[metric], rp, nq, ids.data_ptr(), dist.data_ptr(),
+                                     _stream_ptr()))
+    return ids, dist
 
 
 def exact_knn(X, k, metric="l2", rows=None):
