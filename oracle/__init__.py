@@ -54,7 +54,7 @@ def lib():
         L.obf_knn.restype = i32
         L.obf_knn.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp]
         L.onnd_create.restype = vp
-        L.onnd_create.argtypes = [vp, i64, i64, i32, i32] + [i32] * 10 + [u64]
+        L.onnd_create.argtypes = [vp, i64, i64, i32, i32] + [i32] * 12 + [u64]
         L.onnd_destroy.argtypes = [vp]
         L.onnd_export.argtypes = [vp, vp, vp, vp]
         L.onnd_counters.argtypes = [vp, vp]
@@ -242,11 +242,29 @@ def merge_local(g_ids, g_dist, l_ids, l_dist, l2g):
         raise ValueError("bad arguments")
 
 
-class NNDescent:
-    """O-NND: one object per build; methods are the steps of Algorithm 1."""
+# The bounded hand-over of candidates that the HIP library's local join uses (include/tagore_knn.h, parameters
+# C and parts): per member and group of eight consecutive block positions the closest candidate that the
+# member's list does not hold yet.  A test that follows a device build step by step passes these, with the
+# build's C and parts; the reference mode of O-NND (the defaults of NNDescent) has none of it.
+DEVICE_HANDOVER = dict(retain=1, tile=8, ng_row=8, ng_col=8, exclude_listed=True)
 
-    def __init__(self, X, k, metric=METRIC_L2, S=None, R=None, C=64, retain=1, tile=16,
-                 ng_row=2, ng_col=2, m=2, all_block=False, use_threshold=True, seed=1):
+
+def device_model(prm):
+    """Keyword arguments of NNDescent that follow a build with the parameters ``prm`` (a tg_knn_params) step by step."""
+    return dict(S=prm.S, R=prm.R, C=prm.C, parts=prm.parts, m=prm.m, seed=prm.seed, **DEVICE_HANDOVER)
+
+
+class NNDescent:
+    """O-NND: one object per build; methods are the steps of Algorithm 1.
+
+    The defaults are the plain method (every evaluated pair offered to both nodes, unbounded candidate
+    lists, one update per round).  ``retain``, ``tile``, ``ng_row``, ``ng_col``, ``C``, ``exclude_listed``
+    and ``parts`` model a bounded hand-over of candidates (see tg_oracle.c) and are set by the tests that
+    follow a device build step by step."""
+
+    def __init__(self, X, k, metric=METRIC_L2, S=None, R=None, C=0, retain=0, tile=16,
+                 ng_row=2, ng_col=2, m=2, all_block=False, use_threshold=True, seed=1,
+                 exclude_listed=False, parts=1):
         self.X = _f32(X)
         self.n, self.d = self.X.shape
         self.k = k
@@ -255,7 +273,7 @@ class NNDescent:
         self.S, self.R = S, R
         self._h = lib().onnd_create(self.X.ctypes.data, self.n, self.d, k, metric, S, R, C,
                                     retain, tile, ng_row, ng_col, m, int(all_block),
-                                    int(use_threshold), seed)
+                                    int(use_threshold), int(exclude_listed), int(parts), seed)
         if not self._h:
             raise ValueError("onnd_create: invalid arguments")
 

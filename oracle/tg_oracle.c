@@ -16,9 +16,19 @@
  *                         Algorithm 1, in the algorithm's order.
  *
  * Where the paper leaves a choice open (sample sizes, reverse neighbours,
- * tie order, candidate-buffer overflow, retention grouping, visited marks)
- * the reading implemented here is the one the repository's design notes
- * list; every such reading is a parameter or is commented where it is taken.
+ * tie order, visited marks) the reading implemented here is the one the
+ * repository's design notes list; every such reading is a parameter or is
+ * commented where it is taken.
+ *
+ * The reference mode of O-NND is the plain method: every pair a block
+ * evaluates is offered to both of its nodes, and a node's candidate list is
+ * unbounded (retain = 0, C = 0, parts = 1).  The remaining parameters
+ * (retain, tile, ng_row, ng_col, C with slot_of(), parts) do not belong to the
+ * method: they model a bounded hand-over of candidates from the blocks to
+ * the lists, such as a device with little fast memory per block needs
+ * (section 4.2 keeps one closest node per node and warp sub-tile for the same
+ * reason).  They are here so that such a build can be followed step by step;
+ * what they cost in quality is measured against the reference mode.
  *
  * Pinning: tests/test_oracle_*.py check O-BF against closed forms and an
  * independent full sort, and O-NND against O-BF in the cases where the
@@ -170,6 +180,13 @@ typedef struct {
     int all_block;    /* 1: every anchor's block is all of V, all new          */
     int use_threshold;/* 0 switches off the early threshold test (the merge
                          then discards the same candidates)                    */
+    int exclude_listed;/* 1: a node that the target's list already holds is no
+                         candidate where the pair is met (the merge would drop
+                         it anyway; with retention it matters, because such a
+                         node would otherwise take the place of a useful one)  */
+    int parts;        /* a phase-1 round is carried out in this many parts:
+                         part p joins the blocks of the anchors v = p mod parts,
+                         and the lists are updated after every part            */
     uint64_t seed;
     /* state */
     entry_t *G;       /* n x k, each row sorted by (dist, id)                  */
@@ -199,14 +216,15 @@ static void bag_push(candvec_t *b, double dist, int32_t id)
 
 void *onnd_create(const float *X, int64_t n, int64_t d, int k, int metric,
                   int S, int R, int C, int retain, int tile, int ng_row, int ng_col,
-                  int m, int all_block, int use_threshold, uint64_t seed)
+                  int m, int all_block, int use_threshold, int exclude_listed, int parts, uint64_t seed)
 {
-    if (k < 1 || k >= n || (C & (C - 1)) != 0) return NULL;
+    if (k < 1 || k >= n || (C & (C - 1)) != 0 || parts < 1) return NULL;
     onnd_t *o = (onnd_t *)calloc(1, sizeof(onnd_t));
     o->X = X; o->n = n; o->d = d; o->k = k; o->metric = metric;
     o->S = S; o->R = R; o->C = C; o->retain = retain; o->tile = tile;
     o->ng_row = ng_row; o->ng_col = ng_col; o->m = m;
     o->all_block = all_block; o->use_threshold = use_threshold; o->seed = seed;
+    o->exclude_listed = exclude_listed; o->parts = parts;
     o->G = (entry_t *)calloc((size_t)(n * k), sizeof(entry_t));
     if (C > 0) o->slots = (cand_t *)malloc((size_t)(n * C) * sizeof(cand_t));
     else o->bag = (candvec_t *)calloc((size_t)n, sizeof(candvec_t));
@@ -347,10 +365,15 @@ static void emit(onnd_t *o, int32_t t, int32_t c, double dist, int32_t v, int g)
     if (slot->id < 0 || key_less(dist, c, slot->dist, slot->id)) { slot->dist = dist; slot->id = c; }
 }
 
-/* Threshold of section 4.2: only candidates that would precede the last
- * entry of the target's current list are kept. */
+/* Is c, at this distance, a candidate for t's list?  Threshold of section 4.2:
+ * only candidates that would precede the last entry of the target's current
+ * list are kept; and (exclude_listed) a node the list holds is none. */
 static int passes(const onnd_t *o, int32_t t, int32_t c, double dist)
 {
+    if (o->exclude_listed) {
+        const entry_t *L = o->G + (int64_t)t * o->k;
+        for (int q = 0; q < o->k; ++q) if (L[q].id == c) return 0;
+    }
     if (!o->use_threshold) return 1;
     const entry_t *last = o->G + (int64_t)t * o->k + (o->k - 1);
     return key_less(dist, c, last->dist, last->id);
@@ -582,24 +605,26 @@ int64_t onnd_phase1_round(void *h)
         return o->updates;
     }
 
-    /* (1) sample */
+    /* (1) sample: the blocks of the whole round are fixed here */
     onnd_phase1_sample(h);
-
-    /* (2) local join per anchor */
-    int32_t *blk = (int32_t *)malloc((size_t)(2 * o->S + 2 * o->R) * sizeof(int32_t));
-    for (int64_t v = 0; v < n; ++v) {
-        int sizes[2];
-        onnd_block(h, v, blk, sizes);
-        local_join(o, (int32_t)v, blk, sizes[0], sizes[1]);
-    }
-    free(blk);
+    int bw = 2 * o->S + 2 * o->R;
+    int32_t *blk = (int32_t *)malloc((size_t)n * bw * sizeof(int32_t));
+    int *sizes = (int *)malloc((size_t)n * 2 * sizeof(int));
+    for (int64_t v = 0; v < n; ++v) onnd_block(h, v, blk + v * bw, sizes + v * 2);
 
     /* sampled new entries become old (3.1.1: previously sampled nodes are
      * labelled old) */
     for (int64_t i = 0; i < n * k; ++i) if (o->sampled[i]) o->G[i].fresh = 0;
 
-    /* (3) update */
-    o->updates = merge_all(o);
+    for (int p = 0; p < o->parts; ++p) {
+        if (p) clear_candidates(o);
+        /* (2) local join per anchor of this part */
+        for (int64_t v = p; v < n; v += o->parts)
+            local_join(o, (int32_t)v, blk + v * bw, sizes[v * 2], sizes[v * 2 + 1]);
+        /* (3) update */
+        o->updates += merge_all(o);
+    }
+    free(blk); free(sizes);
     o->round++;
     return o->updates;
 }

@@ -463,3 +463,146 @@ def test_forward_sample_takes_the_first_S_of_each_class():
         for u, f in zip(ids[v].tolist(), fresh[v].tolist()):
             if u in now and f:
                 assert now[u] == (0 if u in first_new[v] else 1)       # sampled: old now; not sampled: still new
+
+
+# ---------------------------------------------------------------------------------------------
+# The two readings added for a bounded hand-over: a node the target's list holds is no candidate
+# where the pair is met (exclude_listed), and a round carried out in parts with an update after
+# each.  For the plain method (every pair offered, unbounded candidate lists) neither can change a
+# list: the update drops a listed node anyway, and a candidate that a tightened threshold turns
+# away could not have stayed.  With retention both matter; there the oracle is checked against a
+# round written out in Python on a small input.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,n,k", [("C1", 700, 8), ("C2", 600, 12)])
+def test_plain_method_is_blind_to_exclusion_and_parts(cfg, n, k):
+    X = inputs.make(cfg, n=n, d=8, comps=4)
+    ref = oracle.NNDescent(X, k, seed=9)
+    variants = [oracle.NNDescent(X, k, seed=9, exclude_listed=True),
+                oracle.NNDescent(X, k, seed=9, parts=3),
+                oracle.NNDescent(X, k, seed=9, parts=4, exclude_listed=True)]
+    for o in [ref] + variants:
+        o.init()
+    for r in range(4):
+        ref.phase1_round()
+        want = ref.graph()
+        offered = ref.counters()["offered"]
+        for j, o in enumerate(variants):
+            o.phase1_round()
+            got = o.graph()
+            assert all((a == b).all() for a, b in zip(got, want)), (r, j)
+            c = o.counters()
+            assert c["pairs"] == ref.counters()["pairs"]
+            assert c["offered"] <= offered, "fewer nodes are offered, never more"
+            if j == 0:
+                assert c["updates"] == ref.counters()["updates"]        # one update per round: the same entries change
+            else:
+                assert c["updates"] >= ref.counters()["updates"]        # an entry may come and go inside one round
+    ref.begin_phase2()
+    for o in variants:
+        o.begin_phase2()
+    ref.phase2_round()
+    for o in variants:
+        o.phase2_round()
+        assert all((a == b).all() for a, b in zip(o.graph(), ref.graph()))
+
+
+def _python_round(X, ids, dist, fresh, blocks, k, tile, ng, exclude, parts, C=0, seed=0, rnd=0):
+    """One phase-1 round written out: blocks fixed, sampled entries old, then for each part the join of its anchors
+    with per (member, group of opposite positions) retention of the closest admissible node, and the update.
+    C > 0: a node has C candidate slots; what a block keeps for it goes to slot_of(...) and the closer one stays."""
+    n = len(X)
+    Xd = X.astype(np.float64)
+    lists = [[(dist[v, j], int(ids[v, j]), 0 if sampled else int(fresh[v, j])) for j, sampled in enumerate(smp)]
+             for v, smp in enumerate(blocks["sampled"])]
+    for p in range(parts):
+        cands = [dict() for _ in range(n)]           # target -> {(anchor, row or column node, group): (dist, id)}
+        for v in range(p, n, parts):
+            N, O = blocks["blocks"][v]
+            mem = list(N) + list(O)
+            if len(N) == 0 or len(mem) < 2:
+                continue
+            for a in range(len(N)):
+                for b in range(a + 1, len(mem)):
+                    t, c = mem[a], mem[b]
+                    dd = float(((Xd[t] - Xd[c]) ** 2).sum())
+                    for role, (tgt, cnd, opp) in enumerate(((t, c, b), (c, t, a))):       # the row node's turn, the column node's
+                        L = lists[tgt]
+                        if exclude and any(e[1] == cnd for e in L):
+                            continue
+                        if not (dd, cnd) < (L[-1][0], L[-1][1]):
+                            continue
+                        key = (v, role, (opp // tile) % ng)
+                        if key not in cands[tgt] or (dd, cnd) < cands[tgt][key]:
+                            cands[tgt][key] = (dd, cnd)
+        for t in range(n):
+            L = lists[t]
+            have = {e[1] for e in L}
+            kept = cands[t]
+            if C > 0:
+                kept = {}
+                for (v, role, g), cand in cands[t].items():
+                    slot = oracle.slot_of(seed, rnd, t, v, g, C)
+                    if slot not in kept or cand < kept[slot]:
+                        kept[slot] = cand
+            new = sorted(set(kept.values()))
+            for dd, c in new:
+                if c == t or c in have:
+                    continue
+                have.add(c)
+                L.append((dd, c, 1))
+            L.sort(key=lambda e: (e[0], e[1]))
+            del L[k:]
+    return lists
+
+
+@pytest.mark.parametrize("exclude", [False, True])
+@pytest.mark.parametrize("parts,C", [(1, 0), (3, 0), (3, 16)])
+def test_round_with_retention_exclusion_and_parts_against_a_python_round(exclude, parts, C):
+    n, k, tile, ng = 150, 6, 4, 8
+    X = inputs.make("C2", n=n, d=6, comps=3)          # integer valued: distances exact either way, ties occur
+    X[5:10] = X[0:5]                                    # and a few points twice: distance 0 between them
+    o = oracle.NNDescent(X, k, S=k, R=5, C=C, retain=1, tile=tile, ng_row=ng, ng_col=ng, seed=4,
+                         exclude_listed=exclude, parts=parts)
+    o.init()
+    for r in range(3):
+        ids, dist, fresh = o.graph()
+        o.phase1_sample()
+        blk = [o.block(v) for v in range(n)]
+        # sampled = the first S new entries of every list (S = k: every new entry)
+        sampled = [[bool(fresh[v, j]) for j in range(k)] for v in range(n)]
+        want = _python_round(X, ids, dist, fresh, dict(blocks=blk, sampled=sampled), k, tile, ng, exclude, parts, C=C, seed=4, rnd=r)
+        o.phase1_round()
+        gi, gd, gf = o.graph()
+        for v in range(n):
+            assert [e[1] for e in want[v]] == gi[v].tolist(), (r, v)
+            assert [e[0] for e in want[v]] == gd[v].tolist(), (r, v)
+            assert [e[2] for e in want[v]] == gf[v].tolist(), (r, v)
+
+
+def test_exclusion_lets_the_next_closest_node_through():
+    """Hand-made: with one retention group a member keeps the closest of the nodes behind it in its block.  Nodes 0, 1, 2
+    meet only in the block of node 7, in this order.  Node 1 is the closest to node 0 and sits in 0's list already: without
+    exclude_listed it takes the one place and the update throws it away; with it, node 2 reaches node 0."""
+    X = np.array([[0.0], [1.0], [2.5], [100.0], [101.0], [103.0], [106.0], [-50.0]], dtype=np.float32)
+    n, k = len(X), 3
+    lists = [[1, 3, 4], [0, 3, 4], [3, 4, 5], [4, 5, 6], [3, 5, 6], [4, 3, 6], [5, 4, 3], [0, 1, 2]]
+
+    def run(exclude):
+        o = oracle.NNDescent(X, k, S=k, R=0, C=0, retain=1, tile=64, ng_row=1, ng_col=1, seed=1, exclude_listed=exclude)
+        o.init()
+        ids = np.array(lists, dtype=np.int32)
+        dist = np.array([[float((X[v, 0] - X[c, 0]) ** 2) for c in ids[v]] for v in range(n)])
+        assert (np.diff(dist, axis=1) >= 0).all(), "the hand-made rows are in list order (the one tie is in id order)"
+        o.set_graph(ids, dist, np.ones((n, k), dtype=np.uint8))
+        o.phase1_sample()
+        assert [b.tolist() for b in o.block(7)] == [[0, 1, 2], []]
+        assert all(not ({0, 2} <= set(o.block(v)[0].tolist())) for v in range(7)), "0 and 2 meet in one block only"
+        o.phase1_round()
+        return o.graph()[0]
+
+    without, with_ = run(False), run(True)
+    assert without[0].tolist() == [1, 3, 4], "node 1, already listed, took node 2's place"
+    assert with_[0].tolist() == [1, 2, 3]
+    # the other two nodes of the block fare alike either way: 1 gets 2 (its place as a row node is its own), 2 gets 1
+    for g in (without, with_):
+        assert g[1].tolist() == [0, 2, 3] and g[2].tolist() == [1, 3, 4]
