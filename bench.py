@@ -37,8 +37,7 @@ def cpu_baseline(config: str, prm, sample_n: int):
     import oracle
     from paper_2508_08744_amd import inputs
     X = inputs.make(config, n=sample_n)
-    o = oracle.NNDescent(X, prm.k, metric=prm.metric, S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16,
-                         ng_row=prm.ng_row, ng_col=prm.ng_col, m=prm.m, seed=prm.seed)
+    o = oracle.NNDescent(X, prm.k, metric=prm.metric, **oracle.device_model(prm))
     t0 = time.perf_counter()
     o.run(prm.it1, prm.it2)
     dt = time.perf_counter() - t0
@@ -146,7 +145,7 @@ def main():
         "config": {"workload": "%s: n=%d d=%d k=%d %s, Gaussian mixture (%s stand-in)" % (
             args.config, n, d, k, metric, {"C1": "small test", "C2": "SIFT-1M", "C3": "Gist", "C4": "Deep", "C5": "Deep"}.get(args.config, "synthetic")),
                    "it1": prm.it1, "it2": prm.it2, "S": prm.S, "R": prm.R, "C": prm.C,
-                   "ng_row": prm.ng_row, "ng_col": prm.ng_col, "m": prm.m, "seed": int(prm.seed)},
+                   "parts": prm.parts, "m": prm.m, "seed": int(prm.seed)},
         "recall_at_k": recall,
         "recall_ok": bool(recall >= 0.95),
         "join_mfma_pct": 100.0 * achieved / MFMA_FP32_PEAK_TFLOPS,

@@ -53,10 +53,16 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *   it1,it2  rounds of phase 1 / phase 2 (Algorithm 1 input; the paper sets it1 = it2)
  *   S        forward sample cap per class (new / old) in phase 1, 1 <= S <= 32
  *   R        reverse sample cap per class in phase 1, 0 <= R <= 32
- *   C        candidate slots per node and round (section 4.2 "candidate list"),
- *            a power of two, 16 <= C <= 256
- *   ng_row   retention groups of row tiles  (2 or 4)  } section 4.2: per node one closest
- *   ng_col   retention groups of column tiles (2,4,8) } candidate per sub-tile group
+ *   C        candidate slots per node (section 4.2 "candidate list"), a power of two, 16 <= C <= 256.  A block
+ *            hands each of its members at most eight candidates: the closest one of every group of eight
+ *            consecutive block positions (section 4.2: one closest candidate per node and sub-tile) that is
+ *            not in the member's list already and would precede the list's last entry; the eight share one
+ *            64-byte line of the member's slots, picked by a hash of (member, anchor), and a slot keeps the
+ *            closer candidate when two meet in it
+ *   parts    a phase-1 round is carried out in this many parts (1, 2, 4 or 8): part p joins the blocks of
+ *            the anchors v = p (mod parts), then every list takes in its candidates, so that the next part
+ *            meets the tightened thresholds and the lengthened lists.  More parts: fewer candidates that
+ *            cannot stay, so fewer slots do; more list updates
  *   m        neighbours expanded per node and phase-2 round (the paper: m = 2), 1..4
  *   delta    early stop: a phase ends when a round changes fewer than delta*n*k
  *            entries; 0 = run exactly it1 + it2 rounds (never synchronises with the host)
@@ -90,7 +96,7 @@ typedef struct tg_knn_params {
     int32_t metric;
     int32_t it1, it2;
     int32_t S, R, C;
-    int32_t ng_row, ng_col;
+    int32_t parts;
     int32_t m;
     float delta;
     int32_t finalize;
@@ -117,17 +123,20 @@ typedef struct tg_knn_stats {
 typedef struct tg_knn_handle tg_knn_handle;
 
 /* Defaults for a given k and total round budget: it1 = ceil(iters/2), it2 = iters - it1
- * (section 7.3: it1 = it2), S = min(k,32), R = 32, C = 64, ng_row = 4, ng_col = 8, m = 2,
+ * (section 7.3: it1 = it2), S = min(k,32), R = 32, C = 64, parts = 4, m = 2,
  * delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with delta = 0.001. */
 int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);
 
-/* Device bytes a build of this size needs as workspace. 0 if the arguments are invalid. */
+/* Device bytes a build of this size needs as workspace, for an X that is 16-byte aligned (rows of d % 4 == 0
+ * floats are then used where they are; other rows are copied, which is counted).  An X with d % 4 == 0 that
+ * is not 16-byte aligned needs 4 n d + 256 bytes more.  0 if the arguments are invalid. */
 size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_params* p);
 
 /*
  * The whole of Algorithm 1.  X: device, row-major n x d fp32.  out_ids: device, n x k
- * int32.  out_dist: device, n x k fp32, may be NULL.  Allocates and frees its own
- * workspace (synchronises the stream once at the end to do so).
+ * int32.  out_dist: device, n x k fp32, may be NULL.  Takes and returns its own workspace in
+ * stream order (hipMallocAsync / hipFreeAsync on `stream`: no wait; with iters > 0 the call
+ * only enqueues work).  Runs with tg_knn_default_params(k, iters).
  * iters > 0: exactly it1 = ceil(iters/2) and it2 = iters - it1 rounds; iters <= 0: up to
  * 16 rounds with early stop.  Valid iff 1 <= k <= 64, k < n < 2^30, 1 <= d <= 4096.
  */
@@ -176,6 +185,11 @@ int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* dist, const
  * the coming round and writes every anchor's block: blk device n x 128 int32 (NEW ids
  * first, then OLD ids), sizes device n x 2 int32 (|NEW|, |OLD|).  Does not advance the round. */
 int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* sizes);
+/* Which members of the blocks last written by tg_knn_sample_blocks already sit in which member's list (the local
+ * join offers no node to a list that holds it): adj device n x 128 x 4 uint32; bit x % 32 of word x / 32 of
+ * entry (v, p) is set iff the node at position x of anchor v's block is in the list of the node at position p, as
+ * the lists stand now.  Entries of positions beyond a block, and of anchors without a join, are 0. */
+int tg_knn_block_adjacency(tg_knn_handle* h, uint32_t* adj);
 /* The local join's distance tile for explicit blocks, through the same LDS/MFMA core:
  * blk device nb x 128 int32, sizes device nb x 2 (|NEW| <= 64, |NEW|+|OLD| <= 128),
  * out device nb x 64 x 128 fp32; entry (b, r, c) is dist(blk[b][r], blk[b][c]) for

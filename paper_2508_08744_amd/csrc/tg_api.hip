@@ -43,8 +43,7 @@ static int check_problem(int64_t n, int32_t d, const tg_knn_params* p)
     if (p->S < 1 || p->S > 32) return fail(TG_ERR_INVALID_ARG, "S = %d outside 1..32", p->S);
     if (p->R < 0 || p->R > 32) return fail(TG_ERR_INVALID_ARG, "R = %d outside 0..32", p->R);
     if (p->C < 16 || p->C > 256 || (p->C & (p->C - 1))) return fail(TG_ERR_INVALID_ARG, "C = %d must be 16, 32, 64, 128 or 256", p->C);
-    if (p->ng_row != 2 && p->ng_row != 4) return fail(TG_ERR_INVALID_ARG, "ng_row = %d must be 2 or 4", p->ng_row);
-    if (p->ng_col != 2 && p->ng_col != 4 && p->ng_col != 8) return fail(TG_ERR_INVALID_ARG, "ng_col = %d must be 2, 4 or 8", p->ng_col);
+    if (p->parts != 1 && p->parts != 2 && p->parts != 4 && p->parts != 8) return fail(TG_ERR_INVALID_ARG, "parts = %d must be 1, 2, 4 or 8", p->parts);
     if (p->m < 1 || p->m > 4) return fail(TG_ERR_INVALID_ARG, "m = %d outside 1..4", p->m);
     if (!(p->delta >= 0.0f && p->delta < 1.0f)) return fail(TG_ERR_INVALID_ARG, "delta must be in [0, 1)");
     if (p->screen != 0 && p->screen != 1) return fail(TG_ERR_INVALID_ARG, "screen = %d must be 0 or 1", p->screen);
@@ -65,8 +64,7 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->S = k < 32 ? (k < 1 ? 1 : k) : 32;
     p->R = 32;
     p->C = 64;
-    p->ng_row = 4;
-    p->ng_col = 8;
+    p->parts = 4;
     p->m = 2;
     p->finalize = 1;
     p->screen = 1;
@@ -156,9 +154,13 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     }
     h->sm.blk = c.take<u32>((size_t)n * h->sm.BC);
     h->sm.bsz = c.take<u32>(n);
-    h->sm.wl = c.take<u64>((size_t)3 * n);
-    h->sm.wl_cnt = c.take<u32>(4);
+    h->sm.wl = c.take<u64>((size_t)3 * (n + TG_MAX_PARTS));
+    h->sm.wl_cnt = c.take<u32>(TG_WL_LISTS);
     h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(n));
+    h->sm.parts = p.parts;
+    h->sm.parts_shift = p.parts == 8 ? 3 : p.parts == 4 ? 2 : p.parts == 2 ? 1 : 0;
+    h->sm.adj_words = h->sm.BC > 64 ? 4 : 2;
+    h->sm.adj = c.take<u32>((size_t)((n + p.parts - 1) / p.parts) * h->sm.BC * h->sm.adj_words);
     h->cd.C = p.C;
     h->cd.slots = c.take<u64>((size_t)n * p.C);
     h->d_updates = c.take<u64>((size_t)TG_MAX_ROUNDS * TG_STAT_BINS);
@@ -172,8 +174,8 @@ extern "C" size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_para
     tg_knn_handle tmp;
     tmp.p = *p;
     size_t need = 0;
-    // worst case: rows need an aligned, padded copy
-    carve(&tmp, reinterpret_cast<const float*>(4), n, d, nullptr, &need);
+    // rows of a whole number of 16 bytes are used where they are (X is then expected 16-byte aligned); others are copied
+    carve(&tmp, reinterpret_cast<const float*>(0), n, d, nullptr, &need);
     return need;
 }
 
@@ -213,8 +215,10 @@ extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int
     size_t need = 0;
     carve(h, X, n, d, workspace, &need);
     if (need > workspace_bytes) {
+        const bool misaligned = h->x_padded && (d & 3) == 0;
         delete h;
-        return fail(TG_ERR_INVALID_ARG, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+        return fail(TG_ERR_INVALID_ARG, "workspace too small: %zu bytes given, %zu needed%s", workspace_bytes, need,
+                    misaligned ? " (X is not 16-byte aligned, so room for an aligned copy of it is needed too)" : "");
     }
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
@@ -300,14 +304,19 @@ static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
     int sp = begin_span(h, SPAN_SAMPLE, r);
     tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->edges_numbered, h->stream);
     h->edges_numbered = false;
+    tg_launch_bin(h->g, h->sm, h->p.parts, h->stream);
     end_span(h, sp);
-    sp = begin_span(h, SPAN_JOIN, r);
-    tg_launch_join(h->g, h->sm, h->cd, h->p.ng_row, h->p.ng_col, tg_hash_seed(h->p.seed, TG_TAG_SLOT(r)),
-                   h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
-    end_span(h, sp);
-    sp = begin_span(h, SPAN_UPDATE, r);
-    tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, number_next, h->stream);
-    end_span(h, sp);
+    for (int part = 0; part < h->p.parts; ++part) {
+        // the anchors v = part mod parts: their blocks are joined, then every list takes in what it was handed
+        sp = begin_span(h, SPAN_JOIN, r);
+        tg_launch_join(h->g, h->sm, h->cd, part, h->p.parts, tg_hash_seed(h->p.seed, TG_TAG_SLOT(r)),
+                       h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
+        end_span(h, sp);
+        sp = begin_span(h, SPAN_UPDATE, r);
+        tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, part == 0,
+                         number_next && part + 1 == h->p.parts, h->stream);
+        end_span(h, sp);
+    }
     h->edges_numbered = number_next;
     h->round++;
     h->rounds1++;
@@ -454,6 +463,14 @@ extern "C" int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* siz
     return launch_status("sample");
 }
 
+extern "C" int tg_knn_block_adjacency(tg_knn_handle* h, uint32_t* adj)
+{
+    if (!h || !adj) return fail(TG_ERR_INVALID_ARG, "NULL argument");
+    if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
+    for (int part = 0; part < h->p.parts; ++part) tg_launch_dump_adj(h->g, h->sm, part, adj, h->stream);
+    return launch_status("block adjacency");
+}
+
 extern "C" int tg_knn_join_distances(tg_knn_handle* h, const int32_t* blk, const int32_t* sizes, int64_t nb, float* out)
 {
     if (!h || !blk || !sizes || !out) return fail(TG_ERR_INVALID_ARG, "NULL argument");
@@ -527,16 +544,19 @@ extern "C" int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int
     if (rc != TG_OK) return rc;
     if (!X) return fail(TG_ERR_INVALID_ARG, "X is NULL");
     if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
-    const size_t bytes = tg_knn_workspace_bytes(n, d, &p);
+    // an X that is not 16-byte aligned is copied: room for that on top of what the size query says
+    size_t bytes = tg_knn_workspace_bytes(n, d, &p);
+    if ((d & 3) == 0 && (reinterpret_cast<uintptr_t>(X) & 15)) bytes += (size_t)n * d * sizeof(float) + 256;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // the workspace lives in stream order: taken before the first kernel, given back behind the last one, no wait
     void* ws = nullptr;
-    if (hipMalloc(&ws, bytes) != hipSuccess) {
+    if (hipMallocAsync(&ws, bytes, s) != hipSuccess) {
         (void)hipGetLastError();
         return fail(TG_ERR_OUT_OF_MEMORY, "workspace of %zu bytes could not be allocated", bytes);
     }
     rc = tg_knn_build_ex(X, n, d, &p, ws, bytes, out_ids, out_dist, nullptr, stream);
-    hipError_t e = hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream));
-    (void)hipFree(ws);
-    if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "build failed: %s", hipGetErrorString(e));
+    const hipError_t e = hipFreeAsync(ws, s);
+    if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "releasing the workspace failed: %s", hipGetErrorString(e));
     return rc;
 }
 

@@ -7,6 +7,8 @@
 #define TG_BLOCK_COLS 128   // a join block holds at most 64 NEW rows and 128 rows in total
 #define TG_BLOCK_ROWS 64
 #define TG_STAT_BINS 1024   // spread of the per-round statistics counters
+#define TG_MAX_PARTS 8      // a phase-1 round is carried out in at most this many parts
+#define TG_WL_LISTS (3 * TG_MAX_PARTS)   // join work lists of a round: one per part and block-size class
 
 // One launch carries fewer than 2^32 work-items.  Kernels that give every node a wave (or a group
 // of lanes) of its own are therefore launched once per chunk of TG_LAUNCH_NODES nodes and told
@@ -50,9 +52,12 @@ struct TgSample {
     int32_t BC;               // row stride of blk: min(k, 2S) + 2R rounded up to 16
     uint32_t* blk;            // n x BC: this round's block of every anchor, NEW ids then OLD ids
     uint32_t* bsz;            // n: |NEW| | (|NEW|+|OLD|) << 8
-    unsigned long long* wl;   // 3 x n: this round's join work lists (anchor | sizes, by block size)
-    uint32_t* wl_cnt;         // 4: their lengths
+    unsigned long long* wl;   // 3 x (n + TG_MAX_PARTS): this round's join work lists (anchor | sizes), by part of the round and block size
+    uint32_t* wl_cnt;         // TG_WL_LISTS: their lengths
     unsigned long long* scan_tmp; // block sums of the prefix sum
+    int32_t parts, parts_shift;   // a round's anchors are joined in `parts` = 1 << parts_shift parts: v goes to part v % parts, slot v / parts
+    uint32_t* adj;                // ceil(n / parts) x BC x adj_words: of the part in hand, per anchor slot and member, bit x = the
+    int32_t adj_words;            // node at block position x is in that member's list already (2 words for blocks of at most 64, else 4)
 };
 
 struct TgCand {
@@ -69,14 +74,23 @@ void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag /* cl
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
 void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool edges_numbered, hipStream_t s);
-void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int ng_row, int ng_col,
+// work lists of the coming round from the stored blocks: anchor v goes to part v mod parts
+void tg_launch_bin(const TgGraph& g, const TgSample& sm, int parts, hipStream_t s);
+// which members of a block sit in which member's list, for the anchors of one part: sm.adj (run by tg_launch_join);
+// the same, copied to n x 128 x 4 words for inspection
+void tg_launch_adj(const TgGraph& g, const TgSample& sm, int part, hipStream_t s);
+void tg_launch_dump_adj(const TgGraph& g, const TgSample& sm, int part, uint32_t* out, hipStream_t s);
+// local join of the blocks of one part (sm.parts parts in all)
+void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int part, int parts,
                     uint64_t hs_slot, unsigned long long* stat_bins /* 2 x TG_STAT_BINS or null */,
                     hipStream_t s);
 void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, int32_t* sizes, hipStream_t s);
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb,
                               float* out, hipStream_t s);
+// flip: the entries sampled as new for this round become old (first update of a round);
+// number_edges: the sampled edges of the written lists take their arrival numbers (last update before the next sampling)
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, unsigned long long* updates,
-                      bool number_edges, hipStream_t s);
+                      bool flip, bool number_edges, hipStream_t s);
 void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
 void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates, unsigned long long* stat_bins,
                       uint32_t* screen_on /* device flag, used when g.Xq is set */, hipStream_t s);

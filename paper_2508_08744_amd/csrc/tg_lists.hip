@@ -597,15 +597,17 @@ __device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, boo
 // ---------------------------------------------------------------------------------------
 // Section 4.2 list update (phase 1).  The wave that owns list v reads the list and v's
 // candidate slots, drops candidates the list already holds, sorts the rest, merges the two
-// ascending sequences and keeps the first k.  Entries sampled as "new" this round become
-// old; arrivals are new.  Used slots are handed back empty.
+// ascending sequences and keeps the first k.  With `flip` (the first update after a sampling)
+// the entries sampled as "new" this round become old; arrivals are new.  Used slots are handed
+// back empty.  A node without candidates whose list needs neither flips nor numbers costs its
+// slot row only.
 // ---------------------------------------------------------------------------------------
 #define UPDATE_MAX_C 256
 #define UPDATE_SET_WORDS 512     // more than 64 + UPDATE_MAX_C ids
 // REMEASURE (the join ranked on rows rounded to fp16): every arrival is measured again in fp32 from the
 // vectors before the list is written, so the lists and their thresholds hold exact distances.
 template <bool REMEASURE>
-__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg, int64_t v0)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg, int flip, int64_t v0)
 {
     extern __shared__ float smem[];      // REMEASURE: a row of X and 128 words of scratch per wave
     __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
@@ -614,13 +616,6 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     const int64_t v = v0 + (int64_t)blockIdx.x * LISTS_WAVES + wave;
     if (v >= g.n) return;
     const int k = g.k;
-    u32 w = 0;
-    float dist = 0.0f;
-    if (lane < k) {
-        w = g.gid[v * k + lane];
-        dist = g.gdist[v * k + lane];
-    }
-    const float aux_v = join_aux(g, v);          // asked for now, needed at the end
     // all filled slots of v, closed up in LDS (the slots are handed back empty)
     const u64 lt = tg_lanemask_lt();
     int nq = 0;
@@ -629,6 +624,20 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
 #pragma unroll
     for (int j = 0; j < UPDATE_MAX_C / 64; ++j)          // every load is on its way before the first is looked at
         cks[j] = (64 * j + lane < cd.C) ? slot0[64 * j] : TG_EMPTY_KEY;
+    u32 w = 0;
+    float dist = 0.0f;
+    if (!flip && !deg) {
+        // nothing but candidates can change this list now: without any, the slot row was all there is to read
+        bool some = false;
+#pragma unroll
+        for (int j = 0; j < UPDATE_MAX_C / 64; ++j) some |= cks[j] != TG_EMPTY_KEY;
+        if (__ballot(some) == 0ull) return;
+    }
+    if (lane < k) {
+        w = g.gid[v * k + lane];
+        dist = g.gdist[v * k + lane];
+    }
+    const float aux_v = join_aux(g, v);          // asked for now, needed at the end
 #pragma unroll
     for (int j = 0; j < UPDATE_MAX_C / 64; ++j) {
         const bool filled = cks[j] != TG_EMPTY_KEY;
@@ -641,8 +650,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     }
     u32 fresh = w >> 31;
     const u64 mf = __ballot(lane < k && fresh);
-    const bool flip = fresh && __popcll(mf & lt) < S;
-    if (flip) fresh = 0;
+    if (flip && fresh && __popcll(mf & lt) < S) fresh = 0;
     u64 L = lane < k ? tg_key(dist, w & TG_ID_MASK, fresh) : TG_EMPTY_KEY;
 
     const bool any_cand = nq > 0;
@@ -685,7 +693,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         }
     }
     if (deg) number_sampled_edges(v, k, S, tg_key_id(L), ((u32)L & 1u) != 0, deg, g.gid_next);
-    if (!any_cand && mf == 0) return;
+    if (!any_cand && (mf == 0 || !flip)) return;      // the list is what it was
     const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
     if (lane < k) {
         g.gid[v * k + lane] = tg_key_id(L) | (((u32)L & 1u) << 31);
@@ -694,7 +702,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     }
     if (ins && lane == 0) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
 }
-void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool number_edges, hipStream_t s)
+void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool flip, bool number_edges, hipStream_t s)
 {
     if (c.C > UPDATE_MAX_C) return;    // the boundary refuses such C; the queue in LDS holds no more
     // rows rounded for the join whatever their values (not the mode that narrows only where that is exact): measure arrivals again
@@ -704,10 +712,10 @@ void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64
         const dim3 grid((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES));
         if (remeasure)
             hipLaunchKernelGGL(update_kernel<true>, grid, dim3(64 * LISTS_WAVES), shm, s, g, sm.S, c, updates,
-                               number_edges ? sm.deg : (u32*)nullptr, v0);
+                               number_edges ? sm.deg : (u32*)nullptr, flip ? 1 : 0, v0);
         else
             hipLaunchKernelGGL(update_kernel<false>, grid, dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
-                               number_edges ? sm.deg : (u32*)nullptr, v0);
+                               number_edges ? sm.deg : (u32*)nullptr, flip ? 1 : 0, v0);
     });
 }
 

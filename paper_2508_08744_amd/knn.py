@@ -19,8 +19,8 @@ METRICS = {"l2": 0, "ip": 1, "cosine": 2}
 
 class Params(ctypes.Structure):
     _fields_ = [("k", ctypes.c_int32), ("metric", ctypes.c_int32), ("it1", ctypes.c_int32), ("it2", ctypes.c_int32),
-                ("S", ctypes.c_int32), ("R", ctypes.c_int32), ("C", ctypes.c_int32), ("ng_row", ctypes.c_int32),
-                ("ng_col", ctypes.c_int32), ("m", ctypes.c_int32), ("delta", ctypes.c_float),
+                ("S", ctypes.c_int32), ("R", ctypes.c_int32), ("C", ctypes.c_int32), ("parts", ctypes.c_int32),
+                ("m", ctypes.c_int32), ("delta", ctypes.c_float),
                 ("finalize", ctypes.c_int32), ("screen", ctypes.c_int32), ("join_f16", ctypes.c_int32),
                 ("seed", ctypes.c_uint64)]
 
@@ -46,7 +46,7 @@ class Stats(ctypes.Structure):
 EXPORTS = ["tg_knn_default_params", "tg_knn_workspace_bytes", "tg_knn_build", "tg_knn_build_ex", "tg_knn_create",
            "tg_knn_destroy", "tg_knn_init", "tg_knn_phase1_round", "tg_knn_begin_phase2", "tg_knn_phase2_round",
            "tg_knn_finalize", "tg_knn_get_stats", "tg_knn_export", "tg_knn_import", "tg_knn_sample_blocks",
-           "tg_knn_join_distances", "tg_exact_knn", "tg_exact_knn_static", "tg_exact_knn_static_scratch_bytes", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_prune_dispersion", "tg_angle_at", "tg_merge_local", "tg_lists_clear",
+           "tg_knn_join_distances", "tg_knn_block_adjacency", "tg_exact_knn", "tg_exact_knn_static", "tg_exact_knn_static_scratch_bytes", "tg_prune_rank", "tg_prune_dist", "tg_prune_angle", "tg_prune_dispersion", "tg_angle_at", "tg_merge_local", "tg_lists_clear",
            "tg_last_error"]
 
 _lib = None
@@ -78,6 +78,7 @@ def lib():
         L.tg_knn_import.argtypes = [vp, vp, vp, vp]
         L.tg_knn_sample_blocks.argtypes = [vp, vp, vp]
         L.tg_knn_join_distances.argtypes = [vp, vp, vp, i64, vp]
+        L.tg_knn_block_adjacency.argtypes = [vp, vp]
         L.tg_exact_knn.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         L.tg_exact_knn_static.argtypes = [vp, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         L.tg_exact_knn_static_scratch_bytes.restype = sz
@@ -234,6 +235,12 @@ class Builder:
         sizes = torch.empty((self.n, 2), dtype=torch.int32, device=dev)
         _check(lib().tg_knn_sample_blocks(self._h, blk.data_ptr(), sizes.data_ptr()))
         return blk, sizes
+
+    def block_adjacency(self):
+        """For the blocks last sampled: uint32 n x 128 x 4, bit x of entry (v, p) = position x of v's block is in position p's list."""
+        adj = torch.zeros((self.n, 128, 4), dtype=torch.int32, device=self.X.device)
+        _check(lib().tg_knn_block_adjacency(self._h, adj.data_ptr()))
+        return adj
 
     def join_distances(self, blk, sizes):
         dev = self.X.device

@@ -56,7 +56,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
         assert lib.tg_last_error()
     assert lib.tg_knn_build(None, 100, 4, 5, 0, 4, 1, fake, None, None) == -1
     assert lib.tg_knn_build(fake, 100, 4, 5, 0, 4, 1, None, None, None) == -1
-    for field, val in [("C", 48), ("C", 8), ("S", 0), ("S", 33), ("R", 33), ("ng_row", 3), ("ng_col", 16), ("m", 0),
+    for field, val in [("C", 48), ("C", 8), ("S", 0), ("S", 33), ("R", 33), ("parts", 3), ("parts", 16), ("parts", 0), ("m", 0),
                        ("it1", 70), ("delta", 2.0), ("screen", 2), ("join_f16", 3), ("join_f16", -1)]:
         p = knn.default_params(8, 4)
         setattr(p, field, val)

@@ -20,8 +20,7 @@ RECALL_TOL = 0.005      # spec tolerance for recall against the oracle
 
 
 def _oracle_for(X, prm, metric=0):
-    return oracle.NNDescent(X, prm.k, metric=metric, S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16,
-                            ng_row=prm.ng_row, ng_col=prm.ng_col, m=prm.m, seed=prm.seed)
+    return oracle.NNDescent(X, prm.k, metric=metric, **oracle.device_model(prm))
 
 
 def _same(gpu_graph, oracle_graph):
@@ -102,14 +101,47 @@ def test_join_distance_rejects_bad_blocks():
     b.close()
 
 
+@pytest.mark.parametrize("n,d,k,kw", [(2000, 64, 32, dict(parts=4)), (700, 16, 48, dict(parts=2, R=32)), (500, 8, 64, dict(parts=1)),
+                                      (900, 24, 10, dict(parts=8, S=4, R=20))])
+def test_block_adjacency_words_are_the_lists(n, d, k, kw):
+    """What the join is told about a block, "the node at position x is in position p's list already", against the
+    definition, for every member of every block (blocks of up to 128 members, ids that share a table slot)."""
+    X = inputs.make("C2", n=n, d=d, comps=4)
+    prm = knn.default_params(k, 6, seed=11, **kw)
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    b.init()
+    for r in range(3):
+        blk, sizes = b.sample_blocks()
+        adj = b.block_adjacency()
+        blk, sizes = blk.cpu().numpy(), sizes.cpu().numpy()
+        adj = adj.cpu().numpy().view(np.uint32)
+        ids = b.graph()[0].cpu().numpy()
+        for v in range(n):
+            nT = int(sizes[v].sum())
+            if sizes[v, 0] == 0 or nT < 2:
+                assert not adj[v].any()
+                continue
+            mem = blk[v, :nT]
+            pos = {int(x): i for i, x in enumerate(mem)}
+            want = np.zeros((128, 4), dtype=np.uint32)
+            for p in range(nT):
+                for c in ids[mem[p]]:
+                    x = pos.get(int(c))
+                    if x is not None:
+                        want[p, x >> 5] |= np.uint32(1 << (x & 31))
+            assert (adj[v] == want).all(), (r, v)
+        b.phase1_round()
+    b.close()
+
+
 STEPWISE = [
     # n, d, k, overrides: several tiles, ragged tails, odd d (padded rows), small and large caps
-    (3000, 64, 32, dict(C=64, ng_row=4, ng_col=8)),
-    (2500, 100, 16, dict(C=32, ng_row=2, ng_col=2, R=8)),
-    (1200, 30, 10, dict(C=16, ng_row=2, ng_col=4, S=6, R=20)),
-    (1500, 132, 32, dict(C=128, ng_row=4, ng_col=4)),
-    (900, 7, 48, dict(C=64, ng_row=2, ng_col=8, R=32)),
-    (400, 16, 64, dict(C=128, ng_row=4, ng_col=2, m=3)),
+    (3000, 64, 32, dict(C=64, parts=4)),
+    (2500, 100, 16, dict(C=32, parts=1, R=8)),
+    (1200, 30, 10, dict(C=16, parts=2, S=6, R=20)),
+    (1500, 132, 32, dict(C=128, parts=8)),
+    (900, 7, 48, dict(C=64, parts=2, R=32)),
+    (400, 16, 64, dict(C=128, parts=4, m=3)),
     (1000, 256, 32, dict(C=256)),          # long rows: the workgroup join with 128-column slabs
     (1400, 128, 32, dict(C=256)),          # the bench shape of rows and slots
 ]
@@ -496,7 +528,7 @@ def test_f16_join_distance_tile(d):
 
 @pytest.mark.parametrize("n,d,k,kw", [(3000, 64, 32, dict(C=64)), (1400, 128, 32, dict(C=256)), (1200, 30, 10, dict(C=32)),
                                       (1500, 100, 24, dict(C=128)), (900, 256, 32, dict(C=64)), (800, 300, 48, dict(C=128)),
-                                      (1000, 64, 16, dict(C=32, ng_row=2, ng_col=4))])
+                                      (1000, 64, 16, dict(C=32, parts=2))])
 def test_f16_join_is_exact_on_representable_data(n, d, k, kw):
     """Byte-valued features (and eighths of them) are f16 numbers: the rounded copy is exact, products and sums are
     exact in fp32, so the graph must equal the oracle's bit for bit."""
@@ -536,7 +568,7 @@ def test_f16_join_statistical_parity_on_real_valued_data(cfg, metric):
     assert np.mean(gaps) >= -RECALL_TOL, gaps
 
 
-@pytest.mark.parametrize("n,d,k,kw", [(2000, 128, 32, dict(C=128)), (1200, 200, 16, dict(C=64)), (1500, 48, 24, dict(C=64, ng_row=2, ng_col=2))])
+@pytest.mark.parametrize("n,d,k,kw", [(2000, 128, 32, dict(C=128)), (1200, 200, 16, dict(C=64)), (1500, 48, 24, dict(C=64, parts=1))])
 def test_f16_join_only_where_exact(n, d, k, kw):
     """join_f16 = 2 narrows only when every value is an f16 number: on such data the graph equals the oracle's, on
     real-valued data it equals the fp32 join's, bit for bit either way."""

@@ -126,7 +126,7 @@ def test_whole_build_random_cases():
         d = int(rng.choice([1, 2, 3, 5, 8, 16, 24, 31, 32, 48, 64, 65, 96, 100, 128, 130, 200, 256]))
         k = int(rng.choice([1, 2, 5, 8, 10, 16, 17, 24, 32, 33, 40, 48, 64]))
         k = min(k, n - 1)
-        kw = dict(C=int(rng.choice([16, 32, 64, 128, 256])), ng_row=int(rng.choice([2, 4])), ng_col=int(rng.choice([2, 4, 8])),
+        kw = dict(C=int(rng.choice([16, 32, 64, 128, 256])), parts=int(rng.choice([1, 2, 4, 8])),
                   m=int(rng.integers(1, 5)), S=int(rng.integers(1, 33)), R=int(rng.integers(0, 33)))
         it1, it2 = int(rng.integers(0, 4)), int(rng.integers(0, 4))
         shrink = 1 if d <= 128 else 4                                   # squared norms stay below 2^23
@@ -134,8 +134,7 @@ def test_whole_build_random_cases():
         metric = str(rng.choice(["l2", "l2", "ip"]))                     # both are exact on these integers
         prm = knn.default_params(k, 6, metric=metric, seed=int(rng.integers(1, 1000)), it1=it1, it2=it2, **kw)
         ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
-        o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row, ng_col=prm.ng_col,
-                             m=prm.m, seed=int(prm.seed))
+        o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], **oracle.device_model(prm))
         o.run(it1, it2)
         oi, od, _ = o.graph()
         where = dict(case=case, n=n, d=d, k=k, metric=metric, it1=it1, it2=it2, seed=int(prm.seed), **kw)
@@ -155,8 +154,7 @@ def test_whole_build_with_ties_everywhere(metric):
         for it1, it2 in ((3, 0), (2, 2)):
             prm = knn.default_params(k, 4, metric=metric, seed=7, it1=it1, it2=it2, C=128)
             ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
-            o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row,
-                                 ng_col=prm.ng_col, m=prm.m, seed=7)
+            o = oracle.NNDescent(X, k, metric=knn.METRICS[metric], **oracle.device_model(prm))
             o.run(it1, it2)
             oi, od, _ = o.graph()
             where = dict(n=n, d=d, k=k, it1=it1, it2=it2)
@@ -172,7 +170,7 @@ def test_longest_rows(d, join_f16):
     X = rng.integers(0, 4, size=(n, d)).astype(np.float32)
     prm = knn.default_params(k, 4, seed=2, C=32, join_f16=join_f16)
     ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
-    o = oracle.NNDescent(X, k, S=prm.S, R=prm.R, C=prm.C, retain=1, tile=16, ng_row=prm.ng_row, ng_col=prm.ng_col, m=prm.m, seed=2)
+    o = oracle.NNDescent(X, k, **oracle.device_model(prm))
     o.run(prm.it1, prm.it2)
     oi, od, _ = o.graph()
     assert (ids.cpu().numpy() == oi).all()
