@@ -122,9 +122,11 @@ typedef struct tg_knn_stats {
 
 typedef struct tg_knn_handle tg_knn_handle;
 
-/* Defaults for a given k and total round budget: it1 = ceil(iters/2), it2 = iters - it1
- * (section 7.3: it1 = it2), S = min(k,32), R = 32, C = 64, parts = 4, m = 2,
- * delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with delta = 0.001. */
+/* Defaults for a given k and total round budget.  From 8 rounds on it1 = ceil(iters/2), it2 = iters - it1
+ * (section 7.3: it1 = it2); a smaller budget goes to the first phase first (it1 = min(iters, 4)), which is
+ * the one that converges while the lists are poor (section 3.1.2).  S = min(k,32), R = 32, C = 64,
+ * parts = 2, m = 2, delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with
+ * delta = 0.001. */
 int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);
 
 /* Device bytes a build of this size needs as workspace, for an X that is 16-byte aligned (rows of d % 4 == 0
@@ -137,7 +139,7 @@ size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_params* p);
  * int32.  out_dist: device, n x k fp32, may be NULL.  Takes and returns its own workspace in
  * stream order (hipMallocAsync / hipFreeAsync on `stream`: no wait; with iters > 0 the call
  * only enqueues work).  Runs with tg_knn_default_params(k, iters).
- * iters > 0: exactly it1 = ceil(iters/2) and it2 = iters - it1 rounds; iters <= 0: up to
+ * iters > 0: exactly that many rounds, split as tg_knn_default_params says; iters <= 0: up to
  * 16 rounds with early stop.  Valid iff 1 <= k <= 64, k < n < 2^30, 1 <= d <= 4096.
  */
 int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int32_t metric, int32_t iters,

@@ -59,12 +59,14 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->metric = TG_METRIC_L2;
     p->delta = 0.0f;
     if (iters <= 0) { iters = 16; p->delta = 0.001f; }
-    p->it1 = (iters + 1) / 2;
+    // the first phase converges fastest while the lists are poor (section 3.1.2): it gets the first four rounds and,
+    // beyond eight, every other one
+    p->it1 = iters < 4 ? iters : (iters + 1) / 2 > 4 ? (iters + 1) / 2 : 4;
     p->it2 = iters - p->it1;
     p->S = k < 32 ? (k < 1 ? 1 : k) : 32;
     p->R = 32;
     p->C = 64;
-    p->parts = 4;
+    p->parts = 2;
     p->m = 2;
     p->finalize = 1;
     p->screen = 1;

@@ -23,8 +23,8 @@
 #define JOIN_THREADS 256
 #define JOIN_CELLS 8                                   // cells per member: one per group of eight positions (mod 8)
 #define JOIN_CELL_BYTES (TG_BLOCK_COLS * JOIN_CELLS * 8)   // workgroup kernel: all cells of a block
-#define T8_SLOTS 2048                                  // table of a block's ids: hash -> block position, one word each
-#define T8_FREE 128u                                   // "no member" (positions are 0..127)
+#define T8_SLOTS 4096                                  // table of a block's ids: hash -> block position, one byte each
+#define T8_FREE 255u                                   // "no member" (positions are 0..127)
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
@@ -67,23 +67,27 @@ __device__ inline float gram_to_dist(float gram, float aux_a, float aux_b)
 // ---------------------------------------------------------------------------------------
 // Which members of a block sit in which member's list already: sm.adj, per anchor of the part
 // (slot v / parts) and member p, adj_words words whose bit x says "the node at position x of
-// the block is in p's list".  One wave per anchor.  The block's ids go into a table in LDS,
-// T8[hash(id)] = block position (of two ids with one hash the later writer stays and the other
-// goes to a short list that every look-up also walks); lane p then reads member p's list and
-// looks every entry up: hash, the table word, the id at that position, one comparison.
+// the block is in p's list".  One wave per anchor.  The block's ids (distinct) go into an
+// open-addressed table in LDS, T8[hash(id) + probes] = block position, a byte each.  The members'
+// lists are then read as one run of 16-byte pieces, 64 pieces per load, so consecutive lanes
+// read consecutive pieces of one list; every id of a piece is looked up (hash, table byte, the
+// id at that position, the next byte while the place is taken by another id) and a hit sets its
+// bit in LDS, from where the words go out in one run.
 // The lists are read as they stand when this part of the round begins.
 // ---------------------------------------------------------------------------------------
 __device__ inline u32 t8_hash(u32 id)
 {
     const u32 x = id ^ (id >> 11);
-    return (u32)__umul24(x, 0x9E3779u) >> 21;      // 11 bits of a 24 x 24 bit product (the intrinsic's type is signed)
+    return (u32)__umul24(x, 0x9E3779u) >> 20;      // 12 bits of a 24 x 24 bit product (the intrinsic's type is signed)
 }
 #define ADJ_WAVES 4
+#define ADJ_UNROLL 8
 struct AdjShared {
-    int ids[TG_BLOCK_COLS + 4];        // entry T8_FREE is no id
-    u32 T8[T8_SLOTS];
-    u32 stash_id[TG_BLOCK_COLS], stash_pos[TG_BLOCK_COLS];
+    int ids[TG_BLOCK_COLS + 4];
+    u32 adjw[TG_BLOCK_COLS * 4];
+    unsigned char T8[T8_SLOTS];
 };
+template <bool VEC>
 __global__ __launch_bounds__(64 * ADJ_WAVES) void adj_kernel(TgGraph g, TgSample sm, int part, int64_t nslots)
 {
     __shared__ AdjShared shs[ADJ_WAVES];
@@ -91,14 +95,17 @@ __global__ __launch_bounds__(64 * ADJ_WAVES) void adj_kernel(TgGraph g, TgSample
     AdjShared& sh = shs[wave];
     const int k = g.k;
     const u32 idmax = (u32)(g.n - 1);
-    const bool lvec = (k & 3) == 0;                // rows of the lists are 16-byte aligned
+    constexpr int W = VEC ? 4 : 1;                 // ids per piece; VEC: rows of the lists are 16-byte aligned (k % 4 == 0)
+    const int per = k / W;                         // pieces per list
+    const int per_sh = (per & (per - 1)) == 0 ? __ffs(per) - 1 : -1;
+    const int aw = sm.adj_words, aw_sh = __ffs(aw) - 1;
     auto lds_fence = [&]() {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
-    for (int c = lane; c < T8_SLOTS; c += 64) sh.T8[c] = T8_FREE;
+    for (int c = lane; c < T8_SLOTS / 4; c += 64) reinterpret_cast<u32*>(sh.T8)[c] = 0xFFFFFFFFu;
     if (lane < 4) sh.ids[TG_BLOCK_COLS + lane] = -1;
-    u32 my_h[2] = {0u, 0u};
+    u32 my_s[2] = {0u, 0u};
     bool my_in[2] = {false, false};
     for (int64_t a = (int64_t)blockIdx.x * ADJ_WAVES + wave; a < nslots; a += (int64_t)gridDim.x * ADJ_WAVES) {
         const int64_t v = a * sm.parts + part;
@@ -107,87 +114,89 @@ __global__ __launch_bounds__(64 * ADJ_WAVES) void adj_kernel(TgGraph g, TgSample
         const int nN = (int)(z & 0xFFu), nT = (int)(z >> 8);
         if (nN == 0 || nT < 2 || nT > sm.BC || nT > TG_BLOCK_COLS || nN > nT) continue;      // no join for this anchor
         const u32* bids = sm.blk + v * (int64_t)sm.BC;
-        // The table of the block's ids: the last block's entries out, this block's in.  Lanes meet in the table's
-        // words (a lane reads back the word it wrote to learn whether another lane's id took it), so these accesses
-        // are volatile: the value read is the one in LDS, never one the compiler remembers having stored.
-        volatile u32* T8v = sh.T8;
+        // The table of the block's ids: the last block's entries out, this block's in.  Lanes meet in the table
+        // (a lane reads back the byte it wrote to learn whether another lane's id took the place), so these
+        // accesses are volatile: the value read is the one in LDS, never one the compiler remembers having stored.
+        volatile unsigned char* T8v = sh.T8;
         lds_fence();
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            if (my_in[h]) T8v[my_h[h]] = T8_FREE;
+            if (my_in[h]) T8v[my_s[h]] = (unsigned char)T8_FREE;
+        for (int c = lane; c < nT * 4; c += 64) sh.adjw[c] = 0u;
         lds_fence();
-        u32 id[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int p = lane + 64 * h;
             my_in[h] = p < nT;
-            id[h] = my_in[h] ? min(bids[p], idmax) : 0u;
-            my_h[h] = t8_hash(id[h]);
-            sh.ids[p] = my_in[h] ? (int)id[h] : -1;
-            if (my_in[h]) T8v[my_h[h]] = (u32)p;
+            const u32 id = my_in[h] ? min(bids[p], idmax) : 0u;
+            my_s[h] = t8_hash(id);
+            sh.ids[p] = my_in[h] ? (int)id : -1;
         }
-        lds_fence();
-        int nstash = 0;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const bool lost = my_in[h] && T8v[my_h[h]] != (u32)(lane + 64 * h);
-            const u64 ml = __ballot(lost);
-            if (lost) {
-                const int s = nstash + __popcll(ml & tg_lanemask_lt());
-                sh.stash_id[s] = id[h];
-                sh.stash_pos[s] = (u32)(lane + 64 * h);
+        for (int h = 0; h < (nT > 64 ? 2 : 1); ++h) {
+            const u32 p = (u32)(lane + 64 * h);
+            bool pending = my_in[h];
+            while (__ballot(pending)) {                  // at most nT turns: the table has room for every member
+                if (pending && T8v[my_s[h]] == T8_FREE) T8v[my_s[h]] = (unsigned char)p;
+                lds_fence();
+                if (pending) {
+                    if (T8v[my_s[h]] == p) pending = false;
+                    else my_s[h] = (my_s[h] + 1u) & (T8_SLOTS - 1);
+                }
+                lds_fence();
             }
-            nstash += __popcll(ml);
         }
         lds_fence();
-        // member p = lane (+ 64): every entry of its list is looked up in the table
-        const int npass = nT > 64 ? 2 : 1;
-        for (int h = 0; h < npass; ++h) {
-            const int p = lane + 64 * h;
-            const bool live_p = p < nT;
-            const u32* lrow = g.gid + (int64_t)(live_p ? id[h] : id[0]) * k;
-            u32 mask[4] = {0u, 0u, 0u, 0u};
-            for (int j0 = 0; j0 < k; j0 += 32) {
-                u32 lid[32];
-                if (lvec) {
+        const int total = nT * per;
+        for (int base = 0; base < total; base += 64 * ADJ_UNROLL) {
+            u32 lid[ADJ_UNROLL][W];
+            int mm[ADJ_UNROLL];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const int j = j0 + 4 * q;
-                        const uint4 t = *reinterpret_cast<const uint4*>(lrow + (j < k ? j : 0));
-                        lid[4 * q] = t.x; lid[4 * q + 1] = t.y; lid[4 * q + 2] = t.z; lid[4 * q + 3] = t.w;
-                    }
+            for (int u = 0; u < ADJ_UNROLL; ++u) {
+                const int idx = base + 64 * u + lane;
+                const bool ok = idx < total;
+                const int ii = ok ? idx : 0;
+                const int m = per_sh >= 0 ? ii >> per_sh : ii / per;
+                const int q = ii - m * per;
+                const u32* src = g.gid + (int64_t)sh.ids[m] * k + q * W;
+                if (VEC) {
+                    const uint4 t = *reinterpret_cast<const uint4*>(src);
+                    lid[u][0] = t.x; lid[u][W > 1 ? 1 : 0] = t.y; lid[u][W > 2 ? 2 : 0] = t.z; lid[u][W > 3 ? 3 : 0] = t.w;
                 } else {
-#pragma unroll
-                    for (int q = 0; q < 32; ++q) lid[q] = lrow[j0 + q < k ? j0 + q : 0];
+                    lid[u][0] = *src;
                 }
+                mm[u] = ok ? m : -1;
+            }
 #pragma unroll
-                for (int q = 0; q < 32; ++q) {
-                    const u32 cid = lid[q] & TG_ID_MASK;
-                    const bool live = live_p && j0 + q < k;
-                    const u32 e = T8v[t8_hash(cid)];
-                    const bool hit = live && (u32)sh.ids[e] == cid;
+            for (int u = 0; u < ADJ_UNROLL; ++u) {
+                if (base + 64 * u >= total) break;       // (wave-uniform)
 #pragma unroll
-                    for (int wd = 0; wd < 4; ++wd) mask[wd] |= (hit && (e >> 5) == (u32)wd) ? (1u << (e & 31u)) : 0u;
-                    for (int s = 0; s < nstash; ++s) {             // nearly always empty
-                        const bool hit2 = live && sh.stash_id[s] == cid;
-                        const u32 e2 = sh.stash_pos[s];
-#pragma unroll
-                        for (int wd = 0; wd < 4; ++wd) mask[wd] |= (hit2 && (e2 >> 5) == (u32)wd) ? (1u << (e2 & 31u)) : 0u;
+                for (int w = 0; w < W; ++w) {
+                    const u32 cid = lid[u][w] & TG_ID_MASK;
+                    u32 s = t8_hash(cid);
+                    u32 e = mm[u] >= 0 ? (u32)sh.T8[s] : T8_FREE;
+                    while (e != T8_FREE) {               // ends at a free place: the table is never full
+                        if ((u32)sh.ids[e] == cid) {
+                            atomicOr(&sh.adjw[mm[u] * 4 + (int)(e >> 5)], 1u << (e & 31u));
+                            break;
+                        }
+                        s = (s + 1u) & (T8_SLOTS - 1);
+                        e = sh.T8[s];
                     }
                 }
             }
-            if (live_p) {
-                u32* out = sm.adj + (a * sm.BC + p) * (int64_t)sm.adj_words;
-                for (int wd = 0; wd < sm.adj_words; ++wd) out[wd] = wd == 0 ? mask[0] : wd == 1 ? mask[1] : wd == 2 ? mask[2] : mask[3];
-            }
         }
+        lds_fence();
+        u32* out = sm.adj + a * sm.BC * (int64_t)aw;
+        for (int c = lane; c < nT * aw; c += 64) out[c] = sh.adjw[(c >> aw_sh) * 4 + (c & (aw - 1))];
     }
 }
 void tg_launch_adj(const TgGraph& g, const TgSample& sm, int part, hipStream_t s)
 {
     const int64_t nslots = (g.n + sm.parts - 1) / sm.parts;
     const int64_t wgs = (nslots + ADJ_WAVES - 1) / ADJ_WAVES;
-    hipLaunchKernelGGL(adj_kernel, dim3((unsigned)(wgs < 8192 ? wgs : 8192)), dim3(64 * ADJ_WAVES), 0, s, g, sm, part, nslots);
+    const dim3 grid((unsigned)(wgs < 16384 ? wgs : 16384)), block(64 * ADJ_WAVES);
+    if ((g.k & 3) == 0) hipLaunchKernelGGL(adj_kernel<true>, grid, block, 0, s, g, sm, part, nslots);
+    else hipLaunchKernelGGL(adj_kernel<false>, grid, block, 0, s, g, sm, part, nslots);
 }
 
 // the stored adjacency words of one part -> the boundary's fixed n x 128 x 4 layout (test interface)

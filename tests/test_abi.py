@@ -33,6 +33,8 @@ def test_default_params_follow_the_paper():
     assert p.delta == 0.0 and p.k == 32
     p = knn.default_params(16, 7)
     assert (p.it1, p.it2, p.S) == (4, 3, 16)
+    # a budget below eight rounds goes to the first phase first
+    assert [(q.it1, q.it2) for q in (knn.default_params(32, i) for i in (1, 3, 4, 5, 8, 9))] == [(1, 0), (3, 0), (4, 0), (4, 1), (4, 4), (5, 4)]
     p = knn.default_params(32, 0)
     assert p.it1 + p.it2 == 16 and p.delta > 0
 
@@ -102,7 +104,7 @@ def test_workspace_fits_the_largest_configuration():
     # the 1e8 x 96 configuration must fit one MI355X (288 GB) together with its vectors and outputs
     from paper_2508_08744_amd import inputs, knn
     cfg = inputs.CONFIGS["C5"]
-    p = knn.default_params(cfg["k"], 12)
+    p = knn.default_params(cfg["k"], 12, parts=8)      # (the adjacency words of one part are n / parts * 2 KB)
     ws = knn.workspace_bytes(cfg["n"], cfg["d"], p)
     total = ws + cfg["n"] * cfg["d"] * 4 + cfg["n"] * cfg["k"] * 8
     assert total < 288e9, total / 1e9

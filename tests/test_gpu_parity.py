@@ -332,6 +332,44 @@ def test_statistical_parity_on_real_valued_data(cfg, metric):
     assert np.mean(gaps) >= -RECALL_TOL, gaps
 
 
+@pytest.mark.parametrize("cfg,n", [("C1", 10000), ("C2", 20000)])
+def test_recall_against_the_plain_oracle(cfg, n):
+    """The plain entry point against the plain method (O-NND's reference mode: every evaluated pair offered to both
+    nodes, unbounded candidate lists, one list update per round; section 3.1.1, Algorithm 1) at equal rounds:
+    recall within 0.005."""
+    c = inputs.CONFIGS[cfg]
+    k, mcode = c["k"], knn.METRICS[c["metric"]]
+    X = inputs.make(cfg, n=n)
+    rows = inputs.sample_rows(n, 2000, seed=4)
+    truth, _ = oracle.brute_force_knn(X, k, mcode, rows)
+    Xg = torch.from_numpy(X).cuda()
+    gaps = []
+    for seed in (1, 2):
+        ids, _ = knn.knn_build(Xg, k, c["metric"], iters=4, seed=seed)
+        prm = knn.default_params(k, 4, metric=c["metric"], seed=seed)
+        plain = oracle.NNDescent(X, k, mcode, S=prm.S, R=prm.R, m=prm.m, seed=seed)
+        plain.run(prm.it1, prm.it2)
+        r_gpu = oracle.recall(ids.cpu().numpy()[rows], truth)
+        r_plain = oracle.recall(plain.graph()[0][rows], truth)
+        assert r_plain > 0.95
+        gaps.append(r_gpu - r_plain)
+    assert min(gaps) >= -RECALL_TOL, gaps
+
+
+def test_whole_build_identical_to_oracle_at_mid_size():
+    """Every step of a build of 50 000 points (d = 128, k = 32: the C2 recipe, wave and workgroup kernels, many
+    blocks per slot line) against the model of its hand-over: ids and distances bit for bit."""
+    n, k = 50000, 32
+    X = inputs.make("C2", n=n)
+    prm = knn.default_params(k, 0, seed=5, it1=2, it2=1, delta=0.0)
+    ids, dist, st = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
+    o = _oracle_for(X, prm)
+    assert o.run(prm.it1, prm.it2) == (st["rounds_phase1"], st["rounds_phase2"])
+    oi, od, _ = o.graph()
+    assert (ids.cpu().numpy() == oi).all()
+    assert (dist.cpu().numpy().astype(np.float64) == od).all()
+
+
 def test_phase1_lists_keep_their_invariants_without_finalize():
     X = inputs.make("C1", n=4000)
     prm = knn.default_params(16, 8, seed=3)
