@@ -108,7 +108,6 @@ struct tg_knn_handle {
     bool phase2;
     bool norms_done;
     bool lists_ready;    // tg_knn_init or tg_knn_import has written the lists
-    bool edges_numbered; // the kernel that wrote the current lists has numbered their sampled edges (deg, gid_next)
     // timing
     std::vector<hipEvent_t> ev;
     struct Span { int kind, round, e0, e1; };
@@ -147,8 +146,10 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.f16_ok = h->d_f16_ok;
     h->g.Xh = h->xh;
     h->sm.S = p.S; h->sm.R = p.R;
-    h->sm.deg = c.take<u32>(n);
-    h->sm.off = c.take<u64>(n + 1);
+    h->sm.bshift = tg_rev_bucket_shift(n);
+    h->sm.nbuckets = (n + (1ll << h->sm.bshift) - 1) >> h->sm.bshift;
+    h->sm.bcnt = c.take<u32>((size_t)h->sm.nbuckets);
+    h->sm.boff = c.take<u64>((size_t)h->sm.nbuckets + 1);
     h->sm.csr = c.take<u32>((size_t)n * p.k);
     {
         const int fwd = p.k < 2 * p.S ? p.k : 2 * p.S;
@@ -158,11 +159,18 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->sm.bsz = c.take<u32>(n);
     h->sm.wl = c.take<u64>((size_t)3 * (n + TG_MAX_PARTS));
     h->sm.wl_cnt = c.take<u32>(TG_WL_LISTS);
-    h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(n));
+    h->sm.scan_tmp = c.take<u64>(tg_scan_tmp_elems(h->sm.nbuckets));
     h->sm.parts = p.parts;
     h->sm.parts_shift = p.parts == 8 ? 3 : p.parts == 4 ? 2 : p.parts == 2 ? 1 : 0;
     h->sm.adj_words = h->sm.BC > 64 ? 4 : 2;
-    h->sm.adj = c.take<u32>((size_t)((n + p.parts - 1) / p.parts) * h->sm.BC * h->sm.adj_words);
+    {
+        // the adjacency words of a part and the edges by bucket are never alive together: one place for both
+        const size_t adj_bytes = (size_t)((n + p.parts - 1) / p.parts) * h->sm.BC * h->sm.adj_words * sizeof(u32);
+        const size_t ebuf_bytes = (size_t)n * p.k * sizeof(u64);
+        u64* both = c.take<u64>((adj_bytes > ebuf_bytes ? adj_bytes : ebuf_bytes) / sizeof(u64) + 1);
+        h->sm.adj = reinterpret_cast<u32*>(both);
+        h->sm.ebuf = both;
+    }
     h->cd.C = p.C;
     h->cd.slots = c.take<u64>((size_t)n * p.C);
     h->d_updates = c.take<u64>((size_t)TG_MAX_ROUNDS * TG_STAT_BINS);
@@ -226,9 +234,8 @@ extern "C" int tg_knn_create(tg_knn_handle** out, const float* X, int64_t n, int
     h->phase2 = false;
     h->norms_done = false;
     h->lists_ready = false;
-    h->edges_numbered = false;
     if (h->x_padded) tg_launch_pad_rows(X, n, d, h->x_padded, h->g.ld, h->stream);
-    tg_launch_fill_u32(h->sm.deg, (size_t)n, 0u, h->stream);
+    tg_launch_fill_u32(h->sm.bcnt, (size_t)h->sm.nbuckets, 0u, h->stream);
     tg_launch_fill_u64(h->cd.slots, (size_t)n * p->C, TG_EMPTY_KEY, h->stream);
     tg_launch_fill_u64(h->d_updates, (size_t)TG_MAX_ROUNDS * TG_STAT_BINS, 0ull, h->stream);
     tg_launch_fill_u64(h->d_stat_bins, (size_t)TG_MAX_ROUNDS * 2 * TG_STAT_BINS, 0ull, h->stream);
@@ -272,10 +279,8 @@ extern "C" int tg_knn_init(tg_knn_handle* h)
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     ensure_norms(h);
     int sp = begin_span(h, SPAN_INIT, 0);
-    if (h->edges_numbered) tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);   // numbers nobody used
-    tg_launch_init(h->g, tg_hash_seed(h->p.seed, TG_TAG_INIT), &h->sm, h->stream);
+    tg_launch_init(h->g, tg_hash_seed(h->p.seed, TG_TAG_INIT), h->stream);
     end_span(h, sp);
-    h->edges_numbered = true;
     h->round = h->rounds1 = h->rounds2 = 0;
     h->phase2 = false;
     h->lists_ready = true;
@@ -294,9 +299,7 @@ static int read_updates(tg_knn_handle* h, int round, int64_t* updates)
     return TG_OK;
 }
 
-// number_next: the list update also numbers the sampled edges of the lists it writes, which
-// saves the next phase-1 round its counting pass (pointless after the last one)
-static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
+static int phase1_round(tg_knn_handle* h, int64_t* updates)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
@@ -304,8 +307,7 @@ static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
     if (h->round >= TG_MAX_ROUNDS) return fail(TG_ERR_INVALID_ARG, "more than %d rounds", TG_MAX_ROUNDS);
     const int r = h->round;
     int sp = begin_span(h, SPAN_SAMPLE, r);
-    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->edges_numbered, h->stream);
-    h->edges_numbered = false;
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(r)), h->stream);
     tg_launch_bin(h->g, h->sm, h->p.parts, h->stream);
     end_span(h, sp);
     for (int part = 0; part < h->p.parts; ++part) {
@@ -315,28 +317,22 @@ static int phase1_round(tg_knn_handle* h, int64_t* updates, bool number_next)
                        h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
         end_span(h, sp);
         sp = begin_span(h, SPAN_UPDATE, r);
-        tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, part == 0,
-                         number_next && part + 1 == h->p.parts, h->stream);
+        tg_launch_update(h->g, h->sm, h->cd, h->d_updates + (size_t)r * TG_STAT_BINS, part == 0, h->stream);
         end_span(h, sp);
     }
-    h->edges_numbered = number_next;
     h->round++;
     h->rounds1++;
     int rc = launch_status("phase-1 round");
     if (rc != TG_OK) return rc;
     return updates ? read_updates(h, r, updates) : TG_OK;
 }
-extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates) { return phase1_round(h, updates, true); }
+extern "C" int tg_knn_phase1_round(tg_knn_handle* h, int64_t* updates) { return phase1_round(h, updates); }
 
 extern "C" int tg_knn_begin_phase2(tg_knn_handle* h)
 {
     if (!h) return fail(TG_ERR_INVALID_ARG, "handle is NULL");
     if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     tg_launch_mark_all_fresh(h->g, h->stream);
-    if (h->edges_numbered) {   // phase 2 reuses the buffer that holds the numbers
-        tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
-        h->edges_numbered = false;
-    }
     if (h->xq) tg_launch_fill_u32(h->d_screen_on, 1, 1u, h->stream);
     if (!h->phase2 && h->xq) {
         ensure_norms(h);
@@ -448,8 +444,6 @@ extern "C" int tg_knn_import(tg_knn_handle* h, const int32_t* ids, const float* 
                 return fail(TG_ERR_INVALID_ARG, "row %lld: id %d out of range", (long long)(i / h->g.k), hi[i]);
     }
     ensure_norms(h);
-    if (h->edges_numbered) tg_launch_fill_u32(h->sm.deg, (size_t)h->g.n, 0u, h->stream);
-    h->edges_numbered = false;
     tg_launch_import(h->g, ids, dist, fresh, h->stream);
     h->lists_ready = true;
     return launch_status("import");
@@ -459,8 +453,7 @@ extern "C" int tg_knn_sample_blocks(tg_knn_handle* h, int32_t* blk, int32_t* siz
 {
     if (!h || !blk || !sizes) return fail(TG_ERR_INVALID_ARG, "NULL argument");
     if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
-    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->edges_numbered, h->stream);
-    h->edges_numbered = false;
+    tg_launch_reverse(h->g, h->sm, tg_hash_seed(h->p.seed, TG_TAG_REV(h->round)), h->stream);
     tg_launch_dump_blocks(h->g, h->sm, blk, sizes, h->stream);
     return launch_status("sample");
 }
@@ -506,7 +499,7 @@ static int run_all(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
     if (rc != TG_OK) return rc;
     for (int r = 0; r < p.it1; ++r) {
         int64_t upd = 0;
-        rc = phase1_round(h, p.delta > 0.0f ? &upd : nullptr, r + 1 < p.it1);
+        rc = phase1_round(h, p.delta > 0.0f ? &upd : nullptr);
         if (rc != TG_OK) return rc;
         if (p.delta > 0.0f && (double)upd < stop) break;
     }

@@ -14,6 +14,9 @@
 // of lanes) of its own are therefore launched once per chunk of TG_LAUNCH_NODES nodes and told
 // where their chunk begins; the chunk size is a multiple of every such group size.
 #define TG_LAUNCH_NODES (1ll << 24)
+#define TG_REV_BUCKETS 8192      // buckets of reverse edges one launch counts in LDS
+#define TG_REV_MAX_SHIFT 11      // a bucket holds at most 2048 targets
+#define TG_REV_MAX_W (1 << TG_REV_MAX_SHIFT)
 template <class F>
 static inline void tg_for_node_chunks(int64_t n, F launch)
 {
@@ -30,7 +33,7 @@ struct TgGraph {
     float* nrm;       // n: squared norms
     float* rnorm;     // n: 1/|x| (cosine only, else unused)
     uint32_t* gid;    // n x k list words of the current round: id | fresh << 31
-    uint32_t* gid_next; // n x k, written by a phase-2 round; in phase 1 it holds the arrival number of every sampled edge
+    uint32_t* gid_next; // n x k, written by a phase-2 round
     float* gdist;     // n x k
     unsigned long long* kth;   // n: what the join needs of a node besides its vector: ordered distance of its list's last entry
                                // (high word), bits of its squared norm, or inverse norm for cosine (low word)
@@ -46,15 +49,18 @@ struct TgGraph {
 
 struct TgSample {
     int32_t S, R;
-    uint32_t* deg;            // n: arrivals per node, zero once the prefix sum has used it
-    unsigned long long* off;  // n + 1
-    uint32_t* csr;            // n x k: source | class << 31
+    int32_t bshift;           // reverse edges are brought together in buckets of 2^bshift consecutive targets
+    int64_t nbuckets;         // ceil(n / 2^bshift)
+    uint32_t* bcnt;           // nbuckets: edges per bucket while a round's reverse samples are built, zero otherwise
+    unsigned long long* boff; // nbuckets + 1: where each bucket's edges begin
+    unsigned long long* ebuf; // n x k: the sampled edges by bucket, target % 2^bshift << 32 | class << 31 | source
+    uint32_t* csr;            // n x k: the same by target, class << 31 | source
     int32_t BC;               // row stride of blk: min(k, 2S) + 2R rounded up to 16
     uint32_t* blk;            // n x BC: this round's block of every anchor, NEW ids then OLD ids
     uint32_t* bsz;            // n: |NEW| | (|NEW|+|OLD|) << 8
     unsigned long long* wl;   // 3 x (n + TG_MAX_PARTS): this round's join work lists (anchor | sizes), by part of the round and block size
     uint32_t* wl_cnt;         // TG_WL_LISTS: their lengths
-    unsigned long long* scan_tmp; // block sums of the prefix sum
+    unsigned long long* scan_tmp; // block sums of the prefix sum over the buckets
     int32_t parts, parts_shift;   // a round's anchors are joined in `parts` = 1 << parts_shift parts: v goes to part v % parts, slot v / parts
     uint32_t* adj;                // ceil(n / parts) x BC x adj_words: of the part in hand, per anchor slot and member, bit x = the
     int32_t adj_words;            // node at block position x is in that member's list already (2 words for blocks of at most 64, else 4)
@@ -67,13 +73,14 @@ struct TgCand {
 
 // range: two words for the smallest and largest value of X, or NULL; undefined: one word that counts the rows without a defined distance, or NULL
 void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hipStream_t s);
-void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges /* or null */, hipStream_t s);
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s);
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s);
 void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag /* cleared when a value is no fp16 number, or null */,
                       hipStream_t s);
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
-void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool edges_numbered, hipStream_t s);
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s);
+int tg_rev_bucket_shift(int64_t n);
 // work lists of the coming round from the stored blocks: anchor v goes to part v mod parts
 void tg_launch_bin(const TgGraph& g, const TgSample& sm, int parts, hipStream_t s);
 // which members of a block sit in which member's list, for the anchors of one part: sm.adj (run by tg_launch_join);
@@ -87,10 +94,9 @@ void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int p
 void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, int32_t* sizes, hipStream_t s);
 void tg_launch_join_distances(const TgGraph& g, const int32_t* blk, const int32_t* sizes, int64_t nb,
                               float* out, hipStream_t s);
-// flip: the entries sampled as new for this round become old (first update of a round);
-// number_edges: the sampled edges of the written lists take their arrival numbers (last update before the next sampling)
+// flip: the entries sampled as new for this round become old (first update of a round)
 void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, unsigned long long* updates,
-                      bool flip, bool number_edges, hipStream_t s);
+                      bool flip, hipStream_t s);
 void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
 void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates, unsigned long long* stat_bins,
                       uint32_t* screen_on /* device flag, used when g.Xq is set */, hipStream_t s);

@@ -502,25 +502,11 @@ __device__ inline bool id_in_list(u32 id, u64 list_key, int k)
     return hit;
 }
 
-// The wave has just written list v (entry `id`, mark `fresh` in lanes < k).  The next round
-// samples its first S new and first S old entries; each of those edges v -> id takes its
-// arrival number at id here (deg counts arrivals, epos keeps the number per list entry), so
-// that the reverse lists of the next round can be laid out without a counting pass.
-__device__ inline void number_sampled_edges(int64_t v, int k, int S, u32 id, bool fresh, u32* deg, u32* epos)
-{
-    const int lane = tg_lane();
-    const bool live = lane < k;
-    const u64 lt = tg_lanemask_lt();
-    const u64 mf = __ballot(live && fresh), mo = __ballot(live && !fresh);
-    const bool take = live && __popcll((fresh ? mf : mo) & lt) < S;
-    if (take) epos[v * k + lane] = atomicAdd(deg + id, 1u);
-}
-
 // ---------------------------------------------------------------------------------------
 // Algorithm 1, initialisation.  Node v draws ids floor(n * u_t), t = 0,1,2,..., from the tagged
 // hash and keeps the first k that differ from v and from all earlier draws.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int S, u32* deg, int64_t v0)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 hs_init, int64_t v0)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -561,14 +547,13 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void init_kernel(TgGraph g, u64 h
         g.gdist[v * g.k + lane] = tg_key_dist(key);
         if (lane == g.k - 1) g.kth[v] = join_word(aux_v, key);
     }
-    if (deg) number_sampled_edges(v, g.k, S, tg_key_id(key), true, deg, g.gid_next);
 }
-void tg_launch_init(const TgGraph& g, uint64_t hs_init, const TgSample* number_edges, hipStream_t s)
+void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s)
 {
     size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
     tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
         hipLaunchKernelGGL(init_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), shm, s, g,
-                           hs_init, number_edges ? number_edges->S : 0, number_edges ? number_edges->deg : (u32*)nullptr, v0);
+                           hs_init, v0);
     });
 }
 
@@ -607,7 +592,7 @@ __device__ inline bool lds_set_insert(u32* tab, u32 mask, int shift, u32 id, boo
 // REMEASURE (the join ranked on rows rounded to fp16): every arrival is measured again in fp32 from the
 // vectors before the list is written, so the lists and their thresholds hold exact distances.
 template <bool REMEASURE>
-__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, u32* deg, int flip, int64_t v0)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int S, TgCand cd, u64* updates, int flip, int64_t v0)
 {
     extern __shared__ float smem[];      // REMEASURE: a row of X and 128 words of scratch per wave
     __shared__ u64 queue[LISTS_WAVES][UPDATE_MAX_C];
@@ -626,7 +611,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         cks[j] = (64 * j + lane < cd.C) ? slot0[64 * j] : TG_EMPTY_KEY;
     u32 w = 0;
     float dist = 0.0f;
-    if (!flip && !deg) {
+    if (!flip) {
         // nothing but candidates can change this list now: without any, the slot row was all there is to read
         bool some = false;
 #pragma unroll
@@ -692,7 +677,6 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
             }
         }
     }
-    if (deg) number_sampled_edges(v, k, S, tg_key_id(L), ((u32)L & 1u) != 0, deg, g.gid_next);
     if (!any_cand && (mf == 0 || !flip)) return;      // the list is what it was
     const int ins = __popcll(__ballot(lane < k && (L & 2ull)));
     if (lane < k) {
@@ -702,7 +686,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
     }
     if (ins && lane == 0) atomicAdd(updates + (v & (TG_STAT_BINS - 1)), (u64)ins);
 }
-void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool flip, bool number_edges, hipStream_t s)
+void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64* updates, bool flip, hipStream_t s)
 {
     if (c.C > UPDATE_MAX_C) return;    // the boundary refuses such C; the queue in LDS holds no more
     // rows rounded for the join whatever their values (not the mode that narrows only where that is exact): measure arrivals again
@@ -711,11 +695,9 @@ void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, u64
     tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
         const dim3 grid((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES));
         if (remeasure)
-            hipLaunchKernelGGL(update_kernel<true>, grid, dim3(64 * LISTS_WAVES), shm, s, g, sm.S, c, updates,
-                               number_edges ? sm.deg : (u32*)nullptr, flip ? 1 : 0, v0);
+            hipLaunchKernelGGL(update_kernel<true>, grid, dim3(64 * LISTS_WAVES), shm, s, g, sm.S, c, updates, flip ? 1 : 0, v0);
         else
-            hipLaunchKernelGGL(update_kernel<false>, grid, dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates,
-                               number_edges ? sm.deg : (u32*)nullptr, flip ? 1 : 0, v0);
+            hipLaunchKernelGGL(update_kernel<false>, grid, dim3(64 * LISTS_WAVES), 0, s, g, sm.S, c, updates, flip ? 1 : 0, v0);
     });
 }
 

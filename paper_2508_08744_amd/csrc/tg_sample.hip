@@ -1,56 +1,78 @@
 // Phase-1 sampling (step (1) of section 3.1.1): forward samples are read straight from
 // the lists (first S new and first S old entries in list order); this file builds the
-// bounded reverse samples.  Every sampled edge v -> u is numbered at u (one atomic add, done
-// by the kernel that wrote the list where possible), a prefix sum turns the counts into
-// segments, the edges are stored at their numbers inside the segments, and the wave
-// that owns node u keeps, per class, the R arrivals with the smallest
+// bounded reverse samples.  The sampled edges v -> u are brought together by target in two
+// steps that write runs, not single words: the targets are cut into buckets of 2^bshift
+// consecutive nodes; a workgroup walks a chunk of lists, counts its edges per bucket in LDS,
+// takes one run per bucket with one atomic and stores its edges there (bucket step); then one
+// workgroup per bucket counts the bucket's edges per target in LDS, stores them grouped by target
+// and, a wave per target, keeps per class the R arrivals with the smallest
 // (hash(round, source, u), source): a uniform subset that does not depend on arrival order.
 // The same wave then assembles the anchor's block and stores it for the join.
 #include "tg_device.h"
 #include "tg_kernels.h"
 
-// ---- walk over the sampled edges: each group of KP lanes (KP = power of two >= k) owns one list
+// ---- walk of a workgroup over the sampled edges of the lists [vbeg, vend): each group of KP lanes
+// (KP = power of two >= k) owns one list at a time
 template <class F>
-__device__ inline void for_each_sampled_edge(const TgGraph& g, int S, int kp, int64_t v0, F f)
+__device__ inline void for_chunk_edges(const TgGraph& g, int S, int kp, int64_t vbeg, int64_t vend, F f)
 {
-    const int lane = tg_lane();
+    const int lane = tg_lane(), wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int per_wave = 64 / kp;
-    const int64_t wave_id = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int sub = lane & (kp - 1), grp = lane / kp;
-    const int64_t v = v0 + wave_id * per_wave + grp;
-    const bool live = v < g.n && sub < g.k;
-    u32 w = live ? g.gid[v * g.k + sub] : 0u;
-    const bool fresh = live && (w >> 31);
-    const bool old = live && !(w >> 31);
     const u64 gmask = (kp == 64 ? ~0ull : ((1ull << kp) - 1ull)) << (grp * kp);
     const u64 below = tg_lanemask_lt() & gmask;
-    const u64 mf = __ballot(fresh), mo = __ballot(old);
-    const bool take_new = fresh && __popcll(mf & below) < S;
-    const bool take_old = old && __popcll(mo & below) < S;
-    if (take_new || take_old) f((u32)v, w & TG_ID_MASK, take_old ? 1u : 0u);
+    for (int64_t base = vbeg + (int64_t)wave * per_wave; base < vend; base += (int64_t)nwaves * per_wave) {
+        const int64_t v = base + grp;
+        const bool live = v < vend && sub < g.k;
+        const u32 w = live ? g.gid[v * g.k + sub] : 0u;
+        const bool fresh = live && (w >> 31);
+        const bool old = live && !(w >> 31);
+        const u64 mf = __ballot(fresh), mo = __ballot(old);
+        const bool take_new = fresh && __popcll(mf & below) < S;
+        const bool take_old = old && __popcll(mo & below) < S;
+        if (take_new || take_old) f((u32)v, w & TG_ID_MASK, take_old ? 1u : 0u);
+    }
 }
 
-// Arrival numbers: every sampled edge v -> u takes the next number at u (deg[u] counts the
-// arrivals) and remembers it in epos, so that the scatter below needs no second atomic.  The
-// kernels that write the lists (initial lists, list update) number the edges of the lists they
-// have just written in the same way; this kernel serves the cases where that has not happened.
-__global__ __launch_bounds__(256) void rev_count_kernel(TgGraph g, int S, int kp, u32* deg, u32* epos, int64_t v0)
+// Bucket step.  Both kernels count the chunk's edges per bucket in LDS (buckets b0 .. b0 + nb of this launch;
+// edges to other buckets belong to another launch).  The first adds the counts to bcnt; once a prefix sum has
+// turned bcnt into the buckets' places (boff), the second takes its runs off bcnt again (which so ends at zero,
+// ready for the next round) and stores every edge as target % 2^bshift << 32 | class << 31 | source.
+#define REV_BUCKET_THREADS 1024      // many waves on one table of counters: the walk is a chain of dependent accesses
+template <bool FILL>
+__global__ __launch_bounds__(REV_BUCKET_THREADS) void rev_bucket_kernel(TgGraph g, int S, int kp, int bshift, int64_t b0, int nb, int64_t chunk,
+                                                         u32* bcnt, const u64* __restrict__ boff, u64* __restrict__ ebuf)
 {
-    const int sub = tg_lane() & (kp - 1);
-    for_each_sampled_edge(g, S, kp, v0, [&](u32 v, u32 u, u32) { epos[(int64_t)v * g.k + sub] = atomicAdd(deg + u, 1u); });
-}
-
-// edge v -> u with arrival number a goes to csr[off[u] + a]
-__global__ __launch_bounds__(256) void rev_fill_kernel(TgGraph g, int S, int kp, const u32* __restrict__ epos,
-                                                       const u64* __restrict__ off, u32* __restrict__ csr, int64_t v0)
-{
-    const int sub = tg_lane() & (kp - 1);
-    for_each_sampled_edge(g, S, kp, v0, [&](u32 v, u32 u, u32 cls) {
-        csr[off[u] + epos[(int64_t)v * g.k + sub]] = v | (cls << 31);
+    __shared__ u32 hist[TG_REV_BUCKETS];
+    for (int i = threadIdx.x; i < nb; i += REV_BUCKET_THREADS) hist[i] = 0u;
+    __syncthreads();
+    const int64_t vbeg = (int64_t)blockIdx.x * chunk, vend = vbeg + chunk < g.n ? vbeg + chunk : g.n;
+    for_chunk_edges(g, S, kp, vbeg, vend, [&](u32, u32 u, u32) {
+        const int64_t b = (int64_t)(u >> bshift) - b0;
+        if (b >= 0 && b < nb) atomicAdd(&hist[b], 1u);
+    });
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb; i += REV_BUCKET_THREADS) {
+        const u32 c = hist[i];
+        if (!FILL) {
+            if (c) atomicAdd(bcnt + b0 + i, c);
+        } else if (c) {
+            hist[i] = atomicSub(bcnt + b0 + i, c) - c;       // where this workgroup's run begins inside the bucket
+        }
+    }
+    if (!FILL) return;
+    __syncthreads();
+    const u32 tmask = (1u << bshift) - 1u;
+    for_chunk_edges(g, S, kp, vbeg, vend, [&](u32 v, u32 u, u32 cls) {
+        const int64_t b = (int64_t)(u >> bshift) - b0;
+        if (b >= 0 && b < nb) {
+            const u32 pos = atomicAdd(&hist[b], 1u);
+            ebuf[boff[b0 + b] + pos] = ((u64)(u & tmask) << 32) | (u64)(v | (cls << 31));
+        }
     });
 }
 
-// ---- exclusive prefix sum of deg[0..n) into off[0..n], three passes -------------------------
+// ---- exclusive prefix sum of cnt[0..n) into off[0..n], three passes (cnt stays) -------------------------
 #define SCAN_BLOCK 1024   // elements per workgroup (256 threads x 4)
 
 __global__ __launch_bounds__(256) void scan_partial_kernel(const u32* deg, int64_t n, u64* block_sums)
@@ -90,7 +112,7 @@ __global__ __launch_bounds__(256) void scan_sums_kernel(u64* block_sums, int64_t
     }
     if (threadIdx.x == 0) *off_total = carry_s;
 }
-__global__ __launch_bounds__(256) void scan_final_kernel(u32* deg, int64_t n, const u64* block_sums, u64* off)
+__global__ __launch_bounds__(256) void scan_final_kernel(const u32* deg, int64_t n, const u64* block_sums, u64* off)
 {
     __shared__ u64 wsum[4];
     int64_t base = (int64_t)blockIdx.x * SCAN_BLOCK + threadIdx.x * 4;
@@ -108,10 +130,7 @@ __global__ __launch_bounds__(256) void scan_final_kernel(u32* deg, int64_t n, co
     for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pre += wsum[w];
     u64 run = pre + incl - s;
     for (int i = 0; i < 4; ++i) {
-        if (base + i < n) {
-            off[base + i] = run;
-            deg[base + i] = 0u;     // counted anew for the next round
-        }
+        if (base + i < n) off[base + i] = run;
         run += x[i];
     }
 }
@@ -155,13 +174,12 @@ __device__ inline int asm_find(const u32* keys, u32 id, bool active)
     }
     return slot;
 }
-__device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int64_t v, u32 rn, int cn, u32 ro, int co,
-                                      u32* keys, u32* tags)
+__device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int64_t v, u32 w /* list entry of lane < k */, u32 rn, int cn,
+                                      u32 ro, int co, u32* keys, u32* tags)
 {
     const int lane = tg_lane();
     const int k = g.k, S = sm.S;
     const u64 lt = tg_lanemask_lt();
-    const u32 w = lane < k ? g.gid[v * k + lane] : 0u;
     const bool fr = lane < k && (w >> 31);
     const bool ol = lane < k && !(w >> 31);
     const u64 mf = __ballot(fr), mo = __ballot(ol);
@@ -204,51 +222,124 @@ __device__ inline void assemble_block(const TgGraph& g, const TgSample& sm, int6
     if (lane == 0) sm.bsz[v] = (u32)nN | ((u32)nT << 8);
 }
 
-__global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev, int64_t v0)
+// One workgroup per bucket: its edges are counted per target in LDS, stored grouped by target (csr, at the
+// bucket's own place: one workgroup writes and reads it, so it stays in that workgroup's cache), and every
+// target's arrivals are then cut down to its reverse samples by one wave, which also assembles its block.
+__global__ __launch_bounds__(256) void rev_select_kernel(TgGraph g, TgSample sm, u64 hs_rev, int64_t bfirst)
 {
+    __shared__ u32 tpos[TG_REV_MAX_W];
     __shared__ u64 part[4][2][64];
     __shared__ u32 asm_keys[4][ASM_WORDS], asm_tags[4][ASM_WORDS];
     const int lane = tg_lane(), wave = threadIdx.x >> 6;
-    const int64_t u = v0 + (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-    if (u >= g.n) return;
-    const u64 beg = sm.off[u], end = sm.off[u + 1];
-    const u64 lt = tg_lanemask_lt();
-    u64 best_new = TG_EMPTY_KEY, best_old = TG_EMPTY_KEY;   // ascending across the wave
-    int tot_new = 0, tot_old = 0;
-    for (u64 base = beg; base < end; base += 64) {
-        // key = priority | class << 31 | source: one sort orders both classes; the class bit sits
-        // below the priority, so inside a class the order is (priority, source)
-        u64 key = TG_EMPTY_KEY;
-        if (base + lane < end) {
-            const u32 e = sm.csr[base + lane];
-            const u32 v = e & TG_ID_MASK;
-            key = (tg_hash_xy(hs_rev, (u64)v, (u64)u) & 0xFFFFFFFF00000000ull) | (u64)e;
-        }
-        key = tg_wave_sort(key);
-        const bool is_old = key != TG_EMPTY_KEY && (((u32)key) >> 31);
-        const bool is_new = key != TG_EMPTY_KEY && !(((u32)key) >> 31);
-        const u64 mn = __ballot(is_new), mo = __ballot(is_old);
-        const int cn = __popcll(mn), co = __popcll(mo);
-        // split into two ascending runs through LDS
-        if (is_new) part[wave][0][__popcll(mn & lt)] = key;
-        if (is_old) part[wave][1][__popcll(mo & lt)] = key & ~0x80000000ull;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        const u64 kn = lane < cn ? part[wave][0][lane] : TG_EMPTY_KEY;
-        const u64 ko = lane < co ? part[wave][1][lane] : TG_EMPTY_KEY;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        if (base == beg) {
-            best_new = kn;
-            best_old = ko;
-        } else {
-            if (cn) best_new = tg_wave_merge_low(best_new, kn);
-            if (co) best_old = tg_wave_merge_low(best_old, ko);
-        }
-        tot_new += cn;
-        tot_old += co;
+    const int64_t b = bfirst + blockIdx.x;
+    if (b >= sm.nbuckets) return;
+    const int W = 1 << sm.bshift;
+    const u64 beg = sm.boff[b], end = sm.boff[b + 1];
+    const u64* eb = sm.ebuf;
+    for (int i = threadIdx.x; i < W; i += 256) tpos[i] = 0u;
+    __syncthreads();
+    for (u64 e0 = beg + threadIdx.x; e0 < end; e0 += 4 * 256) {       // four loads on their way at a time
+        u64 rec[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rec[j] = e0 + 256 * j < end ? eb[e0 + 256 * j] : ~0ull;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e0 + 256 * j < end) atomicAdd(&tpos[(u32)(rec[j] >> 32) & (u32)(W - 1)], 1u);
     }
-    assemble_block(g, sm, u, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R), asm_keys[wave], asm_tags[wave]);
+    __syncthreads();
+    if (wave == 0) {
+        // exclusive prefix sum over the W targets: a lane takes W / 64 neighbouring ones
+        const int per = W >> 6;
+        u32 sum = 0;
+        for (int i = 0; i < per; ++i) sum += tpos[lane * per + i];
+        u32 incl = sum;
+        for (int o = 1; o < 64; o <<= 1) {
+            const u32 y = (u32)__shfl((int)incl, max(lane - o, 0));
+            if (lane >= o) incl += y;
+        }
+        u32 run = incl - sum;
+        for (int i = 0; i < per; ++i) {
+            const u32 c = tpos[lane * per + i];
+            tpos[lane * per + i] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (u64 e0 = beg + threadIdx.x; e0 < end; e0 += 4 * 256) {
+        u64 rec[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rec[j] = e0 + 256 * j < end ? eb[e0 + 256 * j] : ~0ull;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e0 + 256 * j < end) {
+                const u32 pos = atomicAdd(&tpos[(u32)(rec[j] >> 32) & (u32)(W - 1)], 1u);
+                sm.csr[beg + pos] = (u32)rec[j];
+            }
+    }
+    __syncthreads();          // (the stores above are waited for and seen by the whole workgroup)
+    // now tpos[t] is where the arrivals of target t end, and those of t + 1 begin
+    const u64 lt = tg_lanemask_lt();
+    // a wave's targets one after the other; the first arrivals and the list of the next target travel while this one is worked on
+    const int k = g.k;
+    auto arrivals_of = [&](int t, u64& abeg, u64& aend) {
+        abeg = beg + (t ? tpos[t - 1] : 0u);
+        aend = beg + tpos[t];
+    };
+    auto target_ok = [&](int t) { return t < W && (b << sm.bshift) + t < g.n; };
+    u64 abeg = 0, aend = 0;
+    u32 e_first = 0u, w_list = 0u;
+    if (target_ok(wave)) {
+        arrivals_of(wave, abeg, aend);
+        e_first = abeg + lane < aend ? sm.csr[abeg + lane] : 0u;
+        w_list = lane < k ? g.gid[((b << sm.bshift) + wave) * k + lane] : 0u;
+    }
+    for (int t = wave; target_ok(t); t += 4) {
+        const int64_t u = (b << sm.bshift) + t;
+        u64 nbeg = 0, nend = 0;
+        u32 e_next = 0u, w_next = 0u;
+        if (target_ok(t + 4)) {
+            arrivals_of(t + 4, nbeg, nend);
+            e_next = nbeg + lane < nend ? sm.csr[nbeg + lane] : 0u;
+            w_next = lane < k ? g.gid[(u + 4) * k + lane] : 0u;
+        }
+        u64 best_new = TG_EMPTY_KEY, best_old = TG_EMPTY_KEY;   // ascending across the wave
+        int tot_new = 0, tot_old = 0;
+        for (u64 base = abeg; base < aend; base += 64) {
+            // key = priority | class << 31 | source: one sort orders both classes; the class bit sits
+            // below the priority, so inside a class the order is (priority, source)
+            u64 key = TG_EMPTY_KEY;
+            if (base + lane < aend) {
+                const u32 e = base == abeg ? e_first : sm.csr[base + lane];
+                const u32 v = e & TG_ID_MASK;
+                key = (tg_hash_xy(hs_rev, (u64)v, (u64)u) & 0xFFFFFFFF00000000ull) | (u64)e;
+            }
+            key = tg_wave_sort(key);
+            const bool is_old = key != TG_EMPTY_KEY && (((u32)key) >> 31);
+            const bool is_new = key != TG_EMPTY_KEY && !(((u32)key) >> 31);
+            const u64 mn = __ballot(is_new), mo = __ballot(is_old);
+            const int cn = __popcll(mn), co = __popcll(mo);
+            // split into two ascending runs through LDS
+            if (is_new) part[wave][0][__popcll(mn & lt)] = key;
+            if (is_old) part[wave][1][__popcll(mo & lt)] = key & ~0x80000000ull;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const u64 kn = lane < cn ? part[wave][0][lane] : TG_EMPTY_KEY;
+            const u64 ko = lane < co ? part[wave][1][lane] : TG_EMPTY_KEY;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (base == abeg) {
+                best_new = kn;
+                best_old = ko;
+            } else {
+                if (cn) best_new = tg_wave_merge_low(best_new, kn);
+                if (co) best_old = tg_wave_merge_low(best_old, ko);
+            }
+            tot_new += cn;
+            tot_old += co;
+        }
+        assemble_block(g, sm, u, w_list, (u32)best_new, min(tot_new, sm.R), (u32)best_old, min(tot_old, sm.R), asm_keys[wave], asm_tags[wave]);
+        abeg = nbeg; aend = nend; e_first = e_next; w_list = w_next;
+    }
 }
 
 // blocks as stored -> the boundary's fixed n x 128 layout (padding -1) and (|NEW|, |OLD|)
@@ -274,25 +365,41 @@ void tg_launch_dump_blocks(const TgGraph& g, const TgSample& sm, int32_t* blk, i
     hipLaunchKernelGGL(dump_blocks_kernel, dim3((unsigned)grid), dim3(256), 0, s, g, sm, blk, sizes);
 }
 
-void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, bool counted, hipStream_t s)
+void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s)
 {
     int kp = 1;
     while (kp < g.k) kp <<= 1;
-    const int per_wave = 64 / kp;
-    auto edge_blocks = [&](int64_t cnt) { return dim3((unsigned)(((cnt + per_wave - 1) / per_wave + 3) / 4)); };
-    const int64_t nsb = (g.n + SCAN_BLOCK - 1) / SCAN_BLOCK;
-    if (!counted)
-        tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-            hipLaunchKernelGGL(rev_count_kernel, edge_blocks(cnt), dim3(256), 0, s, g, sm.S, kp, sm.deg, g.gid_next, v0);
-        });
-    hipLaunchKernelGGL(scan_partial_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp);
-    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sm.scan_tmp, nsb, sm.off + g.n);
-    hipLaunchKernelGGL(scan_final_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.deg, g.n, sm.scan_tmp, sm.off);
-    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-        hipLaunchKernelGGL(rev_fill_kernel, edge_blocks(cnt), dim3(256), 0, s, g, sm.S, kp, (const u32*)g.gid_next, (const u64*)sm.off,
-                           sm.csr, v0);
-    });
-    tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
-        hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)((cnt + 3) / 4)), dim3(256), 0, s, g, sm, hs_rev, v0);
-    });
+    const int per_step = (REV_BUCKET_THREADS / 64) * (64 / kp);   // lists a workgroup reads at a time
+    // about 2^14 edges per workgroup (measured: many short walks beat long runs per bucket)
+    int64_t chunk = (1 << 14) / g.k;
+    chunk = (chunk + per_step - 1) / per_step * per_step;
+    const unsigned grid = (unsigned)((g.n + chunk - 1) / chunk);
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int64_t b0 = 0; b0 < sm.nbuckets; b0 += TG_REV_BUCKETS) {
+            const int nb = (int)(sm.nbuckets - b0 < TG_REV_BUCKETS ? sm.nbuckets - b0 : TG_REV_BUCKETS);
+            if (pass == 0)
+                hipLaunchKernelGGL(rev_bucket_kernel<false>, dim3(grid), dim3(REV_BUCKET_THREADS), 0, s, g, sm.S, kp, sm.bshift, b0, nb, chunk, sm.bcnt,
+                                   (const u64*)sm.boff, sm.ebuf);
+            else
+                hipLaunchKernelGGL(rev_bucket_kernel<true>, dim3(grid), dim3(REV_BUCKET_THREADS), 0, s, g, sm.S, kp, sm.bshift, b0, nb, chunk, sm.bcnt,
+                                   (const u64*)sm.boff, sm.ebuf);
+        }
+        if (pass == 0) {
+            const int64_t nsb = (sm.nbuckets + SCAN_BLOCK - 1) / SCAN_BLOCK;
+            hipLaunchKernelGGL(scan_partial_kernel, dim3((unsigned)nsb), dim3(256), 0, s, sm.bcnt, sm.nbuckets, sm.scan_tmp);
+            hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sm.scan_tmp, nsb, sm.boff + sm.nbuckets);
+            hipLaunchKernelGGL(scan_final_kernel, dim3((unsigned)nsb), dim3(256), 0, s, (const u32*)sm.bcnt, sm.nbuckets, sm.scan_tmp, sm.boff);
+        }
+    }
+    for (int64_t bf = 0; bf < sm.nbuckets; bf += (1 << 20))
+        hipLaunchKernelGGL(rev_select_kernel, dim3((unsigned)(sm.nbuckets - bf < (1 << 20) ? sm.nbuckets - bf : (1 << 20))), dim3(256), 0, s, g, sm,
+                           hs_rev, bf);
+}
+// buckets of 2^shift targets: 128 (measured: the smaller the faster, down to there), more where the bucket step would otherwise
+// need more than four launches, each of which reads every list
+int tg_rev_bucket_shift(int64_t n)
+{
+    int sh = 7;
+    while (sh < TG_REV_MAX_SHIFT && ((n + (1ll << sh) - 1) >> sh) > 4 * TG_REV_BUCKETS) ++sh;
+    return sh;
 }

@@ -596,11 +596,11 @@ def test_f16_join_statistical_parity_on_real_valued_data(cfg, metric):
     truth, _ = oracle.brute_force_knn(X, k, mcode)
     gaps = []
     for seed in (1, 2, 3):
-        prm = knn.default_params(k, 6, metric=metric, seed=seed, C=32, join_f16=1)
+        prm = knn.default_params(k, 6, metric=metric, seed=seed, C=32, join_f16=1, it1=3, it2=3)
         ids, dist, _ = knn.knn_build_ex(torch.from_numpy(X).cuda(), prm)
         ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
         _check_properties(X, ids, dist, mcode)
-        o = _oracle_for(X, knn.default_params(k, 6, metric=metric, seed=seed, C=32), mcode)
+        o = _oracle_for(X, knn.default_params(k, 6, metric=metric, seed=seed, C=32, it1=3, it2=3), mcode)
         o.run(prm.it1, prm.it2)
         gaps.append(oracle.recall(ids, truth) - oracle.recall(o.graph()[0], truth))
     assert np.mean(gaps) >= -RECALL_TOL, gaps
