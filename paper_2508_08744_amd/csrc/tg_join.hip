@@ -746,7 +746,8 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
             // unsigned order = float order); a pair that must not count gets +inf added, so
             // no validity masks have to be carried around.
             float aux_a[4], pen_a[4];
-            u32 id_a[4], okd_max = 0u, adj_a[4] = {0u, 0u, 0u, 0u};
+            u32 ida_key[4], okd_a[4], adj_a[4] = {0u, 0u, 0u, 0u};
+            const int rowc = (16 * i + 4 * q4) * JOIN_CELLS + (r16 >> 3);      // cell (first of the lane's rows, column group 0) of this lane's half of a tile
             if (i < MT) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -755,13 +756,11 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                     pen_a[e] = a < nN ? 0.f : INF;
                     // L2: the penalty rides on the norm (norm + 0 is the norm, bit for bit)
                     aux_a[e] = METRIC == 0 ? s_aux[aa] + pen_a[e] : s_aux[aa];
-                    id_a[e] = (u32)s_ids[aa];
-                    if (MODE == 0) okd_max = max(okd_max, s_okd[aa]);
+                    ida_key[e] = ((u32)s_ids[aa] << 2) | 3u;
+                    okd_a[e] = (MODE == 0 && a < nN) ? s_okd[aa] : 0u;
                 }
             }
-            // the lane that will speak for row 16 i + 4 q4 + (r16 & 3) keeps that row's threshold
-            const int a_mine = 16 * i + 4 * q4 + (r16 & 3);
-            const u32 okd_mine = (MODE == 0 && i < MT) ? s_okd[a_mine < nN ? a_mine : 0] : 0u;
+            const int colc = r16 * JOIN_CELLS + (q4 >> 1);     // cell (column r16 of column group 0, row group 0)
             {
 #pragma unroll
                 for (int j = i; j < GMAX; ++j) {
@@ -807,44 +806,32 @@ __global__ __launch_bounds__(256) void join_wave_kernel(TgGraph g, TgSample sm, 
                         o[e] = METRIC == 0 ? (__float_as_uint(dist) | 0x80000000u) : tg_ord(dist);
                     }
                     if (MODE == 0) {
-                        const u32 okd_b = s_okd[bb];
+                        const u32 okd_b = b < nT ? s_okd[bb] : 0u;
                         const u32 adj_b = sh.adj[buf][bb][i >> 1];        // bit 16 (i & 1) + 4 q4 + e: row a sits in b's list
+                        const u32 idb_key = (id_b << 2) | 3u;
                         // b is a candidate of a unless a's list holds it, and a of b likewise: such a pair gets every bit set
-                        // (the ordered +inf of a masked pair is 0xFF800000: neither passes any threshold of a finite list)
+                        // (the ordered +inf of a masked pair is 0xFF800000: neither passes any threshold of a finite list).
+                        // Every pair that may precede its target's last entry goes straight to the target's cell for this
+                        // group of eight positions, which keeps the minimum (ds_min_u64): the closest of the group arrives
+                        // there whatever else does, and nothing else is asked of the cell.  (At the threshold's own distance a
+                        // candidate passes whatever its id: the list update sorts that out.)
                         u32 orow[4], ocol[4];
+                        bool prow[4], pcol[4], any = false;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             orow[e] = o[e] | (u32)__builtin_amdgcn_sbfe((int)adj_a[e], 16 * (j & 1) + r16, 1);
                             ocol[e] = o[e] | (u32)__builtin_amdgcn_sbfe((int)adj_b, 16 * (i & 1) + 4 * q4 + e, 1);
+                            prow[e] = orow[e] <= okd_a[e];
+                            pcol[e] = ocol[e] <= okd_b;
+                            any |= prow[e] | pcol[e];
                         }
                         // nothing in this tile can precede any threshold: the common case in late rounds
-                        const u32 rmin = min(min(orow[0], orow[1]), min(orow[2], orow[3]));
-                        const u32 cmin = min(min(ocol[0], ocol[1]), min(ocol[2], ocol[3]));
-                        if (__ballot(rmin <= okd_max || cmin <= okd_b) == 0) continue;
-                        // Row nodes: closest column node of each half of the tile (a group of eight positions)
-                        // for each of the lane's four rows, reduced over the eight lanes of the half; then one
-                        // threshold test by the lane that speaks for the row (if the closest fails, every other pair fails).
-                        u32 ro[4], ri[4];
+                        if (__ballot(any) == 0) continue;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            ro[e] = orow[e];
-                            ri[e] = id_b;
-                            groupmin8(ro[e], ri[e]);
+                            if (prow[e]) atomicMin(cells + rowc + (e * JOIN_CELLS + 2 * j), ((u64)orow[e] << 32) | (u64)idb_key);
+                            if (pcol[e]) atomicMin(cells + colc + (16 * j * JOIN_CELLS + 2 * i), ((u64)ocol[e] << 32) | (u64)ida_key[e]);
                         }
-                        const int e_mine = r16 & 3;
-                        const u32 mo = e_mine == 0 ? ro[0] : e_mine == 1 ? ro[1] : e_mine == 2 ? ro[2] : ro[3];
-                        const u32 mi = e_mine == 0 ? ri[0] : e_mine == 1 ? ri[1] : e_mine == 2 ? ri[2] : ri[3];
-                        // (at the threshold's own distance a candidate passes whatever its id: the list update sorts that out)
-                        if ((r16 & 7) < 4 && mo <= okd_mine)
-                            atomicMin(cells + a_mine * JOIN_CELLS + 2 * j + (r16 >> 3), ((u64)mo << 32) | (u64)((mi << 2) | 3u));
-                        // Column node b: closest row node of the tile over the lane's four rows.
-                        u64 cb = ((u64)ocol[0] << 32) | id_a[0];
-#pragma unroll
-                        for (int e = 1; e < 4; ++e) cb = tg_min64(cb, ((u64)ocol[e] << 32) | id_a[e]);
-                        // (the two row quarters of a group of eight meet in the cell: it takes the minimum)
-                        const u32 co = (u32)(cb >> 32), ci = (u32)cb;
-                        if (co <= okd_b)
-                            atomicMin(cells + b * JOIN_CELLS + 2 * i + (q4 >> 1), ((u64)co << 32) | (u64)((ci << 2) | 3u));
                     }
                 }
             }
