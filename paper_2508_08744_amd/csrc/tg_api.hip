@@ -503,8 +503,10 @@ static int run_all(tg_knn_handle* h, int32_t* out_ids, float* out_dist)
         if (rc != TG_OK) return rc;
         if (p.delta > 0.0f && (double)upd < stop) break;
     }
-    rc = tg_knn_begin_phase2(h);
-    if (rc != TG_OK) return rc;
+    if (p.it2 > 0) {
+        rc = tg_knn_begin_phase2(h);
+        if (rc != TG_OK) return rc;
+    }
     for (int r = 0; r < p.it2; ++r) {
         int64_t upd = 0;
         rc = tg_knn_phase2_round(h, p.delta > 0.0f ? &upd : nullptr);
