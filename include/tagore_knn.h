@@ -83,7 +83,9 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            means for the graph); elsewhere the join ranks its candidates on rounded vectors (11 significant
  *            bits), and the list update measures every candidate that enters a list again in fp32
  *            from the vectors, so lists and thresholds hold exact distances.  Values
- *            beyond +-65504 have no fp16 number: such data must not use 1.
+ *            beyond +-65504 have no fp16 number: such data must not use 1; the rows that hold such a
+ *            value are counted in tg_knn_stats.undefined_rows (their lists stay well-formed and hold
+ *            exact distances, but which candidates reach them is unspecified).
  *            2: as 1, but only if every value of X turned out to be an fp16 number when the copy
  *            was made (a flag on the device; both variants of the join are launched and the one
  *            whose turn it is not ends at once).  No operand is rounded then, so the join's
@@ -124,7 +126,7 @@ typedef struct tg_knn_handle tg_knn_handle;
 
 /* Defaults for a given k and total round budget.  From 8 rounds on it1 = ceil(iters/2), it2 = iters - it1
  * (section 7.3: it1 = it2); a smaller budget goes to the first phase first (it1 = min(iters, 4)), which is
- * the one that converges while the lists are poor (section 3.1.2).  S = min(k,32), R = 32, C = 64,
+ * the one that converges while the lists are poor (section 4.1).  S = min(k,32), R = 32, C = 64,
  * parts = 2, m = 2, delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with
  * delta = 0.001. */
 int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);

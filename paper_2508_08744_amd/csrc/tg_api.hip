@@ -59,7 +59,7 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->metric = TG_METRIC_L2;
     p->delta = 0.0f;
     if (iters <= 0) { iters = 16; p->delta = 0.001f; }
-    // the first phase converges fastest while the lists are poor (section 3.1.2): it gets the first four rounds and,
+    // the first phase converges fastest while the lists are poor (section 4.1): it gets the first four rounds and,
     // beyond eight, every other one
     p->it1 = iters < 4 ? iters : (iters + 1) / 2 > 4 ? (iters + 1) / 2 : 4;
     p->it2 = iters - p->it1;
@@ -269,7 +269,8 @@ static void ensure_norms(tg_knn_handle* h)
     int sp = begin_span(h, SPAN_NORMS, 0);
     tg_launch_norms(h->g, reinterpret_cast<uint32_t*>(h->xqm), h->d_undefined, h->stream);
     if (h->d_f16_ok) tg_launch_fill_u32(h->d_f16_ok, 1, 1u, h->stream);
-    if (h->xh) tg_launch_narrow(h->g, h->xh, h->d_f16_ok, h->stream);
+    // rounding every row whatever its values (join_f16 = 1): a row with a value beyond +-65504 has no fp16 copy to rank on, and is counted
+    if (h->xh) tg_launch_narrow(h->g, h->xh, h->d_f16_ok, h->d_f16_ok ? nullptr : h->d_undefined, h->stream);
     end_span(h, sp);
     h->norms_done = true;
 }

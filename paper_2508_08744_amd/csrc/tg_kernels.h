@@ -76,7 +76,7 @@ void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hip
 void tg_launch_init(const TgGraph& g, uint64_t hs_init, hipStream_t s);
 void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s);
 void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag /* cleared when a value is no fp16 number, or null */,
-                      hipStream_t s);
+                      uint32_t* overflow_rows /* counts the rows with a finite value beyond fp16's range, or null */, hipStream_t s);
 void tg_launch_fill_u64(unsigned long long* p, size_t count, unsigned long long v, hipStream_t s);
 void tg_launch_fill_u32(uint32_t* p, size_t count, uint32_t v, hipStream_t s);
 void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hipStream_t s);

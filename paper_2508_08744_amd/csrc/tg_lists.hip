@@ -202,7 +202,7 @@ void tg_launch_quantize(const TgGraph& g, uint8_t* Xq, float* Xqm, hipStream_t s
 // fp16 copy of the rows for the local join: round to nearest even, eight values per thread,
 // zero beyond column d.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __restrict__ Xh, u32* exact_flag)
+__global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __restrict__ Xh, u32* exact_flag, u32* overflow_rows)
 {
     bool inexact = false;
     const int per_row = g.ldh >> 3;
@@ -213,12 +213,20 @@ __global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __rest
         const int c0 = (int)(i - row * per_row) * 8;
         const float* x = g.X + row * (size_t)g.ld;
         u32 h[8];
+        bool over = false;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float val = c0 + e < g.d ? x[c0 + e] : 0.f;
             const __half hv = __float2half_rn(val);
             inexact |= __half2float(hv) != val;
+            over |= fabsf(val) <= 3.4028234e38f && fabsf(__half2float(hv)) > 65504.f;      // a finite value that fp16 cannot hold
             h[e] = (u32)__half_as_ushort(hv);
+        }
+        if (over && overflow_rows) {
+            // such a row is counted once: by the piece that holds its first such value (rare: the columns before are read again)
+            bool first = true;
+            for (int c = 0; c < c0 && first; ++c) first = !(fabsf(x[c]) > 65504.f && fabsf(x[c]) <= 3.4028234e38f);
+            if (first) atomicAdd(overflow_rows, 1u);
         }
         *reinterpret_cast<uint4*>(Xh + row * (size_t)g.ldh + c0) =
             make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
@@ -226,9 +234,9 @@ __global__ __launch_bounds__(256) void narrow_kernel(TgGraph g, uint16_t* __rest
     // one store per wave that met such a value, and none once the flag is down
     if (exact_flag && __ballot(inexact) != 0ull && tg_lane() == 0 && *exact_flag != 0u) *exact_flag = 0u;
 }
-void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag, hipStream_t s)
+void tg_launch_narrow(const TgGraph& g, uint16_t* Xh, uint32_t* exact_flag, uint32_t* overflow_rows, hipStream_t s)
 {
-    hipLaunchKernelGGL(narrow_kernel, dim3(grid_for((size_t)g.n * (g.ldh >> 3), 256)), dim3(256), 0, s, g, Xh, exact_flag);
+    hipLaunchKernelGGL(narrow_kernel, dim3(grid_for((size_t)g.n * (g.ldh >> 3), 256)), dim3(256), 0, s, g, Xh, exact_flag, overflow_rows);
 }
 
 // ---------------------------------------------------------------------------------------

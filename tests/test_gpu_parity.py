@@ -503,6 +503,29 @@ def test_rows_without_a_defined_distance_are_counted_and_leave_valid_lists(metri
     assert (s[:, 1:] != s[:, :-1]).all()
 
 
+def test_f16_join_counts_rows_beyond_the_fp16_range():
+    """join_f16 = 1 rounds every row to fp16 whatever its values: a row with a finite value beyond +-65504 has
+    no fp16 copy to rank on.  Such rows are counted once each (stats: undefined_rows); every list stays
+    well-formed and holds exact distances (arrivals are measured again in fp32).  With join_f16 = 2 the same data
+    take the fp32 join, and nothing is counted."""
+    n, k = 2500, 16
+    X = inputs.make("C1", n=n, d=40)
+    rows = np.array([7, 300, 301, 2499])
+    X[rows, 3] = 7.0e4
+    X[300, 21] = -1.0e5           # twice in one row, in two pieces of the row: still one row
+    X[301, 39] = 9.0e4
+    Xg = torch.from_numpy(X).cuda()
+    prm = knn.default_params(k, 6, seed=3, join_f16=1)
+    ids, dist, st = knn.knn_build_ex(Xg, prm)
+    assert st["undefined_rows"] == len(rows)
+    _check_properties(X, ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64))
+    prm2 = knn.default_params(k, 6, seed=3, join_f16=2)
+    ids2, _, st2 = knn.knn_build_ex(Xg, prm2)
+    ids0, _, st0 = knn.knn_build_ex(Xg, knn.default_params(k, 6, seed=3))
+    assert st2["undefined_rows"] == 0 and st0["undefined_rows"] == 0
+    assert (ids2 == ids0).all()
+
+
 def test_set_graph_round_trip_and_stream():
     X = inputs.make("C2", n=800, d=20, comps=2)
     prm = knn.default_params(12, 4, seed=6)
