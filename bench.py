@@ -93,7 +93,7 @@ def main():
     n = args.n or cfg["n"]
     d, k, metric = cfg["d"], cfg["k"], cfg["metric"]
     dev = torch.device("cuda:0")
-    big = n > 20_000_000          # the 1e8-point configuration: drawn on the device, rounds in eight parts so that it fits
+    big = n > 20_000_000          # the 1e8-point configuration: drawn on the device, rounds in eight parts and 64 slots per node so that it fits
     if big:
         X = None
         Xg = inputs.make_on_device(args.config, dev, n=n)
@@ -102,7 +102,7 @@ def main():
         Xg = torch.from_numpy(X).to(dev)
     prm = bench_params(k)
     if big:
-        prm.parts = 8
+        prm.parts, prm.C = 8, 64
     if args.it1 is not None:
         prm.it1 = args.it1
     if args.it2 is not None:

@@ -126,7 +126,7 @@ typedef struct tg_knn_handle tg_knn_handle;
 
 /* Defaults for a given k and total round budget.  From 8 rounds on it1 = ceil(iters/2), it2 = iters - it1
  * (section 7.3: it1 = it2); a smaller budget goes to the first phase first (it1 = min(iters, 4)), which is
- * the one that converges while the lists are poor (section 4.1).  S = min(k,32), R = 32, C = 64,
+ * the one that converges while the lists are poor (section 4.1).  S = min(k,32), R = 32, C = 256,
  * parts = 2, m = 2, delta = 0, finalize = 1, screen = 1, seed = 1.  iters <= 0 selects 16 rounds with
  * delta = 0.001. */
 int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p /* host, out */);

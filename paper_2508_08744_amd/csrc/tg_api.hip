@@ -65,7 +65,7 @@ extern "C" int tg_knn_default_params(int32_t k, int32_t iters, tg_knn_params* p)
     p->it2 = iters - p->it1;
     p->S = k < 32 ? (k < 1 ? 1 : k) : 32;
     p->R = 32;
-    p->C = 64;
+    p->C = 256;
     p->parts = 2;
     p->m = 2;
     p->finalize = 1;

@@ -104,7 +104,7 @@ def test_workspace_fits_the_largest_configuration():
     # the 1e8 x 96 configuration must fit one MI355X (288 GB) together with its vectors and outputs
     from paper_2508_08744_amd import inputs, knn
     cfg = inputs.CONFIGS["C5"]
-    p = knn.default_params(cfg["k"], 12, parts=8)      # (the adjacency words of one part are n / parts * 2 KB)
+    p = knn.default_params(cfg["k"], 12, parts=8, C=64)      # (the adjacency words of one part are n / parts * 2 KB, the slots n * C * 8 B)
     ws = knn.workspace_bytes(cfg["n"], cfg["d"], p)
     total = ws + cfg["n"] * cfg["d"] * 4 + cfg["n"] * cfg["k"] * 8
     assert total < 288e9, total / 1e9
