@@ -111,3 +111,33 @@ def test_more_nodes_than_one_launch_can_carry():
         assert bool((ref == dist[rows]).all())
     # better than the random start: the mean distance of the lists dropped over the two rounds, everywhere
     assert float(dist[-5000:].mean()) < 0.8 * float(((Xg[-5000:] - Xg[:5000]) ** 2).sum(dim=1).mean())
+
+
+def test_reverse_samples_over_several_launches_of_the_bucket_step():
+    # 1.3 M nodes are 10 157 buckets of 128 targets, more than one launch of the bucket step counts in LDS (8 192):
+    # the step runs twice, each launch taking the edges whose targets it covers.  Tiny rows and lists keep the oracle
+    # fast; blocks around the border between the two launches and at both ends, then a whole round, bit for bit.
+    n, d, k = 1_300_000, 4, 4
+    X = np.random.Generator(np.random.PCG64(11)).integers(0, 64, size=(n, d)).astype(np.float32)
+    prm = knn.default_params(k, 2, seed=3, C=16)
+    prm.R = 4
+    b = knn.Builder(torch.from_numpy(X).cuda(), prm)
+    o = oracle.NNDescent(X, k, **oracle.device_model(prm))
+    b.init()
+    o.init()
+    assert (b.graph()[0].cpu().numpy() == o.graph()[0]).all()
+    blk, sizes = b.sample_blocks()
+    o.phase1_sample()
+    border = 8192 * 128
+    for lo in (0, border - 1500, n - 3000):
+        bl, sz = blk[lo:lo + 3000].cpu().numpy(), sizes[lo:lo + 3000].cpu().numpy()
+        for i in range(3000):
+            N, O = o.block(lo + i)
+            assert sz[i, 0] == len(N) and sz[i, 1] == len(O), lo + i
+            assert (bl[i, :len(N)] == N).all() and (bl[i, len(N):len(N) + len(O)] == O).all(), lo + i
+    del blk, sizes
+    assert b.phase1_round() == o.phase1_round()
+    gi, gd, gf = b.graph()
+    oi, od, of = o.graph()
+    assert (gi.cpu().numpy() == oi).all() and (gd.cpu().numpy().astype(np.float64) == od).all() and (gf.cpu().numpy() == of).all()
+    b.close()
