@@ -128,7 +128,7 @@ def main():
     truth, _ = knn.exact_knn(Xg, k, metric, rows_g)
     recall = oracle.recall(ids[rows_g].cpu().numpy(), truth.cpu().numpy())
 
-    # dominant kernel: the phase-1 local join.  Algorithmic flops = 2 d per needed pair
+    # dominant kernel: the phase-1 local join (the kernels that multiply).  Algorithmic flops = 2 d per needed pair
     # (new-new and new-old pairs of every block); duration from the HIP events the library
     # records on the launch stream around each join launch.
     r1 = stats[0]["rounds_phase1"]
@@ -148,7 +148,7 @@ def main():
     if args.config == "C2" and n == cfg["n"] and os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("join_traffic_bytes_per_launch"):
-                traffic, traffic_source = float(line.split("=")[1]), "profiles/" + os.path.basename(tfile)
+                traffic, traffic_source = float(line.split("=")[1].split()[0]), "profiles/" + os.path.basename(tfile)
     out = {
         "metric": "k-NN graph build points/sec at recall@32>=0.95 (1Mx128 fp32); join MFMA %",
         "value": n / (ms_per_step * 1e-3),
@@ -169,13 +169,13 @@ def main():
         "recall_at_k": recall,
         "recall_ok": bool(recall >= 0.95),
         "join_mfma_pct": 100.0 * achieved / MFMA_FP32_PEAK_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "phase-1 local join of one round (every part's adj_kernel, join_wave_kernel<3>, <4> and join_kernel)",
+        "roofline": {"bound": "mfma", "kernel": "phase-1 local join of one round (join_wave_kernel<3>, <4> and join_kernel of every part; adj_kernel, which runs before them, is timed apart)",
                      "achieved": achieved,
                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_FP32_PEAK_TFLOPS,
                      "avg_launch_ms": avg_launch_ms, "launches": launches, "gather_GBps": gather_gbs,
                      "hbm_gather_frac": gather_gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source},
         "breakdown_ms": {"norms": last["ms_norms"], "init": last["ms_init"], "finalize": last["ms_finalize"],
-                         "sample": sum(last["ms_sample"]), "join": sum(last["ms_join"][:r1]),
+                         "sample": sum(last["ms_sample"]), "adjacency": sum(last["ms_adjacency"]), "join": sum(last["ms_join"][:r1]),
                          "update": sum(last["ms_update"]), "phase2": sum(last["ms_join"][r1:])},
         "updates_per_round": last["updates"],
     }

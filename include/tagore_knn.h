@@ -115,7 +115,8 @@ typedef struct tg_knn_stats {
     int64_t updates[TG_MAX_ROUNDS];      /* list entries replaced in round r (both phases, in order) */
     float ms_norms, ms_init, ms_finalize; /* ms_norms: norms plus the 8-bit screening copy (screen = 1) */
     float ms_sample[TG_MAX_ROUNDS];      /* reverse-sample build of round r (phase 1)               */
-    float ms_join[TG_MAX_ROUNDS];        /* local join (phase 1) or expand+update (phase 2)         */
+    float ms_join[TG_MAX_ROUNDS];        /* local join (phase 1: the multiplying kernels of every part) or expand+update (phase 2) */
+    float ms_adjacency[TG_MAX_ROUNDS];   /* which members of a block already list which (phase 1, every part) */
     float ms_update[TG_MAX_ROUNDS];      /* list update kernel (phase 1)                            */
     double join_pairs[TG_MAX_ROUNDS];    /* pairs the join of round r had to evaluate               */
     double join_vectors[TG_MAX_ROUNDS];  /* vectors the join of round r had to gather               */

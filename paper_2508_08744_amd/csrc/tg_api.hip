@@ -113,7 +113,7 @@ struct tg_knn_handle {
     struct Span { int kind, round, e0, e1; };
     std::vector<Span> spans;
 };
-enum { SPAN_NORMS, SPAN_INIT, SPAN_SAMPLE, SPAN_JOIN, SPAN_UPDATE, SPAN_FINALIZE };
+enum { SPAN_NORMS, SPAN_INIT, SPAN_SAMPLE, SPAN_ADJ, SPAN_JOIN, SPAN_UPDATE, SPAN_FINALIZE };
 
 static int round_up4(int d) { return (d + 3) & ~3; }
 
@@ -313,6 +313,9 @@ static int phase1_round(tg_knn_handle* h, int64_t* updates)
     end_span(h, sp);
     for (int part = 0; part < h->p.parts; ++part) {
         // the anchors v = part mod parts: their blocks are joined, then every list takes in what it was handed
+        sp = begin_span(h, SPAN_ADJ, r);
+        tg_launch_adj(h->g, h->sm, part, h->stream);
+        end_span(h, sp);
         sp = begin_span(h, SPAN_JOIN, r);
         tg_launch_join(h->g, h->sm, h->cd, part, h->p.parts, tg_hash_seed(h->p.seed, TG_TAG_SLOT(r)),
                        h->d_stat_bins + (size_t)r * 2 * TG_STAT_BINS, h->stream);
@@ -417,6 +420,7 @@ extern "C" int tg_knn_get_stats(tg_knn_handle* h, tg_knn_stats* out)
         case SPAN_INIT: out->ms_init += ms; break;
         case SPAN_FINALIZE: out->ms_finalize += ms; break;
         case SPAN_SAMPLE: out->ms_sample[s.round] += ms; break;
+        case SPAN_ADJ: out->ms_adjacency[s.round] += ms; break;
         case SPAN_JOIN: out->ms_join[s.round] += ms; break;
         case SPAN_UPDATE: out->ms_update[s.round] += ms; break;
         }

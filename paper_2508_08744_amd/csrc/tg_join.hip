@@ -1024,7 +1024,6 @@ void tg_launch_join(const TgGraph& g, const TgSample& sm, const TgCand& c, int p
                     unsigned long long* stat_bins, hipStream_t s)
 {
     const bool wv = wave_path(g);
-    tg_launch_adj(g, sm, part, s);
     if (wv) {
         launch_wave_t<3>(g, sm, c, hs_slot, stat_bins, part * 3 + 0, parts, s);
         launch_wave_t<4>(g, sm, c, hs_slot, stat_bins, part * 3 + 1, parts, s);

@@ -83,7 +83,7 @@ void tg_launch_reverse(const TgGraph& g, const TgSample& sm, uint64_t hs_rev, hi
 int tg_rev_bucket_shift(int64_t n);
 // work lists of the coming round from the stored blocks: anchor v goes to part v mod parts
 void tg_launch_bin(const TgGraph& g, const TgSample& sm, int parts, hipStream_t s);
-// which members of a block sit in which member's list, for the anchors of one part: sm.adj (run by tg_launch_join);
+// which members of a block sit in which member's list, for the anchors of one part: sm.adj (to run before tg_launch_join of that part);
 // the same, copied to n x 128 x 4 words for inspection
 void tg_launch_adj(const TgGraph& g, const TgSample& sm, int part, hipStream_t s);
 void tg_launch_dump_adj(const TgGraph& g, const TgSample& sm, int part, uint32_t* out, hipStream_t s);

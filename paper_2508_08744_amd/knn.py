@@ -30,6 +30,7 @@ class Stats(ctypes.Structure):
                 ("updates", ctypes.c_int64 * TG_MAX_ROUNDS),
                 ("ms_norms", ctypes.c_float), ("ms_init", ctypes.c_float), ("ms_finalize", ctypes.c_float),
                 ("ms_sample", ctypes.c_float * TG_MAX_ROUNDS), ("ms_join", ctypes.c_float * TG_MAX_ROUNDS),
+                ("ms_adjacency", ctypes.c_float * TG_MAX_ROUNDS),
                 ("ms_update", ctypes.c_float * TG_MAX_ROUNDS),
                 ("join_pairs", ctypes.c_double * TG_MAX_ROUNDS), ("join_vectors", ctypes.c_double * TG_MAX_ROUNDS),
                 ("undefined_rows", ctypes.c_int64)]
@@ -39,7 +40,7 @@ class Stats(ctypes.Structure):
         return dict(rounds_phase1=self.rounds_phase1, rounds_phase2=self.rounds_phase2,
                     updates=list(self.updates[:r]), ms_norms=self.ms_norms, ms_init=self.ms_init,
                     ms_finalize=self.ms_finalize, ms_sample=list(self.ms_sample[:r]), ms_join=list(self.ms_join[:r]),
-                    ms_update=list(self.ms_update[:r]), join_pairs=list(self.join_pairs[:r]),
+                    ms_adjacency=list(self.ms_adjacency[:r]), ms_update=list(self.ms_update[:r]), join_pairs=list(self.join_pairs[:r]),
                     join_vectors=list(self.join_vectors[:r]), undefined_rows=self.undefined_rows)
 
 
