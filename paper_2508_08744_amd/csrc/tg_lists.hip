@@ -663,6 +663,7 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
         __builtin_amdgcn_wave_barrier();
         for (int q0 = 0; q0 < nq; q0 += 64) {
             u64 ck = q0 + lane < nq ? queue[wave][q0 + lane] : TG_EMPTY_KEY;
+            if (q0 > 0 && !(ck < tg_shfl64(L, k - 1))) ck = TG_EMPTY_KEY;      // cannot precede the last entry of the list as merged so far
             const u32 cid = tg_key_id(ck);
             const bool cand = ck != TG_EMPTY_KEY && cid != (u32)v;
             const bool known = lds_set_insert(seen, set_mask, set_shift, cid, cand);
@@ -671,6 +672,24 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void update_kernel(TgGraph g, int
             ck = tg_wave_sort(ck);
             L = tg_wave_merge_low(L, ck);
             if (lane >= k) L = TG_EMPTY_KEY;
+            if (q0 == 0 && nq > 128) {
+                // More than two batches (the first parts of the early rounds): the first merge has tightened the list, and most of
+                // what waits cannot precede its last entry any more.  What still can is closed up, usually into one batch.
+                const u64 last = tg_shfl64(L, k - 1);
+                int wr = 64;
+                for (int r0 = 64; r0 < nq; r0 += 64) {
+                    const u64 c = r0 + lane < nq ? queue[wave][r0 + lane] : TG_EMPTY_KEY;
+                    const bool keep = c < last;
+                    const u64 mk = __ballot(keep);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    if (keep) queue[wave][wr + __popcll(mk & lt)] = c;       // (never ahead of what has been read)
+                    wr += __popcll(mk);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                nq = wr;
+            }
         }
         if (REMEASURE) {
             const bool arrival = lane < k && (L & 2ull) != 0ull;
