@@ -84,7 +84,7 @@ __device__ inline u32 t8_hash(u32 id)
 #define ADJ_UNROLL 8
 struct AdjShared {
     int ids[TG_BLOCK_COLS + 4];
-    u32 adjw[TG_BLOCK_COLS * 4];
+    u32 adjw[(TG_BLOCK_COLS + 1) * 4];      // the last row takes what lanes past the end of the block look up
     unsigned char T8[T8_SLOTS];
 };
 template <bool VEC>
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64 * ADJ_WAVES) void adj_kernel(TgGraph g, TgSample
                 } else {
                     lid[u][0] = *src;
                 }
-                mm[u] = ok ? m : -1;
+                mm[u] = ok ? m : TG_BLOCK_COLS;
             }
 #pragma unroll
             for (int u = 0; u < ADJ_UNROLL; ++u) {
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * ADJ_WAVES) void adj_kernel(TgGraph g, TgSample
                 for (int w = 0; w < W; ++w) {
                     const u32 cid = lid[u][w] & TG_ID_MASK;
                     u32 s = t8_hash(cid);
-                    u32 e = mm[u] >= 0 ? (u32)sh.T8[s] : T8_FREE;
+                    u32 e = (u32)sh.T8[s];
                     while (e != T8_FREE) {               // ends at a free place: the table is never full
                         if ((u32)sh.ids[e] == cid) {
                             atomicOr(&sh.adjw[mm[u] * 4 + (int)(e >> 5)], 1u << (e & 31u));
