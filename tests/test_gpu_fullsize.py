@@ -141,3 +141,53 @@ def test_reverse_samples_over_several_launches_of_the_bucket_step():
     oi, od, of = o.graph()
     assert (gi.cpu().numpy() == oi).all() and (gd.cpu().numpy().astype(np.float64) == od).all() and (gf.cpu().numpy() == of).all()
     b.close()
+
+
+def test_c2_full_size_blocks_and_adjacency():
+    # The sampler and the adjacency kernel at the benchmark's size and parameters, on lists that two rounds have shaped:
+    # the blocks of sampled anchors against the oracle's (which samples the same imported lists), and the adjacency words
+    # of those blocks against the lists themselves.
+    cfg = inputs.CONFIGS["C2"]
+    n, k = cfg["n"], cfg["k"]
+    X = inputs.make("C2")
+    Xg = torch.from_numpy(X).cuda()
+    import bench
+    prm = bench.bench_params(k)
+    b = knn.Builder(Xg, prm)
+    b.init()
+    b.phase1_round(False)
+    b.phase1_round(False)
+    gi, gd, gf = b.graph()
+    b.close()
+    b = knn.Builder(Xg, prm)                      # a fresh build takes the lists over: both sides sample as in a first round
+    b.set_graph(gi, gd, gf)
+    ids_h = gi.cpu().numpy()
+    o = oracle.NNDescent(X, k, **oracle.device_model(prm))
+    o.set_graph(ids_h, gd.cpu().numpy().astype(np.float64), gf.cpu().numpy())
+    blk, sizes = b.sample_blocks()
+    adj = b.block_adjacency()
+    o.phase1_sample()
+    rows = np.concatenate([inputs.sample_rows(n, 400, seed=6), np.arange(n - 50, n)])
+    rg = torch.from_numpy(rows).cuda()
+    bl, sz, ad = blk[rg].cpu().numpy(), sizes[rg].cpu().numpy(), adj[rg].cpu().numpy().view(np.uint32)
+    del blk, sizes, adj
+    large = 0
+    for i, v in enumerate(rows):
+        N, O = o.block(int(v))
+        nT = len(N) + len(O)
+        assert sz[i, 0] == len(N) and sz[i, 1] == len(O), v
+        assert (bl[i, :len(N)] == N).all() and (bl[i, len(N):nT] == O).all() and (bl[i, nT:] == -1).all(), v
+        if len(N) == 0 or nT < 2:
+            assert not ad[i].any()
+            continue
+        large += nT > 64
+        pos = {int(x): p for p, x in enumerate(bl[i, :nT])}
+        want = np.zeros((128, 4), dtype=np.uint32)
+        for p in range(nT):
+            for c in ids_h[bl[i, p]]:
+                x = pos.get(int(c))
+                if x is not None:
+                    want[p, x >> 5] |= np.uint32(1 << (x & 31))
+        assert (ad[i] == want).all(), v
+    assert large > 0          # (blocks of both kinds of kernel are among the sampled ones)
+    b.close()
