@@ -23,8 +23,8 @@
  * The reference mode of O-NND is the plain method: every pair a block
  * evaluates is offered to both of its nodes, and a node's candidate list is
  * unbounded (retain = 0, C = 0, parts = 1).  The remaining parameters
- * (retain, tile, ng_row, ng_col, C with slot_of(), parts) do not belong to the
- * method: they model a bounded hand-over of candidates from the blocks to
+ * (retain, tile, ng_row, ng_col, C with slot_of(), exclude_listed, parts) do
+ * not belong to the method: they model a bounded hand-over of candidates from the blocks to
  * the lists, such as a device with little fast memory per block needs
  * (section 4.2 keeps one closest node per node and warp sub-tile for the same
  * reason).  They are here so that such a build can be followed step by step;
