@@ -68,7 +68,11 @@ typedef enum { TG_METRIC_L2 = 0, TG_METRIC_IP = 1, TG_METRIC_COSINE = 2 } tg_met
  *            entries; 0 = run exactly it1 + it2 rounds (never synchronises with the host)
  *   seed     seed of every random decision (initial lists, reverse sampling, slots)
  *   finalize 1: recompute the reported distances directly from the vectors and
- *            re-sort each list before writing the outputs
+ *            re-sort each list before writing the outputs.  Where X holds whole numbers with
+ *            2 d max|x|^2 <= 2^24 (byte-valued features of up to 129 dimensions, say; found while
+ *            the norms are formed) and the distance is not the cosine, every fp32 sum the rounds
+ *            form is exact, the lists hold the directly computed distances already, and nothing is
+ *            recomputed
  *   screen   1: a phase-2 round first bounds every candidate's distance from below on an
  *            8-bit copy of the vectors (n x (d + 47) bytes of workspace) and measures in fp32
  *            only those that may still enter the list; the bound is rigorous, so the graph is

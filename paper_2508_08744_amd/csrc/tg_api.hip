@@ -134,7 +134,7 @@ static void carve(tg_knn_handle* h, const float* X, int64_t n, int32_t d, void* 
     h->g.kth = c.take<u64>(n);
     h->g.ldq = (d + 15) & ~15;
     h->xq = p.screen ? c.take<uint8_t>((size_t)n * h->g.ldq) : nullptr;
-    h->xqm = p.screen ? c.take<float>(64) : nullptr;
+    h->xqm = c.take<float>(64);          // also where the norms leave the range of the values
     h->g.Xq = h->xq;
     h->g.Xqm = h->xqm;
     h->d_screen_on = c.take<u32>(64);
@@ -373,7 +373,8 @@ extern "C" int tg_knn_finalize(tg_knn_handle* h, int32_t* out_ids, float* out_di
     if (!h->lists_ready) return fail(TG_ERR_INVALID_ARG, "no lists yet: call tg_knn_init or tg_knn_import first");
     if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
     int sp = begin_span(h, SPAN_FINALIZE, 0);
-    tg_launch_finalize(h->g, h->p.finalize, out_ids, out_dist, h->stream);
+    ensure_norms(h);
+    tg_launch_finalize(h->g, h->p.finalize, reinterpret_cast<const uint32_t*>(h->xqm), out_ids, out_dist, h->stream);
     end_span(h, sp);
     return launch_status("finalize");
 }

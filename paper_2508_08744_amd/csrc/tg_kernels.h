@@ -14,6 +14,7 @@
 // of lanes) of its own are therefore launched once per chunk of TG_LAUNCH_NODES nodes and told
 // where their chunk begins; the chunk size is a multiple of every such group size.
 #define TG_LAUNCH_NODES (1ll << 24)
+#define TG_RANGE_NONINT 8        // word of the range buffer: set when a value of X is not a whole number
 #define TG_REV_BUCKETS 8192      // buckets of reverse edges one launch counts in LDS
 #define TG_REV_MAX_SHIFT 11      // a bucket holds at most 2048 targets
 #define TG_REV_MAX_W (1 << TG_REV_MAX_SHIFT)
@@ -100,7 +101,8 @@ void tg_launch_update(const TgGraph& g, const TgSample& sm, const TgCand& c, uns
 void tg_launch_mark_all_fresh(const TgGraph& g, hipStream_t s);
 void tg_launch_phase2(const TgGraph& g, int m, unsigned long long* updates, unsigned long long* stat_bins,
                       uint32_t* screen_on /* device flag, used when g.Xq is set */, hipStream_t s);
-void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s);
+// range: the words tg_launch_norms filled, or null: where they show whole numbers whose fp32 sums are all exact, nothing is recomputed
+void tg_launch_finalize(const TgGraph& g, int recompute, const uint32_t* range, int32_t* out_ids, float* out_dist, hipStream_t s);
 void tg_launch_export(const TgGraph& g, int32_t* ids, float* dist, uint8_t* fresh, hipStream_t s);
 void tg_launch_import(const TgGraph& g, const int32_t* ids, const float* dist, const uint8_t* fresh, hipStream_t s);
 void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hipStream_t s);

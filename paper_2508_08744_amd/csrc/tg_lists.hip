@@ -61,8 +61,9 @@ void tg_launch_pad_rows(const float* X, int64_t n, int d, float* Xp, int ld, hip
 
 // ---------------------------------------------------------------------------------------
 // squared norms: 16 lanes per row, float4 loads; workgroups walk the rows with the stride of
-// the grid.  With `range` (two words, ordered bits) the smallest and the largest value of X are
-// found on the way, for the grid of the 8-bit codes of phase 2.  With `undefined`, rows that have no
+// the grid.  With `range` (words 0 and 1, ordered bits) the smallest and the largest value of X are
+// found on the way, for the grid of the 8-bit codes of phase 2, and word TG_RANGE_NONINT is set when a
+// value is not a whole number (finalize_kernel asks).  With `undefined`, rows that have no
 // defined distance are counted there: a squared norm that is not a finite number (an infinite or
 // undefined value in the row, or an overflow), and a zero norm where the reciprocal is asked for.
 // ---------------------------------------------------------------------------------------
@@ -73,6 +74,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
     __shared__ u32 s_lo[16], s_hi[16];
     const int sub = threadIdx.x & 15;
     float lo = __builtin_inff(), hi = -__builtin_inff();
+    bool nonint = false;
     for (int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4); row < n; row += (int64_t)gridDim.x * 16) {
         const float* x = X + row * (int64_t)ld;
         float acc = 0.0f;
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
                 const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (c + i < d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); }       // padding columns are no values
+                    if (c + i < d) { lo = fminf(lo, e[i]); hi = fmaxf(hi, e[i]); nonint |= !(e[i] == rintf(e[i])); }       // padding columns are no values
             }
         }
         acc += __shfl_xor(acc, 1);
@@ -110,6 +112,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const float* __restrict__ X,
         atomicMin(range + 0, a);
         atomicMax(range + 1, b);
     }
+    if (__ballot(nonint) != 0ull && tg_lane() == 0 && range[TG_RANGE_NONINT] == 0u) range[TG_RANGE_NONINT] = 1u;
 }
 void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hipStream_t s)
 {
@@ -117,6 +120,7 @@ void tg_launch_norms(const TgGraph& g, uint32_t* range, uint32_t* undefined, hip
     if (range) {
         tg_launch_fill_u32(range + 0, 1, 0xFF800000u, s);      // ordered +infinity: the smallest value so far
         tg_launch_fill_u32(range + 1, 1, 0x007FFFFFu, s);      // ordered -infinity
+        tg_launch_fill_u32(range + TG_RANGE_NONINT, 1, 0u, s);
     }
     const int64_t wgs = (g.n + 15) / 16;
     hipLaunchKernelGGL(norms_kernel, dim3((unsigned)(wgs < 2048 ? wgs : 2048)), dim3(256), 0, s, g.X, g.n, g.d, g.ld, g.nrm,
@@ -956,7 +960,8 @@ void tg_launch_phase2(const TgGraph& g, int m, u64* updates, u64* stat_bins, u32
 // Output: optionally recompute every kept distance directly from the vectors (the join
 // ranks with the norm-plus-Gram form, which loses digits to cancellation) and re-sort.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, int recompute, int32_t* out_ids, float* out_dist, int64_t v0)
+__global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, int recompute, const u32* __restrict__ range, int32_t* out_ids,
+                                                                    float* out_dist, int64_t v0)
 {
     extern __shared__ float smem[];
     const int wave = threadIdx.x >> 6, lane = tg_lane();
@@ -970,6 +975,12 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, i
     if (lane < k) {
         id = (int)(g.gid[v * k + lane] & TG_ID_MASK);
         dist = g.gdist[v * k + lane];
+    }
+    if (recompute && range && g.metric != 2 && range[TG_RANGE_NONINT] == 0u) {
+        // Whole numbers small enough that every fp32 sum of the norms, the inner products and their combination is exact
+        // (2 d max|x|^2 <= 2^24): the distances in the lists are the directly computed ones already, bit for bit.
+        const float m = fmaxf(fabsf(tg_unord(range[0])), fabsf(tg_unord(range[1])));
+        if (2.0f * (float)g.d * m * m <= 16777216.0f) recompute = 0;
     }
     if (recompute) {
         stage_row(g, v, xs);
@@ -985,12 +996,12 @@ __global__ __launch_bounds__(64 * LISTS_WAVES) void finalize_kernel(TgGraph g, i
         if (out_dist) out_dist[v * k + lane] = dist;
     }
 }
-void tg_launch_finalize(const TgGraph& g, int recompute, int32_t* out_ids, float* out_dist, hipStream_t s)
+void tg_launch_finalize(const TgGraph& g, int recompute, const uint32_t* range, int32_t* out_ids, float* out_dist, hipStream_t s)
 {
     size_t shm = (size_t)LISTS_WAVES * g.ld * sizeof(float) + LISTS_WAVES * 128 * sizeof(u32);
     tg_for_node_chunks(g.n, [&](int64_t v0, int64_t cnt) {
         hipLaunchKernelGGL(finalize_kernel, dim3((unsigned)((cnt + LISTS_WAVES - 1) / LISTS_WAVES)), dim3(64 * LISTS_WAVES), shm, s, g,
-                           recompute, out_ids, out_dist, v0);
+                           recompute, range, out_ids, out_dist, v0);
     });
 }
 
