@@ -547,16 +547,24 @@ extern "C" int tg_knn_build(const float* X, int64_t n, int32_t d, int32_t k, int
     if (rc != TG_OK) return rc;
     if (!X) return fail(TG_ERR_INVALID_ARG, "X is NULL");
     if (!out_ids) return fail(TG_ERR_INVALID_ARG, "out_ids is NULL");
-    // an X that is not 16-byte aligned is copied: room for that on top of what the size query says
-    size_t bytes = tg_knn_workspace_bytes(n, d, &p);
-    if ((d & 3) == 0 && (reinterpret_cast<uintptr_t>(X) & 15)) bytes += (size_t)n * d * sizeof(float) + 256;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    // the workspace lives in stream order: taken before the first kernel, given back behind the last one, no wait
+    // The workspace lives in stream order: taken before the first kernel, given back behind the last one, no wait.
+    // Where the defaults' workspace cannot be had (1e8 points), the two parameters that only trade memory for recall per
+    // round step down until it can: rounds in 4, then 8 parts, then 128, 64, 32 slots.
+    static const int steps[][2] = {{0, 0}, {4, 0}, {8, 0}, {8, 128}, {8, 64}, {8, 32}};
     void* ws = nullptr;
-    if (hipMallocAsync(&ws, bytes, s) != hipSuccess) {
+    size_t bytes = 0;
+    for (const auto& st : steps) {
+        if (st[0]) p.parts = st[0];
+        if (st[1]) p.C = st[1];
+        // an X that is not 16-byte aligned is copied: room for that on top of what the size query says
+        bytes = tg_knn_workspace_bytes(n, d, &p);
+        if ((d & 3) == 0 && (reinterpret_cast<uintptr_t>(X) & 15)) bytes += (size_t)n * d * sizeof(float) + 256;
+        if (hipMallocAsync(&ws, bytes, s) == hipSuccess) break;
         (void)hipGetLastError();
-        return fail(TG_ERR_OUT_OF_MEMORY, "workspace of %zu bytes could not be allocated", bytes);
+        ws = nullptr;
     }
+    if (!ws) return fail(TG_ERR_OUT_OF_MEMORY, "workspace of %zu bytes could not be allocated", bytes);
     rc = tg_knn_build_ex(X, n, d, &p, ws, bytes, out_ids, out_dist, nullptr, stream);
     const hipError_t e = hipFreeAsync(ws, s);
     if (rc == TG_OK && e != hipSuccess) return fail(TG_ERR_HIP, "releasing the workspace failed: %s", hipGetErrorString(e));
