@@ -146,7 +146,7 @@ size_t tg_knn_workspace_bytes(int64_t n, int32_t d, const tg_knn_params* p);
  * int32.  out_dist: device, n x k fp32, may be NULL.  Takes and returns its own workspace in
  * stream order (hipMallocAsync / hipFreeAsync on `stream`: no wait; with iters > 0 the call
  * only enqueues work).  Runs with tg_knn_default_params(k, iters); where the device cannot give the
- * workspace of those (about 3.5 KB per point at k = 32), parts and C step down (parts 4, 8, then C 128,
+ * workspace of those (about 3.9 KB per point at k = 32), parts and C step down (parts 4, 8, then C 128,
  * 64, 32) until it can.
  * iters > 0: exactly that many rounds, split as tg_knn_default_params says; iters <= 0: up to
  * 16 rounds with early stop.  Valid iff 1 <= k <= 64, k < n < 2^30, 1 <= d <= 4096.
